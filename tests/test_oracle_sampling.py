@@ -1,0 +1,137 @@
+"""Pins of the oracle's sampler: Table 1, Eq. 3 and Algorithm 1's slot layout
+(Sec. 3.2-3.3), against hand-worked vectors, band edges and invariants."""
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from conftest import golden_lines
+from helpers import random_csr
+
+
+def _vectors():
+    out = []
+    for ln in golden_lines("table1_eq3_vectors.txt"):
+        a, b, c = [p.split() for p in ln.split("|")]
+        out.append((int(a[0]), int(a[1]), int(b[0]), int(b[1]), [int(x) for x in c]))
+    return out
+
+
+@pytest.mark.parametrize("W,nnz,N,cnt,starts", _vectors())
+def test_hand_worked_vectors(oracle, W, nnz, N, cnt, starts):
+    assert oracle.strategy(nnz, W) == (N, cnt)
+    assert [oracle.hash_start(i, nnz, N) for i in range(cnt)] == starts
+    assert oracle.row_slots(nnz, W) == N * cnt
+
+
+def test_band_edges(oracle):
+    for ln in golden_lines("table1_band_edges.txt"):
+        W, nnz, N, cnt = map(int, ln.split())
+        assert oracle.strategy(nnz, W) == (N, cnt), ln
+
+
+def test_slot_layout_golden(oracle):
+    for ln in golden_lines("slot_layout.txt"):
+        a, b = ln.split("|")
+        W, nnz = map(int, a.split())
+        offs = [int(x) for x in b.split()]
+        # one row whose element e has column e and value e+0.5: slots reveal offsets
+        rowptr = np.array([0, nnz], dtype=np.int64)
+        col = np.arange(nnz, dtype=np.int32)
+        val = (np.arange(nnz) + 0.5).astype(np.float32)
+        s_rowptr, s_col, s_val, s_eid = oracle.sample_build(rowptr, col, val, W, seed=0)
+        assert s_rowptr.tolist() == [0, len(offs)]
+        assert s_col.tolist() == offs
+        assert s_eid.tolist() == offs
+        assert s_val.tolist() == [o + 0.5 for o in offs]
+
+
+def test_bands_by_exact_rational_ratio(oracle):
+    """Table 1 evaluated with exact rationals R = row_nnz / W (no integer
+    division, no floats) over a dense sweep, including non-power-of-two W."""
+    for W in [1, 2, 3, 4, 7, 8, 16, 31, 32, 48, 64, 100, 128, 256, 1000, 1024]:
+        probe = set(range(0, 70))
+        for k in (1, 2, 36, 54):
+            probe.update(range(max(0, k * W - 2), k * W + 3))
+        probe.update([100 * W, 12345])
+        for nnz in sorted(probe):
+            R = Fraction(nnz, W)
+            if R <= 1:
+                exp = (nnz, 1)
+            else:
+                c = 4 if R <= 2 else 8 if R <= 36 else 16 if R <= 54 else 32
+                exp = (max(1, W // c), min(c, W))
+            assert oracle.strategy(nnz, W) == exp, (W, nnz)
+
+
+def test_power_of_two_width_fills_exactly(oracle):
+    for W in [1, 2, 4, 8, 16, 32, 64, 128, 256, 512, 1024]:
+        for nnz in [0, 1, W - 1, W, W + 1, 2 * W, 2 * W + 1, 36 * W + 1, 54 * W + 1, 10 ** 6]:
+            if nnz < 0:
+                continue
+            assert oracle.row_slots(nnz, W) == min(nnz, W)
+
+
+def test_hash_range_and_seed_zero(oracle):
+    rng = np.random.default_rng(0)
+    for _ in range(300):
+        W = int(rng.choice([4, 16, 32, 64, 256]))
+        nnz = int(rng.integers(W + 1, 200 * W))
+        N, cnt = oracle.strategy(nnz, W)
+        starts = [oracle.hash_start(i, nnz, N) for i in range(cnt)]
+        assert starts[0] == 0
+        assert all(0 <= s <= nnz - N for s in starts)
+        assert starts == [(i * 1429) % (nnz - N + 1) for i in range(cnt)]
+    assert oracle.row_offset(0, 12345) == 0
+
+
+def test_row_offset_definition(oracle):
+    """The seed extension: s_r = low 32 bits of seed*(2r+1)*2654435761."""
+    for seed, r in [(1, 0), (1, 1), (7, 123456), (2 ** 63 + 5, 2 ** 31), (0xDEADBEEF, 99)]:
+        exp = (seed * (2 * r + 1) * 2654435761) & 0xFFFFFFFF
+        assert oracle.row_offset(seed, r) == exp
+
+
+@pytest.mark.parametrize("W", [1, 4, 16, 32, 48, 64, 256])
+@pytest.mark.parametrize("seed", [0, 1234567])
+def test_plan_invariants(oracle, W, seed):
+    rng = np.random.default_rng(W + seed)
+    n = 400
+    deg = np.concatenate([rng.integers(0, 3 * W + 2, size=n - 6),
+                          [0, W, W + 1, 36 * W + 1, 54 * W + 1, 60 * W]])
+    rng.shuffle(deg)
+    rowptr, col, val = random_csr(n, 70 * W + 50, deg, rng)
+    s_rowptr, s_col, s_val, s_eid = oracle.sample_build(rowptr, col, val, W, seed=seed)
+    assert s_rowptr[0] == 0 and s_rowptr[-1] == s_col.size
+    for r in range(n):
+        nnz = int(deg[r])
+        N, cnt = oracle.strategy(nnz, W)
+        k0, k1 = int(s_rowptr[r]), int(s_rowptr[r + 1])
+        assert k1 - k0 == N * cnt
+        if W & (W - 1) == 0:
+            assert k1 - k0 == min(nnz, W)
+        e = s_eid[k0:k1]
+        assert np.all((e >= rowptr[r]) & (e < rowptr[r + 1]))
+        assert np.array_equal(s_col[k0:k1], col[e])
+        assert np.array_equal(s_val[k0:k1].view(np.uint32), val[e].view(np.uint32))
+        if nnz <= W:
+            assert np.array_equal(e, np.arange(rowptr[r], rowptr[r + 1]))
+        else:
+            grid = e.reshape(N, cnt)                  # slot i + j*cnt -> [j, i]
+            assert np.all(np.diff(grid, axis=0) == 1)  # N consecutive elements per sample
+            assert np.all(grid[0] - rowptr[r] <= nnz - N)
+            s_r = oracle.row_offset(seed, r)
+            exp = [((i + s_r) * 1429) % (nnz - N + 1) for i in range(cnt)]
+            assert (grid[0] - rowptr[r]).tolist() == exp
+            if seed == 0:
+                assert grid[0, 0] == rowptr[r]
+
+
+def test_exact_path_is_identity(oracle):
+    rng = np.random.default_rng(5)
+    deg = rng.integers(0, 90, size=64)
+    rowptr, col, val = random_csr(64, 200, deg, rng)
+    s_rowptr, s_col, s_val, s_eid = oracle.sample_build(rowptr, col, val, 0)
+    assert np.array_equal(s_rowptr, rowptr)
+    assert np.array_equal(s_col, col)
+    assert np.array_equal(s_eid, np.arange(col.size))
