@@ -1,0 +1,265 @@
+#!/usr/bin/env python3
+"""Benchmark of the AES-SpMM hot path on one MI355X.
+
+One step = one pass of the whole hot path over one synthetic graph already
+resident in HBM:
+    aes_sample_build -> aes_spmm_f32 -> aes_quantize_features -> aes_spmm_q8
+The default workload is the largest graph ("products_like": 2.45 M nodes,
+~120 M edges, F = 128, W = 64, int8 features with per-row scales).
+
+Prints ONE JSON line.  `value` is the step's algorithmic bytes (no-reuse model:
+8 B per sampled slot + one feature row per slot + the output, see
+`algorithmic_bytes`) divided by the step time.  `roofline` is the same for the
+dominant kernel (the fp32 SpMM) from HIP-event times taken inside the timed
+region; `cpu_baseline` is the CPU oracle timed on a bounded sample of the same
+workload on this machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+
+
+def algorithmic_bytes(n_rows, S, F, elem_bytes, per_row_scale):
+    """Bytes one multiply over a plan must move if nothing is reused:
+    (col, val) per slot, one feature row per slot, Y once, s_rowptr + row_perm."""
+    b = 8 * S + S * F * elem_bytes + 4 * n_rows * F + 8 * n_rows + 4 * n_rows
+    if per_row_scale:
+        b += 4 * S
+    return b
+
+
+def build_bytes(n_rows, S):
+    """rowptr in, sampled (col, val) in and out, s_rowptr and row_perm out."""
+    return 8 * (n_rows + 1) + 8 * S + 8 * S + 8 * (n_rows + 1) + 4 * n_rows
+
+
+def quantize_bytes(n, F, groups):
+    return 4 * n * F + n * F + 8 * groups
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="products_like")
+    ap.add_argument("--width", type=int, default=0, help="sampling width W (default: the workload's first)")
+    ap.add_argument("--cpu-rows", type=int, default=200_000, help="rows in the CPU oracle's sample (0: skip)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2503_18427_amd as aes
+    from workloads import configs
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    aes.library()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    t_gen = time.time()
+    d = configs.make(args.workload, dev)
+    w = d["workload"]
+    W = args.width or w.widths[0]
+    n, F, nnz = d["n"], d["F"], d["nnz"]
+    rowptr, colidx, val, X = d["rowptr"], d["colidx"], d["val"], d["X"]
+    torch.cuda.synchronize()
+    t_gen = time.time() - t_gen
+
+    scheme, gran = w.q_scheme, w.q_granularity
+    groups = {0: 1, 1: F, 2: n}[gran]
+    plan = aes.aes_sample_build(rowptr, colidx, val, n, W, 0)
+    ws_build = torch.empty(max(aes.aes_sample_workspace_bytes(n), 8), dtype=torch.uint8, device=dev)
+    ws_q = torch.empty(max(aes.aes_quantize_workspace_bytes(n, F, gran), 8), dtype=torch.uint8, device=dev)
+    Y = torch.empty((n, F), dtype=torch.float32, device=dev)
+    Yq = torch.empty((n, F), dtype=torch.float32, device=dev)
+    qbuf = (torch.empty((n, F), dtype=torch.int8 if scheme == 1 else torch.uint8, device=dev),
+            torch.empty(groups, dtype=torch.float32, device=dev), torch.empty(groups, dtype=torch.float32, device=dev))
+    torch.cuda.synchronize()
+    S = int(plan.s_rowptr[-1].item())
+
+    legs = ["sample_build", "spmm_f32", "quantize", "spmm_q8"]
+    leg_bytes = {
+        "sample_build": build_bytes(n, S),
+        "spmm_f32": algorithmic_bytes(n, S, F, 4, False),
+        "quantize": quantize_bytes(n, F, groups),
+        "spmm_q8": algorithmic_bytes(n, S, F, 1, gran == 2),
+    }
+
+    def step(events=None):
+        marks = []
+
+        def mark():
+            if events is not None:
+                e = torch.cuda.Event(enable_timing=True)
+                e.record()
+                marks.append(e)
+
+        mark()
+        aes.aes_sample_build(rowptr, colidx, val, n, W, 0, out=plan, workspace=ws_build)
+        mark()
+        aes.aes_spmm_f32(plan, X, Y)
+        mark()
+        aes.aes_quantize_features(X, scheme, gran, out=qbuf, workspace=ws_q)
+        mark()
+        aes.aes_spmm_q8(plan, qbuf[0], scheme, gran, qbuf[1], qbuf[2], Yq)
+        mark()
+        if events is not None:
+            events.append(marks)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(events)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    leg_ms = {k: 0.0 for k in legs}
+    for marks in events:
+        for i, k in enumerate(legs):
+            leg_ms[k] += marks[i].elapsed_time(marks[i + 1])
+    leg_ms = {k: v / args.steps for k, v in leg_ms.items()}
+    total_bytes = sum(leg_bytes.values())
+    value = total_bytes / (ms_per_step * 1e-3) / 1e9
+    leg_gbps = {k: leg_bytes[k] / (leg_ms[k] * 1e-3) / 1e9 for k in legs}
+
+    traffic = None
+    if os.path.exists(TRAFFIC_FILE):
+        try:
+            with open(TRAFFIC_FILE) as f:
+                rec = json.load(f).get(f"{args.workload}:W{W}:spmm_f32")
+            traffic = rec["hbm_bytes"] if rec else None
+        except (OSError, ValueError, KeyError):
+            traffic = None
+    roofline = {
+        "kernel": "spmm_rows_kernel (aes_spmm_f32)",
+        "bound": "hbm",
+        "achieved": leg_gbps["spmm_f32"],
+        "peak": HBM_PEAK_GBPS,
+        "unit": "GB/s",
+        "frac": leg_gbps["spmm_f32"] / HBM_PEAK_GBPS,
+        "traffic": traffic,
+        "algorithmic_bytes": leg_bytes["spmm_f32"],
+        "avg_ms": leg_ms["spmm_f32"],
+    }
+
+    out = {
+        "metric": "effective SpMM GB/s over the hot path (sample build + fp32 SpMM + int8 quantise + int8 SpMM; "
+                  "algorithmic bytes / time)",
+        "value": value,
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": args.workload, "n_nodes": n, "nnz": nnz, "F": F, "W": W, "slots": S,
+                   "int8": {"scheme": "symmetric_rne_i8" if scheme == 1 else "affine_floor_u8",
+                            "granularity": ["tensor", "column", "row"][gran]},
+                   "generate_s": round(t_gen, 2)},
+        "legs": {k: {"ms": leg_ms[k], "GBps": leg_gbps[k], "bytes": leg_bytes[k],
+                     "frac_hbm_peak": leg_gbps[k] / HBM_PEAK_GBPS} for k in legs},
+        "gflops": {"spmm_f32": 2.0 * S * F / (leg_ms["spmm_f32"] * 1e-3) / 1e9,
+                   "spmm_q8": 2.0 * S * F / (leg_ms["spmm_q8"] * 1e-3) / 1e9},
+        "roofline": roofline,
+    }
+
+    if args.cpu_rows > 0:
+        out["cpu_baseline"], out["max_rel_err"] = cpu_baseline(
+            d, plan, Y, Yq, qbuf, W, scheme, gran, min(args.cpu_rows, n), leg_bytes, total_bytes, S)
+    print(json.dumps(out))
+    return 0
+
+
+def cpu_baseline(d, plan, Y, Yq, qbuf, W, scheme, gran, n_rows_sample, leg_bytes, total_bytes, S):
+    """The CPU oracle on a bounded sample of the same workload, on this machine's host
+    cores; also the GPU-vs-oracle error on the sampled rows."""
+    import numpy as np
+    import torch
+
+    import oracle as orc
+
+    n, F = d["n"], d["F"]
+    rowptr, colidx, val = (d[k].cpu().numpy() for k in ("rowptr", "colidx", "val"))
+    X = d["X"].cpu().numpy()
+    rng = np.random.default_rng(0)
+    rows = np.sort(rng.choice(n, size=n_rows_sample, replace=False)).astype(np.int64)
+
+    t = time.perf_counter()
+    ref = orc.sample_build(rowptr, colidx, val, W, 0, want_eid=False)
+    t_build = time.perf_counter() - t
+    slots_rows = int((ref[0][rows + 1] - ref[0][rows]).sum())
+
+    t = time.perf_counter()
+    Yref, Yabs = orc.spmm_plan(ref[0], ref[1], ref[2], X, rows=rows, want_abs=True)
+    t_f32 = time.perf_counter() - t
+
+    nq = min(n, n_rows_sample)
+    t = time.perf_counter()
+    orc.quantize(X[:nq], scheme, gran)
+    t_quant = time.perf_counter() - t
+
+    Xq_h = qbuf[0].cpu().numpy()
+    sc_h, zr_h = qbuf[1].cpu().numpy(), qbuf[2].cpu().numpy()
+    t = time.perf_counter()
+    Yqref, Yqabs = orc.spmm_q8(ref[0], ref[1], ref[2], Xq_h, scheme, gran, sc_h, zr_h, rows=rows, want_abs=True)
+    t_q8 = time.perf_counter() - t
+
+    groups_q = {0: 1, 1: F, 2: nq}[gran]
+    rate = {
+        "sample_build": leg_bytes["sample_build"] / t_build,
+        "spmm_f32": algorithmic_bytes(n_rows_sample, slots_rows, F, 4, False) / t_f32,
+        "quantize": quantize_bytes(nq, F, groups_q) / t_quant,
+        "spmm_q8": algorithmic_bytes(n_rows_sample, slots_rows, F, 1, gran == 2) / t_q8,
+    }
+    est_step_s = sum(leg_bytes[k] / rate[k] for k in rate)
+
+    rows_t = torch.from_numpy(rows).to(Y.device)
+    Yg = Y[rows_t].cpu().numpy().astype(np.float64)
+    Yqg = Yq[rows_t].cpu().numpy().astype(np.float64)
+    e32 = float(np.max(np.abs(Yg - Yref) / np.where(Yabs > 0, Yabs, 1.0)))
+    e8 = float(np.max(np.abs(Yqg - Yqref) / np.where(Yqabs > 0, Yqabs, 1.0)))
+    plan_ok = bool(np.array_equal(plan.s_rowptr.cpu().numpy(), ref[0])
+                   and np.array_equal(plan.s_col[:S].cpu().numpy(), ref[1]))
+
+    base = {
+        "value": total_bytes / est_step_s / 1e9,
+        "unit": "GB/s",
+        "cores": orc.num_threads(),
+        "kind": "oracle",
+        "sample": f"sample build on all rows; fp32 and int8 SpMM on {n_rows_sample} random rows "
+                  f"({slots_rows} slots; the int8 leg dequantises all of X first, as the oracle defines it); "
+                  f"quantise on the first {nq} rows; each leg's rate scaled to the full step's bytes",
+        "seconds": {"sample_build": t_build, "spmm_f32": t_f32, "quantize": t_quant, "spmm_q8": t_q8},
+        "leg_GBps": {k: v / 1e9 for k, v in rate.items()},
+    }
+    errs = {"fp32_vs_oracle": e32, "int8_vs_oracle_dequantised": e8, "plan_bit_exact": plan_ok,
+            "rows_checked": n_rows_sample}
+    return base, errs
+
+
+if __name__ == "__main__":
+    sys.exit(main())

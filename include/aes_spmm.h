@@ -1,0 +1,211 @@
+/*
+ * aes_spmm.h - C ABI of the MI355X (gfx950) adaptive-edge-sampling SpMM library.
+ *
+ * The library computes Y = A_s * X, where A_s is the CSR matrix A after the
+ * per-row adaptive edge sampling of the AES-SpMM paper (Sec. 3.2 Algorithm 1,
+ * Sec. 3.3 Table 1 and Eq. 3), and X is a dense feature matrix in float32 or in
+ * 8-bit quantised form (Sec. 2.3 Eq. 1-2) that is dequantised while it is
+ * gathered.
+ *
+ * Conventions for every entry point
+ *   - Pointers marked [dev] are DEVICE pointers on the current HIP device;
+ *     [host] pointers are ordinary host memory.  The library never allocates,
+ *     frees or keeps device memory: all buffers, workspaces included, are owned
+ *     by the caller and may be released once the stream has passed the call.
+ *   - Every call is asynchronous: it enqueues kernels on `stream` (a
+ *     hipStream_t passed as void*, NULL = the default stream) and returns.  It
+ *     never synchronises.  Calls on different streams may run concurrently as
+ *     long as their output buffers and workspaces do not overlap.
+ *   - Return value: AES_OK (0) or a negative aes_status.  Argument errors
+ *     (NULL where not allowed, negative sizes, bad enum, too small workspace,
+ *     misaligned leading dimension) are found on the host BEFORE anything is
+ *     launched.  AES_ERR_HIP reports a launch failure.  Contents of CSR arrays
+ *     are not validated on the device: a monotone rowptr with rowptr[0] == 0,
+ *     rowptr[n_rows] == nnz and 0 <= colidx < n_cols is the caller's contract.
+ *   - aes_last_error() returns a static, thread-local, human-readable message
+ *     for the last failing call of the calling thread.
+ *   - Matrices are row-major.  Leading dimensions (ldx, ldq, ldy) are counted
+ *     in elements and must be >= the row length.
+ *   - Within-row order of CSR entries is the caller's; the sampling takes runs
+ *     of consecutive entries, so results depend on it.  Nothing is sorted.
+ */
+#ifndef AES_SPMM_H
+#define AES_SPMM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum aes_status {
+    AES_OK = 0,
+    AES_ERR_INVALID_ARG = -1,  /* NULL pointer, negative size, bad enum, bad ld  */
+    AES_ERR_UNSUPPORTED = -2,  /* size beyond what the kernels index             */
+    AES_ERR_WORKSPACE = -3,    /* workspace NULL or smaller than the query says  */
+    AES_ERR_HIP = -4           /* HIP reported an error at launch                */
+} aes_status;
+
+/* Group that shares one (scale, zero) pair. */
+typedef enum aes_q_granularity {
+    AES_Q_PER_TENSOR = 0,      /* 1 group                                        */
+    AES_Q_PER_COLUMN = 1,      /* F groups, one per feature column               */
+    AES_Q_PER_ROW = 2          /* n groups, one per node                         */
+} aes_q_granularity;
+
+typedef enum aes_q_scheme {
+    /* Sec. 2.3 Eq. 1-2 with b = 8: q = floor((x-x_min)/(x_max-x_min)*255) in
+     * 0..255 (uint8 bit pattern), x_hat = q*scale + zero with
+     * scale = (x_max-x_min)/255, zero = x_min.  x_max == x_min gives q = 0. */
+    AES_Q_AFFINE_FLOOR_U8 = 0,
+    /* Symmetric variant: a = max|x|, scale = a/127 (1 if a == 0),
+     * q = round-half-even(x/scale) clamped to -127..127, x_hat = q*scale. */
+    AES_Q_SYMMETRIC_RNE_I8 = 1
+} aes_q_scheme;
+
+enum { AES_MAX_W = 1 << 20 };
+
+/* Message of the calling thread's last failing call ("" if none). */
+const char *aes_last_error(void);
+
+/* ------------------------------------------------------------------------- */
+/* Sampling: CSR -> sampled plan (Algorithm 1 sampling loop, Table 1, Eq. 3)  */
+
+/*
+ * Upper bound, computable without reading device memory, on the number of
+ * slots aes_sample_build writes: min(nnz, n_rows * W), or nnz when W == 0.
+ * s_col / s_val / s_eid must have at least this many elements.
+ * Returns a negative aes_status on bad arguments.
+ */
+int64_t aes_sample_capacity(int64_t n_rows, int64_t nnz, int32_t W);
+
+/* Bytes of device workspace aes_sample_build needs for n_rows rows. */
+size_t aes_sample_workspace_bytes(int64_t n_rows);
+
+/*
+ * Builds the sampled matrix A_s of CSR matrix A (Sec. 2.2 format).
+ *
+ * For each row r with row_nnz = rowptr[r+1] - rowptr[r]:
+ *   (N, sample_cnt) follow Table 1 from R = row_nnz / W (real ratio), with
+ *   N >= 1 and sample_cnt <= W; rows with row_nnz <= W keep every entry.
+ *   Sample i (0 <= i < sample_cnt) starts at
+ *       start_i = ((i + s_r) * 1429) mod (row_nnz - N + 1)            (Eq. 3)
+ *   and slot i + j*sample_cnt (0 <= j < N) receives entry start_i + j of the
+ *   row (Algorithm 1, sampling loop).  s_r is a per-row offset derived from
+ *   `seed` (low 32 bits of seed*(2r+1)*2654435761); seed == 0 gives s_r == 0,
+ *   i.e. exactly Eq. 3.  Overlapping samples are kept; nothing de-duplicates.
+ *   Row r owns N*sample_cnt slots (== min(row_nnz, W) when W is a power of
+ *   two), stored at s_rowptr[r] .. s_rowptr[r+1]-1.
+ * W == 0 selects "no sampling": the plan is a copy of the CSR matrix.
+ *
+ *   n_rows, n_cols  matrix shape; n_rows >= 0, 0 <= n_cols < 2^31
+ *   nnz             stored entries of A; >= 0
+ *   rowptr   [dev]  n_rows+1 int64
+ *   colidx   [dev]  nnz int32
+ *   val      [dev]  nnz float32
+ *   W               sampling width, 0 or 1..AES_MAX_W (any integer)
+ *   seed            see above
+ *   s_rowptr [dev]  out, n_rows+1 int64
+ *   s_col    [dev]  out, aes_sample_capacity() int32
+ *   s_val    [dev]  out, same count, float32 (bit copies of val)
+ *   s_eid    [dev]  out or NULL, same count, int64: index into colidx/val each
+ *                   slot was taken from
+ *   row_perm [dev]  out or NULL, n_rows int32: the rows ordered by decreasing
+ *                   slot-count class (class = bit length of the slot count),
+ *                   original order kept within a class.  A scheduling hint for
+ *                   the SpMM entry points; requires n_rows < 2^31.
+ *   workspace[dev]  aes_sample_workspace_bytes(n_rows) bytes, 8-byte aligned
+ */
+int aes_sample_build(int64_t n_rows, int64_t n_cols, int64_t nnz,
+                     const int64_t *rowptr, const int32_t *colidx, const float *val,
+                     int32_t W, uint64_t seed,
+                     int64_t *s_rowptr, int32_t *s_col, float *s_val, int64_t *s_eid,
+                     int32_t *row_perm,
+                     void *workspace, size_t workspace_bytes, void *stream);
+
+/* ------------------------------------------------------------------------- */
+/* Multiply stage (Algorithm 1, accumulation loop) on a plan                   */
+
+/*
+ * Y[r, c] = sum_k s_val[k] * X[s_col[k], c] over the slots k of row r, for
+ * 0 <= c < F.  float32 accumulation (fused multiply-add); the summation order
+ * within a row is fixed, so results are bit-reproducible from run to run.
+ * Rows without slots give zero rows.  Every element of Y[0..n_rows, 0..F) is
+ * written; padding columns F..ldy are not touched.
+ *
+ *   n_rows, n_cols  shape of A_s; X has n_cols rows
+ *   s_rowptr/s_col/s_val [dev]  a plan from aes_sample_build (or any CSR with
+ *                   int64 rowptr, int32 colidx, float32 val); s_col / s_val may
+ *                   be NULL only when the plan has no slots at all
+ *   row_perm [dev]  NULL, or a permutation of 0..n_rows-1 giving the order in
+ *                   which rows are handed to wavefronts (from aes_sample_build)
+ *   X        [dev]  n_cols x F float32, leading dimension ldx
+ *   Y        [dev]  out, n_rows x F float32, leading dimension ldy; must not
+ *                   overlap X
+ *   F               1 <= F < 2^24
+ * The fast path needs X and Y 16-byte aligned and F, ldx, ldy multiples of 4;
+ * anything else runs a slower element-wise kernel with the same results.
+ */
+int aes_spmm_f32(int64_t n_rows, int64_t n_cols,
+                 const int64_t *s_rowptr, const int32_t *s_col, const float *s_val,
+                 const int32_t *row_perm,
+                 const float *X, int64_t ldx, int32_t F,
+                 float *Y, int64_t ldy, void *stream);
+
+/* ------------------------------------------------------------------------- */
+/* Feature quantisation (Sec. 2.3 Eq. 1; once per feature matrix)              */
+
+/* Bytes of device workspace aes_quantize_features needs (0 for PER_ROW). */
+size_t aes_quantize_workspace_bytes(int64_t n, int32_t F, int32_t granularity);
+
+/*
+ * Quantises X (n x F float32) to 8 bits per value, see aes_q_scheme.  All
+ * arithmetic is IEEE binary32 with one rounding per operation (subtract,
+ * divide, multiply, floor / divide, round-half-even), so the codes are
+ * bit-reproducible on any conforming implementation.  NaN/Inf inputs give
+ * unspecified codes.
+ *
+ *   X     [dev]  n x F float32, leading dimension ldx
+ *   Xq    [dev]  out, n x F bytes, leading dimension ldq (uint8 bit pattern
+ *                for AFFINE_FLOOR_U8, int8 for SYMMETRIC_RNE_I8)
+ *   scale [dev]  out, 1 | F | n float32 according to granularity
+ *   zero  [dev]  out, same count; may be NULL for SYMMETRIC_RNE_I8 (written
+ *                as 0 otherwise)
+ *   workspace [dev] aes_quantize_workspace_bytes() bytes, 4-byte aligned; may
+ *                be NULL when that is 0
+ */
+int aes_quantize_features(int64_t n, int32_t F, const float *X, int64_t ldx,
+                          int32_t scheme, int32_t granularity,
+                          int8_t *Xq, int64_t ldq, float *scale, float *zero,
+                          void *workspace, size_t workspace_bytes, void *stream);
+
+/* ------------------------------------------------------------------------- */
+/* Multiply stage with the dequantisation of Eq. 2 fused into the gather       */
+
+/*
+ * Y[r, c] = sum_k s_val[k] * x_hat[s_col[k], c], where
+ * x_hat = q*scale_g + zero_g (AFFINE_FLOOR_U8) or q*scale_g (SYMMETRIC_RNE_I8)
+ * and g is the group of element (s_col[k], c).  The group constants are
+ * factored out of the inner loop (per column: applied once per output; per
+ * row: folded into the edge value), so the result equals the dequantise-then-
+ * multiply definition up to float32 rounding, not bit for bit.
+ *
+ *   Xq    [dev]  n_cols x F bytes, leading dimension ldq
+ *   scale, zero [dev]  as written by aes_quantize_features; zero may be NULL
+ *                for SYMMETRIC_RNE_I8
+ * Other arguments as aes_spmm_f32.  The fast path needs Xq 4-byte aligned,
+ * F and ldq multiples of 4, Y 16-byte aligned and ldy a multiple of 4.
+ */
+int aes_spmm_q8(int64_t n_rows, int64_t n_cols,
+                const int64_t *s_rowptr, const int32_t *s_col, const float *s_val,
+                const int32_t *row_perm,
+                const int8_t *Xq, int64_t ldq, int32_t F,
+                int32_t scheme, int32_t granularity,
+                const float *scale, const float *zero,
+                float *Y, int64_t ldy, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AES_SPMM_H */

@@ -1,0 +1,214 @@
+"""ctypes marshalling for libaes_spmm.so (see include/aes_spmm.h for semantics)."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import NamedTuple, Optional
+
+import torch
+
+from . import build as _build
+
+AES_OK, AES_ERR_INVALID_ARG, AES_ERR_UNSUPPORTED, AES_ERR_WORKSPACE, AES_ERR_HIP = 0, -1, -2, -3, -4
+AES_Q_PER_TENSOR, AES_Q_PER_COLUMN, AES_Q_PER_ROW = 0, 1, 2
+AES_Q_AFFINE_FLOOR_U8, AES_Q_SYMMETRIC_RNE_I8 = 0, 1
+
+_i64, _i32, _u64, _vp, _sz = ctypes.c_int64, ctypes.c_int32, ctypes.c_uint64, ctypes.c_void_p, ctypes.c_size_t
+
+# name -> (restype, argtypes); one entry per symbol declared in include/aes_spmm.h
+SIGNATURES = {
+    "aes_last_error": (ctypes.c_char_p, []),
+    "aes_sample_capacity": (_i64, [_i64, _i64, _i32]),
+    "aes_sample_workspace_bytes": (_sz, [_i64]),
+    "aes_sample_build": (ctypes.c_int, [_i64, _i64, _i64, _vp, _vp, _vp, _i32, _u64, _vp, _vp, _vp, _vp, _vp,
+                                        _vp, _sz, _vp]),
+    "aes_spmm_f32": (ctypes.c_int, [_i64, _i64, _vp, _vp, _vp, _vp, _vp, _i64, _i32, _vp, _i64, _vp]),
+    "aes_quantize_workspace_bytes": (_sz, [_i64, _i32, _i32]),
+    "aes_quantize_features": (ctypes.c_int, [_i64, _i32, _vp, _i64, _i32, _i32, _vp, _i64, _vp, _vp, _vp, _sz, _vp]),
+    "aes_spmm_q8": (ctypes.c_int, [_i64, _i64, _vp, _vp, _vp, _vp, _vp, _i64, _i32, _i32, _i32, _vp, _vp, _vp,
+                                   _i64, _vp]),
+}
+
+_lib = None
+
+
+class AesError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"aes status {code}: {message}")
+        self.code = code
+
+
+def library() -> ctypes.CDLL:
+    """The loaded shared library; built first if no build is present."""
+    global _lib
+    if _lib is None:
+        path = _build.lib_path()
+        if not os.path.exists(path):
+            _build.build()
+        lib = ctypes.CDLL(path)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(lib, name)          # AttributeError if a declared symbol is missing
+            fn.restype = res
+            fn.argtypes = args
+        _lib = lib
+    return _lib
+
+
+def aes_last_error() -> str:
+    return library().aes_last_error().decode()
+
+
+def _check(rc: int) -> None:
+    if rc != AES_OK:
+        raise AesError(rc, aes_last_error())
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _dev(t: torch.Tensor, dtype, name: str, dims: int = 1) -> torch.Tensor:
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{name}: a tensor in GPU memory is required")
+    if t.dtype != dtype:
+        raise TypeError(f"{name}: dtype {dtype} required, got {t.dtype}")
+    if t.dim() != dims:
+        raise TypeError(f"{name}: {dims}-d tensor required")
+    if dims == 1 and t.numel() > 1 and t.stride(0) != 1:
+        raise TypeError(f"{name}: must be contiguous")
+    if dims == 2 and t.shape[1] > 1 and t.stride(1) != 1:
+        raise TypeError(f"{name}: rows must be contiguous (unit stride along features)")
+    return t
+
+
+def _ld(t: torch.Tensor) -> int:
+    return int(t.stride(0)) if t.shape[0] > 1 else max(int(t.shape[1]), 1)
+
+
+class Plan(NamedTuple):
+    """The sampled matrix A_s as written by aes_sample_build (device tensors)."""
+    n_rows: int
+    n_cols: int
+    W: int
+    s_rowptr: torch.Tensor            # int64, n_rows + 1
+    s_col: torch.Tensor               # int32, capacity; valid up to s_rowptr[-1]
+    s_val: torch.Tensor               # float32, same
+    s_eid: Optional[torch.Tensor]     # int64 or None
+    row_perm: Optional[torch.Tensor]  # int32, n_rows, or None
+
+
+def aes_sample_capacity(n_rows: int, nnz: int, W: int) -> int:
+    cap = int(library().aes_sample_capacity(n_rows, nnz, W))
+    if cap < 0:
+        raise AesError(cap, aes_last_error())
+    return cap
+
+
+def aes_sample_workspace_bytes(n_rows: int) -> int:
+    return int(library().aes_sample_workspace_bytes(n_rows))
+
+
+def aes_quantize_workspace_bytes(n: int, F: int, granularity: int) -> int:
+    return int(library().aes_quantize_workspace_bytes(n, F, granularity))
+
+
+def aes_sample_build(rowptr, colidx, val, n_cols: int, W: int, seed: int = 0, *, want_eid: bool = False,
+                     want_perm: bool = True, out: Optional[Plan] = None, workspace=None, stream=None) -> Plan:
+    """Build the sampled plan of a CSR matrix.  `out` reuses the buffers of an earlier plan."""
+    rowptr = _dev(rowptr, torch.int64, "rowptr")
+    colidx = _dev(colidx, torch.int32, "colidx")
+    val = _dev(val, torch.float32, "val")
+    n_rows = rowptr.numel() - 1
+    nnz = colidx.numel()
+    if val.numel() != nnz:
+        raise ValueError("colidx and val differ in length")
+    dev = rowptr.device
+    cap = aes_sample_capacity(n_rows, nnz, W)
+    if out is None:
+        out = Plan(n_rows, int(n_cols), int(W),
+                   torch.empty(n_rows + 1, dtype=torch.int64, device=dev),
+                   torch.empty(cap, dtype=torch.int32, device=dev),
+                   torch.empty(cap, dtype=torch.float32, device=dev),
+                   torch.empty(cap, dtype=torch.int64, device=dev) if want_eid else None,
+                   torch.empty(n_rows, dtype=torch.int32, device=dev) if want_perm else None)
+    elif out.s_rowptr.numel() != n_rows + 1 or out.s_col.numel() < cap or out.s_val.numel() < cap:
+        raise ValueError("out: plan buffers too small")
+    need = aes_sample_workspace_bytes(n_rows)
+    if workspace is None:
+        workspace = torch.empty(max(need, 8), dtype=torch.uint8, device=dev)
+    _check(library().aes_sample_build(n_rows, int(n_cols), nnz, _ptr(rowptr), _ptr(colidx), _ptr(val), int(W),
+                                      int(seed) & (2 ** 64 - 1), _ptr(out.s_rowptr), _ptr(out.s_col),
+                                      _ptr(out.s_val), _ptr(out.s_eid), _ptr(out.row_perm), _ptr(workspace),
+                                      workspace.numel(), _stream(stream)))
+    return out._replace(n_rows=n_rows, n_cols=int(n_cols), W=int(W))
+
+
+def aes_spmm_f32(plan: Plan, X, Y=None, *, use_perm: bool = True, stream=None):
+    """Y = A_s X for float32 features."""
+    X = _dev(X, torch.float32, "X", 2)
+    F = X.shape[1]
+    if X.shape[0] != plan.n_cols:
+        raise ValueError("X must have n_cols rows")
+    if Y is None:
+        Y = torch.empty((plan.n_rows, F), dtype=torch.float32, device=X.device)
+    Y = _dev(Y, torch.float32, "Y", 2)
+    if Y.shape[0] != plan.n_rows or Y.shape[1] != F:
+        raise ValueError("Y has the wrong shape")
+    perm = plan.row_perm if use_perm else None
+    _check(library().aes_spmm_f32(plan.n_rows, plan.n_cols, _ptr(plan.s_rowptr), _ptr(plan.s_col), _ptr(plan.s_val),
+                                  _ptr(perm), _ptr(X), _ld(X), F, _ptr(Y), _ld(Y), _stream(stream)))
+    return Y
+
+
+def aes_quantize_features(X, scheme: int, granularity: int, *, out=None, workspace=None, stream=None):
+    """Returns (Xq, scale, zero); Xq is uint8 for the affine scheme, int8 for the symmetric one."""
+    X = _dev(X, torch.float32, "X", 2)
+    n, F = X.shape
+    dev = X.device
+    groups = {AES_Q_PER_TENSOR: 1, AES_Q_PER_COLUMN: F, AES_Q_PER_ROW: n}.get(granularity, 1)
+    qdtype = torch.uint8 if scheme == AES_Q_AFFINE_FLOOR_U8 else torch.int8
+    if out is None:
+        out = (torch.empty((n, F), dtype=qdtype, device=dev),
+               torch.empty(groups, dtype=torch.float32, device=dev),
+               torch.empty(groups, dtype=torch.float32, device=dev))
+    Xq, scale, zero = out
+    need = aes_quantize_workspace_bytes(n, F, granularity)
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    _check(library().aes_quantize_features(n, F, _ptr(X), _ld(X), int(scheme), int(granularity), _ptr(Xq), _ld(Xq),
+                                           _ptr(scale), _ptr(zero), _ptr(workspace),
+                                           0 if workspace is None else workspace.numel(), _stream(stream)))
+    return Xq, scale, zero
+
+
+def aes_spmm_q8(plan: Plan, Xq, scheme: int, granularity: int, scale, zero=None, Y=None, *, use_perm: bool = True,
+                stream=None):
+    """Y = A_s x_hat with the dequantisation fused into the gather."""
+    if not isinstance(Xq, torch.Tensor) or Xq.dtype not in (torch.int8, torch.uint8):
+        raise TypeError("Xq: int8 / uint8 tensor required")
+    Xq = _dev(Xq, Xq.dtype, "Xq", 2)
+    scale = _dev(scale, torch.float32, "scale")
+    if zero is not None:
+        zero = _dev(zero, torch.float32, "zero")
+    F = Xq.shape[1]
+    if Xq.shape[0] != plan.n_cols:
+        raise ValueError("Xq must have n_cols rows")
+    groups = {AES_Q_PER_TENSOR: 1, AES_Q_PER_COLUMN: F, AES_Q_PER_ROW: plan.n_cols}.get(granularity)
+    if groups is not None and (scale.numel() < groups or (zero is not None and zero.numel() < groups)):
+        raise ValueError("scale / zero too short for this granularity")
+    if Y is None:
+        Y = torch.empty((plan.n_rows, F), dtype=torch.float32, device=Xq.device)
+    Y = _dev(Y, torch.float32, "Y", 2)
+    if Y.shape[0] != plan.n_rows or Y.shape[1] != F:
+        raise ValueError("Y has the wrong shape")
+    perm = plan.row_perm if use_perm else None
+    _check(library().aes_spmm_q8(plan.n_rows, plan.n_cols, _ptr(plan.s_rowptr), _ptr(plan.s_col), _ptr(plan.s_val),
+                                 _ptr(perm), _ptr(Xq), _ld(Xq), F, int(scheme), int(granularity), _ptr(scale),
+                                 _ptr(zero), _ptr(Y), _ld(Y), _stream(stream)))
+    return Y

@@ -1,0 +1,351 @@
+// aes_quantize_features: float32 features -> 8-bit codes + (scale, zero) on gfx950.
+//
+// Method: Sec. 2.3 Eq. 1 (b = 8) for the affine scheme; the symmetric scheme is
+// the round-to-nearest variant the benchmark configurations use.  The paper
+// runs this step offline on the CPU; it is on the GPU here so that a feature
+// matrix already resident in HBM can be compressed in place of a host round
+// trip.  Every floating-point step is a single IEEE binary32 operation
+// (subtract, divide, multiply, floor / divide, round-half-even): the file is
+// compiled without contraction and with correctly rounded division, so the
+// codes do not depend on the hardware.
+//
+//   per row            : one kernel, a lane group per row (min/max by cross-lane
+//                        shuffles, then encode; the row stays in registers
+//                        when it fits one chunk)
+//   per column / tensor: column-wise partial min/max over row slabs, a small
+//                        finalise kernel, then an element-wise encode kernel
+#include <cmath>
+
+#include "aes_common.hpp"
+
+namespace {
+
+using aes::kBlock;
+using aes::kWave;
+
+constexpr int kColsPerBlock = 64;                  // partial kernel: 64 columns x 4 row lanes
+constexpr int kRowLanes = kBlock / kColsPerBlock;  // 4
+constexpr int kMaxSlabs = 1024;
+
+__device__ inline uint32_t encode(float x, float lo, float d, float scale, bool affine)
+{
+    if (affine) {
+        int q = 0;
+        if (d != 0.0f) {
+            float t = (x - lo) / d;
+            t = t * 255.0f;
+            q = static_cast<int>(floorf(t));
+            q = q < 0 ? 0 : q > 255 ? 255 : q;
+        }
+        return static_cast<uint32_t>(q);
+    }
+    int q = static_cast<int>(rintf(x / scale));
+    q = q < -127 ? -127 : q > 127 ? 127 : q;
+    return static_cast<uint32_t>(q) & 0xffu;
+}
+
+__device__ inline void group_constants(float lo, float hi, bool affine, float &d, float &scale, float &zero)
+{
+    if (affine) {
+        d = hi - lo;
+        scale = d / 255.0f;
+        zero = lo;
+    } else {
+        d = 0.0f;
+        scale = hi == 0.0f ? 1.0f : hi / 127.0f;   // hi holds max |x|
+        zero = 0.0f;
+    }
+}
+
+// ---- per row ----------------------------------------------------------------
+template <int LPR, int VEC, bool SINGLE>
+__global__ void __launch_bounds__(kBlock)
+quantize_rows_kernel(int64_t n, int32_t F, const float *__restrict__ X, int64_t ldx, int affine_,
+                     int8_t *__restrict__ Xq, int64_t ldq, float *__restrict__ scale_out,
+                     float *__restrict__ zero_out)
+{
+    constexpr int kGroups = kBlock / LPR;
+    const bool affine = affine_ != 0;
+    const int lane = threadIdx.x % LPR;
+    const int64_t r = static_cast<int64_t>(blockIdx.x) * kGroups + threadIdx.x / LPR;
+    if (r >= n) return;
+    const float *x_row = X + r * ldx;
+    float lo = INFINITY, hi = -INFINITY;
+    float keep[VEC];
+    for (int32_t f0 = 0; f0 < F; f0 += LPR * VEC) {
+        const int32_t f = f0 + lane * VEC;
+        if (f < F) {
+            float x[VEC];
+            if constexpr (VEC == 4) {
+                const float4 v = *reinterpret_cast<const float4 *>(x_row + f);
+                x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
+            } else {
+                x[0] = x_row[f];
+            }
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) {
+                if (SINGLE) keep[i] = x[i];
+                const float a = affine ? x[i] : fabsf(x[i]);
+                lo = fminf(lo, a);
+                hi = fmaxf(hi, a);
+            }
+        }
+    }
+#pragma unroll
+    for (int s = LPR / 2; s >= 1; s >>= 1) {
+        lo = fminf(lo, __shfl_xor(lo, s, LPR));
+        hi = fmaxf(hi, __shfl_xor(hi, s, LPR));
+    }
+    float d, scale, zero;
+    group_constants(lo, hi, affine, d, scale, zero);
+    if (lane == 0) {
+        scale_out[r] = scale;
+        if (zero_out) zero_out[r] = zero;
+    }
+    int8_t *q_row = Xq + r * ldq;
+    for (int32_t f0 = 0; f0 < F; f0 += LPR * VEC) {
+        const int32_t f = f0 + lane * VEC;
+        if (f < F) {
+            float x[VEC];
+            if (SINGLE) {
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) x[i] = keep[i];
+            } else if constexpr (VEC == 4) {
+                const float4 v = *reinterpret_cast<const float4 *>(x_row + f);
+                x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
+            } else {
+                x[0] = x_row[f];
+            }
+            if constexpr (VEC == 4) {
+                uint32_t w = encode(x[0], lo, d, scale, affine) | (encode(x[1], lo, d, scale, affine) << 8) |
+                             (encode(x[2], lo, d, scale, affine) << 16) | (encode(x[3], lo, d, scale, affine) << 24);
+                *reinterpret_cast<uint32_t *>(q_row + f) = w;
+            } else {
+                q_row[f] = static_cast<int8_t>(encode(x[0], lo, d, scale, affine));
+            }
+        }
+    }
+}
+
+// ---- per column / per tensor --------------------------------------------------
+// partial[(slab*2 + 0) * F + c] = min, [(slab*2 + 1) * F + c] = max over the slab's rows
+__global__ void __launch_bounds__(kBlock)
+column_partials_kernel(int64_t n, int32_t F, const float *__restrict__ X, int64_t ldx, int affine_,
+                       float *__restrict__ partial)
+{
+    __shared__ float sh_lo[kRowLanes][kColsPerBlock];
+    __shared__ float sh_hi[kRowLanes][kColsPerBlock];
+    const bool affine = affine_ != 0;
+    const int tx = threadIdx.x % kColsPerBlock, ty = threadIdx.x / kColsPerBlock;
+    const int32_t c = blockIdx.y * kColsPerBlock + tx;
+    float lo = INFINITY, hi = -INFINITY;
+    if (c < F) {
+        for (int64_t r = static_cast<int64_t>(blockIdx.x) * kRowLanes + ty; r < n;
+             r += static_cast<int64_t>(gridDim.x) * kRowLanes) {
+            const float x = X[r * ldx + c];
+            const float a = affine ? x : fabsf(x);
+            lo = fminf(lo, a);
+            hi = fmaxf(hi, a);
+        }
+    }
+    sh_lo[ty][tx] = lo;
+    sh_hi[ty][tx] = hi;
+    __syncthreads();
+    if (ty == 0 && c < F) {
+        for (int j = 1; j < kRowLanes; ++j) {
+            lo = fminf(lo, sh_lo[j][tx]);
+            hi = fmaxf(hi, sh_hi[j][tx]);
+        }
+        partial[(static_cast<int64_t>(blockIdx.x) * 2 + 0) * F + c] = lo;
+        partial[(static_cast<int64_t>(blockIdx.x) * 2 + 1) * F + c] = hi;
+    }
+}
+
+// One thread per column folds the slabs; per tensor, one workgroup then folds the
+// columns.  Besides (scale, zero) it keeps x_min and d = x_max - x_min per group
+// for the encode kernel, which must divide by exactly the d that Eq. 1 names
+// (scale * 255 would have been rounded twice).
+__global__ void __launch_bounds__(kBlock)
+finalise_kernel(int32_t F, int n_slabs, int empty, const float *__restrict__ partial, int affine_, int per_tensor,
+                float *__restrict__ scale_out, float *__restrict__ zero_out, float *__restrict__ lo_out,
+                float *__restrict__ d_out)
+{
+    __shared__ float sh_lo[kBlock];
+    __shared__ float sh_hi[kBlock];
+    const bool affine = affine_ != 0;
+    float tlo = INFINITY, thi = -INFINITY;
+    const int32_t first = per_tensor ? threadIdx.x : blockIdx.x * kBlock + threadIdx.x;
+    const int32_t step = per_tensor ? kBlock : F;   // per column: exactly one column per thread
+    for (int32_t c = first; c < F; c += step) {
+        float lo = INFINITY, hi = -INFINITY;
+        for (int s = 0; s < n_slabs; ++s) {
+            lo = fminf(lo, partial[(static_cast<int64_t>(s) * 2 + 0) * F + c]);
+            hi = fmaxf(hi, partial[(static_cast<int64_t>(s) * 2 + 1) * F + c]);
+        }
+        if (empty) { lo = 0.0f; hi = 0.0f; }
+        if (!per_tensor) {
+            float d, scale, zero;
+            group_constants(lo, hi, affine, d, scale, zero);
+            scale_out[c] = scale;
+            if (zero_out) zero_out[c] = zero;
+            lo_out[c] = lo;
+            d_out[c] = d;
+        }
+        tlo = fminf(tlo, lo);
+        thi = fmaxf(thi, hi);
+    }
+    if (!per_tensor) return;
+    sh_lo[threadIdx.x] = tlo;
+    sh_hi[threadIdx.x] = thi;
+    __syncthreads();
+    for (int s = kBlock / 2; s >= 1; s >>= 1) {
+        if (threadIdx.x < s) {
+            sh_lo[threadIdx.x] = fminf(sh_lo[threadIdx.x], sh_lo[threadIdx.x + s]);
+            sh_hi[threadIdx.x] = fmaxf(sh_hi[threadIdx.x], sh_hi[threadIdx.x + s]);
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        float d, scale, zero;
+        group_constants(sh_lo[0], sh_hi[0], affine, d, scale, zero);
+        scale_out[0] = scale;
+        if (zero_out) zero_out[0] = zero;
+        lo_out[0] = sh_lo[0];
+        d_out[0] = d;
+    }
+}
+
+// Element-wise encode with the finished group constants.
+template <int VEC>
+__global__ void __launch_bounds__(kBlock)
+encode_kernel(int64_t n, int32_t F, const float *__restrict__ X, int64_t ldx, int affine_, int per_tensor,
+              const float *__restrict__ scale_in, const float *__restrict__ lo_in, const float *__restrict__ d_in,
+              int8_t *__restrict__ Xq, int64_t ldq)
+{
+    const bool affine = affine_ != 0;
+    const int64_t per_row = F / VEC;
+    const int64_t items = n * per_row;
+    for (int64_t it = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; it < items;
+         it += static_cast<int64_t>(gridDim.x) * kBlock) {
+        const int64_t r = it / per_row;
+        const int32_t f = static_cast<int32_t>(it - r * per_row) * VEC;
+        if constexpr (VEC == 4) {
+            const float4 v = *reinterpret_cast<const float4 *>(X + r * ldx + f);
+            const float x[4] = {v.x, v.y, v.z, v.w};
+            uint32_t w = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int g = per_tensor ? 0 : f + i;
+                w |= encode(x[i], affine ? lo_in[g] : 0.0f, affine ? d_in[g] : 0.0f, scale_in[g], affine) << (8 * i);
+            }
+            *reinterpret_cast<uint32_t *>(Xq + r * ldq + f) = w;
+        } else {
+            const int g = per_tensor ? 0 : f;
+            Xq[r * ldq + f] = static_cast<int8_t>(
+                encode(X[r * ldx + f], affine ? lo_in[g] : 0.0f, affine ? d_in[g] : 0.0f, scale_in[g], affine));
+        }
+    }
+}
+
+int slabs_for(int64_t n)
+{
+    int64_t s = aes::ceil_div(n, static_cast<int64_t>(kRowLanes) * 16);
+    return static_cast<int>(s < 1 ? 1 : s > kMaxSlabs ? kMaxSlabs : s);
+}
+
+template <int LPR, int VEC>
+void launch_rows(int64_t n, int32_t F, const float *X, int64_t ldx, int affine, int8_t *Xq, int64_t ldq,
+                 float *scale, float *zero, hipStream_t stream)
+{
+    const unsigned grid = static_cast<unsigned>(aes::ceil_div(n, kBlock / LPR));
+    if (F <= LPR * VEC)
+        quantize_rows_kernel<LPR, VEC, true><<<dim3(grid), dim3(kBlock), 0, stream>>>(n, F, X, ldx, affine, Xq, ldq, scale, zero);
+    else
+        quantize_rows_kernel<LPR, VEC, false><<<dim3(grid), dim3(kBlock), 0, stream>>>(n, F, X, ldx, affine, Xq, ldq, scale, zero);
+}
+
+}  // namespace
+
+extern "C" size_t aes_quantize_workspace_bytes(int64_t n, int32_t F, int32_t granularity)
+{
+    if (n < 0 || F < 1 || granularity == AES_Q_PER_ROW) return 0;
+    // slab partials (min and max per column) + per-group x_min and range
+    return (static_cast<size_t>(slabs_for(n)) * 2 + 2) * static_cast<size_t>(F) * sizeof(float);
+}
+
+extern "C" int aes_quantize_features(int64_t n, int32_t F, const float *X, int64_t ldx,
+                                     int32_t scheme, int32_t granularity,
+                                     int8_t *Xq, int64_t ldq, float *scale, float *zero,
+                                     void *workspace, size_t workspace_bytes, void *stream_)
+{
+    const char *what = "aes_quantize_features";
+    if (n < 0) return aes::fail(AES_ERR_INVALID_ARG, "%s: n=%lld is negative", what, (long long)n);
+    if (F < 1 || F >= (1 << 24)) return aes::fail(AES_ERR_INVALID_ARG, "%s: F=%d outside 1..2^24-1", what, (int)F);
+    if (ldx < F || ldq < F)
+        return aes::fail(AES_ERR_INVALID_ARG, "%s: leading dimension smaller than F (ldx=%lld ldq=%lld F=%d)", what,
+                         (long long)ldx, (long long)ldq, (int)F);
+    if (scheme != AES_Q_AFFINE_FLOOR_U8 && scheme != AES_Q_SYMMETRIC_RNE_I8)
+        return aes::fail(AES_ERR_INVALID_ARG, "%s: unknown scheme %d", what, (int)scheme);
+    if (granularity < AES_Q_PER_TENSOR || granularity > AES_Q_PER_ROW)
+        return aes::fail(AES_ERR_INVALID_ARG, "%s: unknown granularity %d", what, (int)granularity);
+    const int affine = scheme == AES_Q_AFFINE_FLOOR_U8 ? 1 : 0;
+    if (n > 0 && (X == nullptr || Xq == nullptr)) return aes::fail(AES_ERR_INVALID_ARG, "%s: X / Xq is NULL", what);
+    if (scale == nullptr && (n > 0 || granularity != AES_Q_PER_ROW))
+        return aes::fail(AES_ERR_INVALID_ARG, "%s: scale is NULL", what);
+    if (affine && zero == nullptr && (n > 0 || granularity != AES_Q_PER_ROW))
+        return aes::fail(AES_ERR_INVALID_ARG, "%s: zero is NULL for the affine scheme", what);
+    const size_t need = aes_quantize_workspace_bytes(n, F, granularity);
+    if (need > 0 && (workspace == nullptr || workspace_bytes < need))
+        return aes::fail(AES_ERR_WORKSPACE, "%s: workspace of %zu bytes needed, %zu given%s", what, need,
+                         workspace_bytes, workspace == nullptr ? " (NULL)" : "");
+    if (need > 0 && !aes::aligned(workspace, 4))
+        return aes::fail(AES_ERR_WORKSPACE, "%s: workspace must be 4-byte aligned", what);
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    const bool vec_in = aes::aligned(X, 16) && F % 4 == 0 && ldx % 4 == 0;
+    const bool vec = vec_in && aes::aligned(Xq, 4) && ldq % 4 == 0;
+
+    if (granularity == AES_Q_PER_ROW) {
+        if (n == 0) return AES_OK;
+        if (aes::ceil_div(n, kBlock / 64) > INT32_MAX) return aes::fail(AES_ERR_UNSUPPORTED, "%s: n=%lld too large", what, (long long)n);
+        if (!vec) {
+            launch_rows<64, 1>(n, F, X, ldx, affine, Xq, ldq, scale, zero, stream);
+        } else {
+            int l = aes::pow2_ceil(aes::ceil_div(F, 4));
+            l = l < 8 ? 8 : l > 64 ? 64 : l;
+            switch (l) {
+                case 8: launch_rows<8, 4>(n, F, X, ldx, affine, Xq, ldq, scale, zero, stream); break;
+                case 16: launch_rows<16, 4>(n, F, X, ldx, affine, Xq, ldq, scale, zero, stream); break;
+                case 32: launch_rows<32, 4>(n, F, X, ldx, affine, Xq, ldq, scale, zero, stream); break;
+                default: launch_rows<64, 4>(n, F, X, ldx, affine, Xq, ldq, scale, zero, stream); break;
+            }
+        }
+        return aes::check_launch("aes_quantize_features/rows");
+    }
+
+    const int per_tensor = granularity == AES_Q_PER_TENSOR ? 1 : 0;
+    const int n_slabs = slabs_for(n);
+    float *partial = static_cast<float *>(workspace);
+    float *group_lo = partial + static_cast<size_t>(n_slabs) * 2 * F;
+    float *group_d = group_lo + F;
+    const unsigned col_blocks = static_cast<unsigned>(aes::ceil_div(F, kColsPerBlock));
+    if (n > 0) {
+        column_partials_kernel<<<dim3(n_slabs, col_blocks), dim3(kBlock), 0, stream>>>(n, F, X, ldx, affine, partial);
+        if (int rc = aes::check_launch("aes_quantize_features/partials")) return rc;
+    }
+    const int empty = n == 0 ? 1 : 0;
+    const unsigned fin_blocks = per_tensor ? 1u : static_cast<unsigned>(aes::ceil_div(F, kBlock));
+    finalise_kernel<<<dim3(fin_blocks), dim3(kBlock), 0, stream>>>(F, empty ? 0 : n_slabs, empty, partial, affine,
+                                                                   per_tensor, scale, zero, group_lo, group_d);
+    if (int rc = aes::check_launch("aes_quantize_features/finalise")) return rc;
+    if (n == 0) return AES_OK;
+    const int64_t items = n * (vec ? F / 4 : F);
+    int64_t blocks = aes::ceil_div(items, kBlock);
+    if (blocks > 256 * 64) blocks = 256 * 64;
+    if (vec)
+        encode_kernel<4><<<dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, stream>>>(
+            n, F, X, ldx, affine, per_tensor, scale, group_lo, group_d, Xq, ldq);
+    else
+        encode_kernel<1><<<dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, stream>>>(
+            n, F, X, ldx, affine, per_tensor, scale, group_lo, group_d, Xq, ldq);
+    return aes::check_launch("aes_quantize_features/encode");
+}

@@ -1,0 +1,375 @@
+// aes_sample_build: CSR -> sampled plan on gfx950.
+//
+// Method: AES-SpMM Sec. 3.2 Algorithm 1 (sampling loop), Sec. 3.3 Table 1
+// (strategy selector) and Eq. 3 (start-index hash).  The paper samples inside
+// its SpMM kernel into shared memory; here the sampled rows are materialised
+// once per (graph, W, seed) so that every later multiply only streams them.
+//
+// Four launches on the caller's stream, integer work only:
+//   1 classify : per 1024-row block, slot total and slot-count-class histogram
+//   2 scan     : exclusive scans of the block totals and of the histogram
+//   3 offsets  : s_rowptr and the class-ordered row permutation
+//   4 sample   : one lane group per row copies / samples (col, val) pairs
+#include "aes_common.hpp"
+
+namespace {
+
+using aes::kBlock;
+using aes::kWave;
+
+constexpr int kSubTiles = 4;                          // rows per thread in kernels 1 and 3
+constexpr int kRowsPerBlock = kBlock * kSubTiles;     // 1024
+constexpr int kClasses = 32;                          // class = bit length of the slot count
+constexpr int kScanThreads = 1024;
+constexpr int kScanItems = 8;
+
+// Table 1 with R = row_nnz / W as a real ratio (integer cross-multiplication),
+// N >= 1 and sample_cnt <= W.  Only called for row_nnz > W >= 1.
+__device__ inline void sample_strategy(int64_t row_nnz, int64_t W, int32_t &N, int32_t &sample_cnt)
+{
+    int32_t c;
+    if (row_nnz <= 2 * W)
+        c = 4;
+    else if (row_nnz <= 36 * W)
+        c = 8;
+    else if (row_nnz <= 54 * W)
+        c = 16;
+    else
+        c = 32;
+    int32_t n = static_cast<int32_t>(W) / c;
+    N = n < 1 ? 1 : n;
+    sample_cnt = c > W ? static_cast<int32_t>(W) : c;
+}
+
+// Slots owned by a row: the whole row if it fits (or W == 0), else N*sample_cnt.
+__device__ inline int64_t row_slot_count(int64_t row_nnz, int32_t W)
+{
+    if (W == 0 || row_nnz <= W) return row_nnz;
+    int32_t N, cnt;
+    sample_strategy(row_nnz, W, N, cnt);
+    return static_cast<int64_t>(N) * cnt;
+}
+
+__device__ inline int slot_class(int64_t slots)
+{
+    if (slots <= 0) return 0;
+    int c = 64 - __builtin_clzll(static_cast<unsigned long long>(slots));
+    return c > kClasses - 1 ? kClasses - 1 : c;
+}
+
+// Histogram entry of (class, block): classes in DEcreasing order, blocks ascending,
+// so that one exclusive scan of the flat array yields the row_perm offsets.
+__device__ inline int64_t hist_index(int cls, int64_t blk, int64_t nblk)
+{
+    return static_cast<int64_t>(kClasses - 1 - cls) * nblk + blk;
+}
+
+__device__ inline int64_t wave_inclusive_scan(int64_t v, int lane)
+{
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        int64_t o = __shfl_up(v, d, kWave);
+        if (lane >= d) v += o;
+    }
+    return v;
+}
+
+// ---- kernel 1 ---------------------------------------------------------------
+__global__ void __launch_bounds__(kBlock)
+classify_kernel(int64_t n_rows, const int64_t *__restrict__ rowptr, int32_t W, int64_t nblk,
+                int64_t *__restrict__ blk_slots, int32_t *__restrict__ hist, int want_hist)
+{
+    __shared__ int32_t sh_hist[kClasses];
+    __shared__ int64_t sh_part[aes::kWavesPerBlock];
+    const int t = threadIdx.x, lane = t % kWave, wave = t / kWave;
+    const int64_t blk = blockIdx.x;
+    if (t < kClasses) sh_hist[t] = 0;
+    __syncthreads();
+    int64_t mine = 0;
+    for (int q = 0; q < kSubTiles; ++q) {
+        int64_t r = blk * kRowsPerBlock + q * kBlock + t;
+        if (r < n_rows) {
+            int64_t s = row_slot_count(rowptr[r + 1] - rowptr[r], W);
+            mine += s;
+            if (want_hist) atomicAdd(&sh_hist[slot_class(s)], 1);
+        }
+    }
+    int64_t incl = wave_inclusive_scan(mine, lane);
+    if (lane == kWave - 1) sh_part[wave] = incl;
+    __syncthreads();
+    if (t == 0) {
+        int64_t tot = 0;
+        for (int w = 0; w < aes::kWavesPerBlock; ++w) tot += sh_part[w];
+        blk_slots[blk] = tot;
+    }
+    if (want_hist && t < kClasses) hist[hist_index(t, blk, nblk)] = sh_hist[t];
+}
+
+// ---- kernel 2 ---------------------------------------------------------------
+// In-place exclusive scan of data[0..n) by one workgroup; returns the total to
+// every thread.
+template <typename T>
+__device__ T block_exclusive_scan_inplace(T *data, int64_t n, T *sh_wave /* kScanThreads/64 + 1 */)
+{
+    const int t = threadIdx.x, lane = t % kWave, wave = t / kWave;
+    constexpr int kWaves = kScanThreads / kWave;
+    T carry = 0;
+    for (int64_t base = 0; base < n; base += static_cast<int64_t>(kScanThreads) * kScanItems) {
+        int64_t first = base + static_cast<int64_t>(t) * kScanItems;
+        T item[kScanItems];
+        T sum = 0;
+#pragma unroll
+        for (int i = 0; i < kScanItems; ++i) {
+            item[i] = (first + i < n) ? data[first + i] : T(0);
+            sum += item[i];
+        }
+        T incl = sum;
+#pragma unroll
+        for (int d = 1; d < kWave; d <<= 1) {
+            T o = __shfl_up(incl, d, kWave);
+            if (lane >= d) incl += o;
+        }
+        if (lane == kWave - 1) sh_wave[wave] = incl;
+        __syncthreads();
+        T wave_off = 0, chunk_total = 0;
+        for (int w = 0; w < kWaves; ++w) {
+            T s = sh_wave[w];
+            if (w < wave) wave_off += s;
+            chunk_total += s;
+        }
+        T run = carry + wave_off + (incl - sum);
+#pragma unroll
+        for (int i = 0; i < kScanItems; ++i) {
+            if (first + i < n) data[first + i] = run;
+            run += item[i];
+        }
+        carry += chunk_total;
+        __syncthreads();
+    }
+    return carry;
+}
+
+__global__ void __launch_bounds__(kScanThreads)
+scan_kernel(int64_t n_rows, int64_t nblk, int64_t *__restrict__ blk_slots,
+            int32_t *__restrict__ hist, int n_classes, int64_t *__restrict__ s_rowptr)
+{
+    __shared__ int64_t sh64[kScanThreads / kWave + 1];
+    __shared__ int32_t sh32[kScanThreads / kWave + 1];
+    int64_t total = block_exclusive_scan_inplace<int64_t>(blk_slots, nblk, sh64);
+    if (threadIdx.x == 0) s_rowptr[n_rows] = total;
+    if (hist != nullptr && n_classes > 0) {
+        // entries of classes >= n_classes are all zero and never read: skip them
+        int64_t skip = static_cast<int64_t>(kClasses - n_classes) * nblk;
+        block_exclusive_scan_inplace<int32_t>(hist + skip, static_cast<int64_t>(n_classes) * nblk, sh32);
+    }
+}
+
+// ---- kernel 3 ---------------------------------------------------------------
+__global__ void __launch_bounds__(kBlock)
+offsets_kernel(int64_t n_rows, const int64_t *__restrict__ rowptr, int32_t W, int64_t nblk,
+               const int64_t *__restrict__ blk_slots, const int32_t *__restrict__ hist,
+               int n_classes, int64_t *__restrict__ s_rowptr, int32_t *__restrict__ row_perm)
+{
+    __shared__ int64_t sh_part[aes::kWavesPerBlock];
+    __shared__ int32_t sh_wave_cnt[aes::kWavesPerBlock][kClasses];
+    __shared__ int32_t sh_running[kClasses];
+    const int t = threadIdx.x, lane = t % kWave, wave = t / kWave;
+    const int64_t blk = blockIdx.x;
+    if (t < kClasses) sh_running[t] = 0;
+    int64_t block_prefix = blk_slots[blk];
+    for (int q = 0; q < kSubTiles; ++q) {
+        const int64_t r = blk * kRowsPerBlock + q * kBlock + t;
+        const bool valid = r < n_rows;
+        int64_t s = valid ? row_slot_count(rowptr[r + 1] - rowptr[r], W) : 0;
+        int64_t incl = wave_inclusive_scan(s, lane);
+        if (lane == kWave - 1) sh_part[wave] = incl;
+        const int cls = valid ? slot_class(s) : -1;
+        int rank_in_wave = 0;
+        if (row_perm != nullptr) {
+            for (int c = 0; c < n_classes; ++c) {
+                unsigned long long m = __ballot(cls == c);
+                if (cls == c) rank_in_wave = __popcll(m & ((1ull << lane) - 1ull));
+                if (lane == 0) sh_wave_cnt[wave][c] = __popcll(m);
+            }
+        }
+        __syncthreads();
+        int64_t wave_off = 0, tile_total = 0;
+        for (int w = 0; w < aes::kWavesPerBlock; ++w) {
+            int64_t p = sh_part[w];
+            if (w < wave) wave_off += p;
+            tile_total += p;
+        }
+        if (valid) s_rowptr[r] = block_prefix + wave_off + (incl - s);
+        block_prefix += tile_total;
+        if (row_perm != nullptr && valid) {
+            int rank = sh_running[cls] + rank_in_wave;
+            for (int w = 0; w < wave; ++w) rank += sh_wave_cnt[w][cls];
+            row_perm[hist[hist_index(cls, blk, nblk)] + rank] = static_cast<int32_t>(r);
+        }
+        __syncthreads();
+        if (row_perm != nullptr && t < n_classes) {
+            int add = 0;
+            for (int w = 0; w < aes::kWavesPerBlock; ++w) add += sh_wave_cnt[w][t];
+            sh_running[t] += add;
+        }
+        __syncthreads();
+    }
+}
+
+// ---- kernel 4 ---------------------------------------------------------------
+// One group of L lanes per row.  Rows that fit are copied; longer rows take
+// sample_cnt runs of N consecutive entries, run i starting at Eq. 3's
+// start_i, entry j of run i going to slot i + j*sample_cnt.
+template <int L>
+__global__ void __launch_bounds__(kBlock)
+sample_kernel(int64_t n_rows, const int64_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
+              const float *__restrict__ val, int32_t W, uint64_t seed,
+              const int64_t *__restrict__ s_rowptr, int32_t *__restrict__ s_col,
+              float *__restrict__ s_val, int64_t *__restrict__ s_eid)
+{
+    constexpr int kGroups = kBlock / L;
+    const int lane = threadIdx.x % L;
+    const int64_t r = static_cast<int64_t>(blockIdx.x) * kGroups + threadIdx.x / L;
+    if (r >= n_rows) return;
+    const int64_t row_begin = rowptr[r];
+    const int64_t row_nnz = rowptr[r + 1] - row_begin;
+    const int64_t out = s_rowptr[r];
+    if (W == 0 || row_nnz <= W) {
+        for (int64_t k = lane; k < row_nnz; k += L) {
+            s_col[out + k] = colidx[row_begin + k];
+            s_val[out + k] = val[row_begin + k];
+            if (s_eid) s_eid[out + k] = row_begin + k;
+        }
+        return;
+    }
+    int32_t N, cnt;
+    sample_strategy(row_nnz, W, N, cnt);
+    // lane i < sample_cnt owns sample i's start index (sample_cnt <= min(32, W) <= L)
+    const uint32_t s_r = static_cast<uint32_t>(seed * (2ull * static_cast<uint64_t>(r) + 1ull) * 2654435761ull);
+    const uint64_t modulus = static_cast<uint64_t>(row_nnz - N + 1);
+    const uint64_t prod = (static_cast<uint64_t>(lane) + s_r) * 1429ull;
+    int64_t my_start;
+    if (prod < modulus)
+        my_start = static_cast<int64_t>(prod);
+    else if ((prod | modulus) >> 32 == 0)
+        my_start = static_cast<int64_t>(static_cast<uint32_t>(prod) % static_cast<uint32_t>(modulus));
+    else
+        my_start = static_cast<int64_t>(prod % modulus);
+    const int32_t total = N * cnt;
+    for (int32_t base = 0; base < total; base += L) {
+        const int32_t k = base + lane;
+        const bool valid = k < total;
+        const int32_t i = valid ? k % cnt : 0;
+        const int32_t j = k / cnt;
+        const int64_t start = __shfl(my_start, i, L);
+        if (valid) {
+            const int64_t e = row_begin + start + j;
+            s_col[out + k] = colidx[e];
+            s_val[out + k] = val[e];
+            if (s_eid) s_eid[out + k] = e;
+        }
+    }
+}
+
+template <int L>
+void launch_sample(int64_t n_rows, const int64_t *rowptr, const int32_t *colidx, const float *val,
+                   int32_t W, uint64_t seed, const int64_t *s_rowptr, int32_t *s_col, float *s_val,
+                   int64_t *s_eid, hipStream_t stream)
+{
+    constexpr int kGroups = kBlock / L;
+    const int64_t grid = aes::ceil_div(n_rows, kGroups);
+    sample_kernel<L><<<dim3(static_cast<unsigned>(grid)), dim3(kBlock), 0, stream>>>(
+        n_rows, rowptr, colidx, val, W, seed, s_rowptr, s_col, s_val, s_eid);
+}
+
+int bit_length(int64_t v)
+{
+    int b = 0;
+    while (v > 0) { ++b; v >>= 1; }
+    return b;
+}
+
+}  // namespace
+
+extern "C" int64_t aes_sample_capacity(int64_t n_rows, int64_t nnz, int32_t W)
+{
+    if (n_rows < 0 || nnz < 0 || W < 0 || W > AES_MAX_W)
+        return aes::fail(AES_ERR_INVALID_ARG, "aes_sample_capacity: n_rows=%lld nnz=%lld W=%d out of range",
+                         (long long)n_rows, (long long)nnz, (int)W);
+    if (W == 0) return nnz;
+    // n_rows * W cannot overflow: n_rows < 2^42 is enforced by aes_sample_build, W <= 2^20
+    if (n_rows > (INT64_MAX / AES_MAX_W)) return nnz;
+    const int64_t cap = n_rows * static_cast<int64_t>(W);
+    return cap < nnz ? cap : nnz;
+}
+
+extern "C" size_t aes_sample_workspace_bytes(int64_t n_rows)
+{
+    if (n_rows < 0) return 0;
+    const int64_t nblk = aes::ceil_div(n_rows, kRowsPerBlock);
+    return static_cast<size_t>(8 * (nblk + 1) + 4 * static_cast<int64_t>(kClasses) * nblk);
+}
+
+extern "C" int aes_sample_build(int64_t n_rows, int64_t n_cols, int64_t nnz,
+                                const int64_t *rowptr, const int32_t *colidx, const float *val,
+                                int32_t W, uint64_t seed,
+                                int64_t *s_rowptr, int32_t *s_col, float *s_val, int64_t *s_eid,
+                                int32_t *row_perm,
+                                void *workspace, size_t workspace_bytes, void *stream_)
+{
+    if (n_rows < 0 || n_cols < 0 || nnz < 0)
+        return aes::fail(AES_ERR_INVALID_ARG, "aes_sample_build: negative size (n_rows=%lld n_cols=%lld nnz=%lld)",
+                         (long long)n_rows, (long long)n_cols, (long long)nnz);
+    if (n_cols > INT32_MAX)
+        return aes::fail(AES_ERR_UNSUPPORTED, "aes_sample_build: n_cols=%lld does not fit int32 column indices",
+                         (long long)n_cols);
+    if (W < 0 || W > AES_MAX_W)
+        return aes::fail(AES_ERR_INVALID_ARG, "aes_sample_build: W=%d outside 0..%d", (int)W, (int)AES_MAX_W);
+    if (rowptr == nullptr || s_rowptr == nullptr)
+        return aes::fail(AES_ERR_INVALID_ARG, "aes_sample_build: rowptr / s_rowptr is NULL");
+    if (nnz > 0 && (colidx == nullptr || val == nullptr || s_col == nullptr || s_val == nullptr))
+        return aes::fail(AES_ERR_INVALID_ARG, "aes_sample_build: colidx / val / s_col / s_val is NULL with nnz > 0");
+    if (row_perm != nullptr && n_rows > INT32_MAX)
+        return aes::fail(AES_ERR_UNSUPPORTED, "aes_sample_build: row_perm needs n_rows < 2^31");
+    const int64_t nblk = aes::ceil_div(n_rows, kRowsPerBlock);
+    if (nblk > INT32_MAX)
+        return aes::fail(AES_ERR_UNSUPPORTED, "aes_sample_build: n_rows=%lld too large", (long long)n_rows);
+    const size_t need = aes_sample_workspace_bytes(n_rows);
+    if (workspace == nullptr || workspace_bytes < need)
+        return aes::fail(AES_ERR_WORKSPACE, "aes_sample_build: workspace of %zu bytes needed, %zu given%s", need,
+                         workspace_bytes, workspace == nullptr ? " (NULL)" : "");
+    if (!aes::aligned(workspace, 8))
+        return aes::fail(AES_ERR_WORKSPACE, "aes_sample_build: workspace must be 8-byte aligned");
+
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    int64_t *blk_slots = static_cast<int64_t *>(workspace);            // nblk + 1
+    int32_t *hist = reinterpret_cast<int32_t *>(blk_slots + nblk + 1);  // kClasses * nblk
+    const int want_hist = row_perm != nullptr ? 1 : 0;
+    const int n_classes = W == 0 ? kClasses : bit_length(W) + 1;        // slot counts are <= W
+
+    if (nblk > 0) {
+        classify_kernel<<<dim3(static_cast<unsigned>(nblk)), dim3(kBlock), 0, stream>>>(
+            n_rows, rowptr, W, nblk, blk_slots, hist, want_hist);
+        if (int rc = aes::check_launch("aes_sample_build/classify")) return rc;
+    }
+    scan_kernel<<<dim3(1), dim3(kScanThreads), 0, stream>>>(n_rows, nblk, blk_slots,
+                                                            want_hist ? hist : nullptr, n_classes, s_rowptr);
+    if (int rc = aes::check_launch("aes_sample_build/scan")) return rc;
+    if (nblk == 0) return AES_OK;
+    offsets_kernel<<<dim3(static_cast<unsigned>(nblk)), dim3(kBlock), 0, stream>>>(
+        n_rows, rowptr, W, nblk, blk_slots, hist, n_classes, s_rowptr, row_perm);
+    if (int rc = aes::check_launch("aes_sample_build/offsets")) return rc;
+    if (nnz == 0) return AES_OK;
+
+    // lane-group width: wide enough for sample_cnt (<= min(32, W)) and for the typical row
+    const int L = W == 0 ? 64 : aes::pow2_ceil(W) < 8 ? 8 : aes::pow2_ceil(W) > 64 ? 64 : aes::pow2_ceil(W);
+    if (aes::ceil_div(n_rows, kBlock / L) > INT32_MAX)
+        return aes::fail(AES_ERR_UNSUPPORTED, "aes_sample_build: n_rows=%lld too large for W=%d", (long long)n_rows, (int)W);
+    switch (L) {
+        case 8: launch_sample<8>(n_rows, rowptr, colidx, val, W, seed, s_rowptr, s_col, s_val, s_eid, stream); break;
+        case 16: launch_sample<16>(n_rows, rowptr, colidx, val, W, seed, s_rowptr, s_col, s_val, s_eid, stream); break;
+        case 32: launch_sample<32>(n_rows, rowptr, colidx, val, W, seed, s_rowptr, s_col, s_val, s_eid, stream); break;
+        default: launch_sample<64>(n_rows, rowptr, colidx, val, W, seed, s_rowptr, s_col, s_val, s_eid, stream); break;
+    }
+    return aes::check_launch("aes_sample_build/sample");
+}

@@ -1,0 +1,324 @@
+// aes_spmm_f32 / aes_spmm_q8: the multiply stage of AES-SpMM on gfx950.
+//
+// Method: Sec. 3.2 Algorithm 1, accumulation loop: result += sh_val[k] *
+// B[sh_col[k], cid] over the row's sampled slots; the quantised variant applies
+// Sec. 2.3 Eq. 2 to each gathered feature.  The paper maps one thread to one
+// output element and one thread block to a row; here the mapping follows the
+// 64-wide wavefront and the 512 B - 1 KB feature rows instead:
+//
+//   - a GROUP of LPR lanes owns one output row; each lane owns 4 consecutive
+//     features, so one wavefront load instruction fetches 64/LPR whole feature
+//     rows, each as one contiguous, 16 B-per-lane coalesced segment;
+//   - a wavefront therefore works on 64/LPR rows at once (2 rows at F = 128, 1
+//     at F = 256); rows reach the wavefronts in slot-count-class order (row_perm)
+//     so the groups of a wavefront run the same number of iterations;
+//   - the row's (col, val) slots are staged through a wavefront-private LDS tile
+//     (coalesced load, broadcast read), no workgroup barrier anywhere;
+//   - UNROLL independent feature-row gathers are in flight per lane before the
+//     first fused multiply-add consumes one, which is what keeps HBM busy;
+//   - no cross-lane reduction is needed: a lane sees every slot of its row.
+//
+// The kernel is bound by the gather traffic (about 2 flop per 4 bytes), not by
+// arithmetic, so there is no MFMA here.
+#include "aes_common.hpp"
+
+namespace {
+
+using aes::kBlock;
+using aes::kWave;
+
+constexpr int kTile = 64;          // slots staged in LDS per group per round
+
+enum QMode {
+    kQNone = 0,      // float32 features, or 8-bit features with per-tensor / per-column constants
+    kQRowScale = 1   // 8-bit features with per-row constants: folded into the staged edge value
+};
+
+struct QParams {
+    const float *scale;   // per-row: indexed by column of A (= row of X)
+    const float *zero;    // may be NULL
+    int granularity;      // aes_q_granularity
+    int affine;           // 1: x_hat = q*scale + zero, q unsigned; 0: x_hat = q*scale, q signed
+};
+
+// ---- feature loaders: VEC consecutive features of one row of X --------------
+template <int VEC> struct FeatF32;
+template <> struct FeatF32<4> {
+    using elem_t = float;
+    using raw_t = float4;
+    static __device__ inline raw_t load(const elem_t *p) { return *reinterpret_cast<const float4 *>(p); }
+    static __device__ inline void fma(float (&acc)[4], float v, const raw_t &x)
+    {
+        acc[0] = __builtin_fmaf(v, x.x, acc[0]);
+        acc[1] = __builtin_fmaf(v, x.y, acc[1]);
+        acc[2] = __builtin_fmaf(v, x.z, acc[2]);
+        acc[3] = __builtin_fmaf(v, x.w, acc[3]);
+    }
+};
+template <> struct FeatF32<1> {
+    using elem_t = float;
+    using raw_t = float;
+    static __device__ inline raw_t load(const elem_t *p) { return *p; }
+    static __device__ inline void fma(float (&acc)[1], float v, const raw_t &x) { acc[0] = __builtin_fmaf(v, x, acc[0]); }
+};
+
+template <int VEC, bool SIGNED> struct FeatQ8;
+template <bool SIGNED> struct FeatQ8<4, SIGNED> {
+    using elem_t = int8_t;
+    using raw_t = uint32_t;
+    static __device__ inline raw_t load(const elem_t *p) { return *reinterpret_cast<const uint32_t *>(p); }
+    static __device__ inline float cvt(uint32_t w, int byte)
+    {
+        if (SIGNED) return static_cast<float>(static_cast<int8_t>((w >> (8 * byte)) & 0xffu));
+        return static_cast<float>((w >> (8 * byte)) & 0xffu);
+    }
+    static __device__ inline void fma(float (&acc)[4], float v, const raw_t &x)
+    {
+        acc[0] = __builtin_fmaf(v, cvt(x, 0), acc[0]);
+        acc[1] = __builtin_fmaf(v, cvt(x, 1), acc[1]);
+        acc[2] = __builtin_fmaf(v, cvt(x, 2), acc[2]);
+        acc[3] = __builtin_fmaf(v, cvt(x, 3), acc[3]);
+    }
+};
+template <bool SIGNED> struct FeatQ8<1, SIGNED> {
+    using elem_t = int8_t;
+    using raw_t = int8_t;
+    static __device__ inline raw_t load(const elem_t *p) { return *p; }
+    static __device__ inline void fma(float (&acc)[1], float v, const raw_t &x)
+    {
+        float q = SIGNED ? static_cast<float>(x) : static_cast<float>(static_cast<uint8_t>(x));
+        acc[0] = __builtin_fmaf(v, q, acc[0]);
+    }
+};
+
+// Orders this wavefront's LDS traffic: earlier LDS accesses of any lane are
+// complete (and not moved by the compiler) before later ones start.
+__device__ inline void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// ---- the kernel ---------------------------------------------------------------
+// LPR   lanes per output row (8, 16, 32 or 64); a wavefront holds 64/LPR rows
+// VEC   features per lane per chunk (4 on the aligned fast path, 1 otherwise)
+// Feat  feature loader; QMODE see above; QUANT: apply the 8-bit epilogue
+template <int LPR, int VEC, int UNROLL, typename Feat, int QMODE, bool QUANT>
+__global__ void __launch_bounds__(kBlock)
+spmm_rows_kernel(int64_t n_rows, const int64_t *__restrict__ s_rowptr, const int32_t *__restrict__ s_col,
+                 const float *__restrict__ s_val, const int32_t *__restrict__ row_perm,
+                 const typename Feat::elem_t *__restrict__ X, int64_t ldx, int32_t F, QParams qp,
+                 float *__restrict__ Y, int64_t ldy)
+{
+    constexpr int kGroups = kWave / LPR;                 // rows per wavefront
+    constexpr int kRowsPerBlock = kGroups * aes::kWavesPerBlock;
+    constexpr int kStride = kTile + 1;                   // +1 slot: groups start in different LDS banks
+    __shared__ int2 stage[aes::kWavesPerBlock][kGroups][kStride];
+
+    const int wave = threadIdx.x / kWave;
+    const int group = (threadIdx.x % kWave) / LPR;
+    const int lane = threadIdx.x % LPR;
+    const int64_t slot_in_order = static_cast<int64_t>(blockIdx.x) * kRowsPerBlock + wave * kGroups + group;
+    if (slot_in_order >= n_rows) return;                 // whole group leaves together
+    const int64_t r = row_perm ? static_cast<int64_t>(row_perm[slot_in_order]) : slot_in_order;
+    const int64_t k_begin = s_rowptr[r];
+    const int64_t n_slots = s_rowptr[r + 1] - k_begin;
+    int2 *my_stage = stage[wave][group];
+
+    for (int32_t f0 = 0; f0 < F; f0 += LPR * VEC) {
+        const int32_t f = f0 + lane * VEC;
+        const bool lane_on = f < F;
+        float acc[VEC];
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) acc[i] = 0.0f;
+        float side = 0.0f;      // this lane's share of sum(val * zero-point weight), see epilogue
+
+        for (int64_t t0 = 0; t0 < n_slots; t0 += kTile) {
+            const int m = static_cast<int>(n_slots - t0 < kTile ? n_slots - t0 : kTile);
+            wave_lds_sync();                             // previous tile fully consumed
+#pragma unroll
+            for (int s = lane; s < kTile; s += LPR) {
+                if (s < m) {
+                    const int32_t c = s_col[k_begin + t0 + s];
+                    float v = s_val[k_begin + t0 + s];
+                    if (QUANT) {
+                        if (QMODE == kQRowScale) {
+                            if (qp.affine) side = __builtin_fmaf(v, qp.zero[c], side);
+                            v *= qp.scale[c];
+                        } else if (qp.affine) {
+                            side += v;
+                        }
+                    }
+                    my_stage[s] = make_int2(c, __float_as_int(v));
+                }
+            }
+            wave_lds_sync();                             // tile visible to the whole group
+            if (lane_on) {
+                int k = 0;
+                for (; k + UNROLL <= m; k += UNROLL) {
+                    int2 cv[UNROLL];
+                    typename Feat::raw_t x[UNROLL];
+#pragma unroll
+                    for (int u = 0; u < UNROLL; ++u) cv[u] = my_stage[k + u];
+#pragma unroll
+                    for (int u = 0; u < UNROLL; ++u) x[u] = Feat::load(X + static_cast<int64_t>(cv[u].x) * ldx + f);
+#pragma unroll
+                    for (int u = 0; u < UNROLL; ++u) Feat::fma(acc, __int_as_float(cv[u].y), x[u]);
+                }
+                for (; k < m; ++k) {
+                    const int2 cv = my_stage[k];
+                    const typename Feat::raw_t x = Feat::load(X + static_cast<int64_t>(cv.x) * ldx + f);
+                    Feat::fma(acc, __int_as_float(cv.y), x);
+                }
+            }
+        }
+
+        if (QUANT) {
+            // x_hat = q*scale_g + zero_g, with the group constants taken out of the sum:
+            //   per tensor / column: Y = scale_c * sum(v*q) + zero_c * sum(v)
+            //   per row            : Y = sum((v*scale_col)*q) + sum(v*zero_col)
+            if (qp.affine) {
+#pragma unroll
+                for (int d = LPR / 2; d >= 1; d >>= 1) side += __shfl_xor(side, d, LPR);
+            }
+            if (lane_on) {
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) {
+                    if (QMODE == kQRowScale) {
+                        if (qp.affine) acc[i] += side;
+                    } else {
+                        const int g = qp.granularity == AES_Q_PER_COLUMN ? f + i : 0;
+                        acc[i] *= qp.scale[g];
+                        if (qp.affine) acc[i] = __builtin_fmaf(side, qp.zero[g], acc[i]);
+                    }
+                }
+            }
+        }
+        if (lane_on) {
+            float *y = Y + r * ldy + f;
+            if (VEC == 4) {
+                *reinterpret_cast<float4 *>(y) = make_float4(acc[0], acc[1 % VEC], acc[2 % VEC], acc[3 % VEC]);
+            } else {
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) y[i] = acc[i];
+            }
+        }
+    }
+}
+
+template <int LPR, int VEC, int UNROLL, typename Feat, int QMODE, bool QUANT>
+int launch_rows(int64_t n_rows, const int64_t *s_rowptr, const int32_t *s_col, const float *s_val,
+                const int32_t *row_perm, const typename Feat::elem_t *X, int64_t ldx, int32_t F, QParams qp,
+                float *Y, int64_t ldy, hipStream_t stream, const char *what)
+{
+    constexpr int kRowsPerBlock = (kWave / LPR) * aes::kWavesPerBlock;
+    const int64_t grid = aes::ceil_div(n_rows, kRowsPerBlock);
+    if (grid > INT32_MAX) return aes::fail(AES_ERR_UNSUPPORTED, "%s: n_rows=%lld too large", what, (long long)n_rows);
+    spmm_rows_kernel<LPR, VEC, UNROLL, Feat, QMODE, QUANT>
+        <<<dim3(static_cast<unsigned>(grid)), dim3(kBlock), 0, stream>>>(n_rows, s_rowptr, s_col, s_val, row_perm,
+                                                                           X, ldx, F, qp, Y, ldy);
+    return aes::check_launch(what);
+}
+
+// Lanes per row for the 4-features-per-lane path.
+int lanes_per_row(int32_t F)
+{
+    int l = aes::pow2_ceil(aes::ceil_div(F, 4));
+    return l < 8 ? 8 : l > 64 ? 64 : l;
+}
+
+template <typename FeatVec, typename FeatScalar, int QMODE, bool QUANT>
+int dispatch(bool fast, int64_t n_rows, const int64_t *s_rowptr, const int32_t *s_col, const float *s_val,
+             const int32_t *row_perm, const typename FeatVec::elem_t *X, int64_t ldx, int32_t F, QParams qp,
+             float *Y, int64_t ldy, hipStream_t stream, const char *what)
+{
+    if (!fast)
+        return launch_rows<64, 1, 4, FeatScalar, QMODE, QUANT>(n_rows, s_rowptr, s_col, s_val, row_perm, X, ldx, F,
+                                                                qp, Y, ldy, stream, what);
+    switch (lanes_per_row(F)) {
+        case 8:
+            return launch_rows<8, 4, 8, FeatVec, QMODE, QUANT>(n_rows, s_rowptr, s_col, s_val, row_perm, X, ldx, F, qp,
+                                                                Y, ldy, stream, what);
+        case 16:
+            return launch_rows<16, 4, 8, FeatVec, QMODE, QUANT>(n_rows, s_rowptr, s_col, s_val, row_perm, X, ldx, F, qp,
+                                                                 Y, ldy, stream, what);
+        case 32:
+            return launch_rows<32, 4, 8, FeatVec, QMODE, QUANT>(n_rows, s_rowptr, s_col, s_val, row_perm, X, ldx, F, qp,
+                                                                 Y, ldy, stream, what);
+        default:
+            return launch_rows<64, 4, 8, FeatVec, QMODE, QUANT>(n_rows, s_rowptr, s_col, s_val, row_perm, X, ldx, F, qp,
+                                                                 Y, ldy, stream, what);
+    }
+}
+
+int check_common(const char *what, int64_t n_rows, int64_t n_cols, const int64_t *s_rowptr, const int32_t *s_col,
+                 const float *s_val, const void *X, int64_t ldx, int32_t F, const float *Y, int64_t ldy)
+{
+    if (n_rows < 0 || n_cols < 0)
+        return aes::fail(AES_ERR_INVALID_ARG, "%s: negative size (n_rows=%lld n_cols=%lld)", what, (long long)n_rows,
+                         (long long)n_cols);
+    if (n_cols > INT32_MAX) return aes::fail(AES_ERR_UNSUPPORTED, "%s: n_cols=%lld does not fit int32", what, (long long)n_cols);
+    if (F < 1 || F >= (1 << 24)) return aes::fail(AES_ERR_INVALID_ARG, "%s: F=%d outside 1..2^24-1", what, (int)F);
+    if (ldx < F || ldy < F)
+        return aes::fail(AES_ERR_INVALID_ARG, "%s: leading dimension smaller than F (ldx=%lld ldy=%lld F=%d)", what,
+                         (long long)ldx, (long long)ldy, (int)F);
+    if (s_rowptr == nullptr) return aes::fail(AES_ERR_INVALID_ARG, "%s: s_rowptr is NULL", what);
+    if (n_rows > 0 && Y == nullptr) return aes::fail(AES_ERR_INVALID_ARG, "%s: Y is NULL", what);
+    // s_col / s_val may be NULL only for a plan without slots; that cannot be seen from the host
+    if (n_rows > 0 && n_cols > 0 && X == nullptr) return aes::fail(AES_ERR_INVALID_ARG, "%s: X is NULL", what);
+    return AES_OK;
+}
+
+}  // namespace
+
+extern "C" int aes_spmm_f32(int64_t n_rows, int64_t n_cols,
+                            const int64_t *s_rowptr, const int32_t *s_col, const float *s_val,
+                            const int32_t *row_perm,
+                            const float *X, int64_t ldx, int32_t F,
+                            float *Y, int64_t ldy, void *stream)
+{
+    const char *what = "aes_spmm_f32";
+    if (int rc = check_common(what, n_rows, n_cols, s_rowptr, s_col, s_val, X, ldx, F, Y, ldy)) return rc;
+    if (n_rows == 0) return AES_OK;
+    const bool fast = aes::aligned(X, 16) && aes::aligned(Y, 16) && F % 4 == 0 && ldx % 4 == 0 && ldy % 4 == 0;
+    QParams qp = {nullptr, nullptr, 0, 0};
+    return dispatch<FeatF32<4>, FeatF32<1>, kQNone, false>(fast, n_rows, s_rowptr, s_col, s_val, row_perm, X, ldx, F,
+                                                           qp, Y, ldy, static_cast<hipStream_t>(stream), what);
+}
+
+extern "C" int aes_spmm_q8(int64_t n_rows, int64_t n_cols,
+                           const int64_t *s_rowptr, const int32_t *s_col, const float *s_val,
+                           const int32_t *row_perm,
+                           const int8_t *Xq, int64_t ldq, int32_t F,
+                           int32_t scheme, int32_t granularity,
+                           const float *scale, const float *zero,
+                           float *Y, int64_t ldy, void *stream_)
+{
+    const char *what = "aes_spmm_q8";
+    if (int rc = check_common(what, n_rows, n_cols, s_rowptr, s_col, s_val, Xq, ldq, F, Y, ldy)) return rc;
+    if (scheme != AES_Q_AFFINE_FLOOR_U8 && scheme != AES_Q_SYMMETRIC_RNE_I8)
+        return aes::fail(AES_ERR_INVALID_ARG, "%s: unknown scheme %d", what, (int)scheme);
+    if (granularity < AES_Q_PER_TENSOR || granularity > AES_Q_PER_ROW)
+        return aes::fail(AES_ERR_INVALID_ARG, "%s: unknown granularity %d", what, (int)granularity);
+    if (scale == nullptr) return aes::fail(AES_ERR_INVALID_ARG, "%s: scale is NULL", what);
+    const bool affine = scheme == AES_Q_AFFINE_FLOOR_U8;
+    if (affine && zero == nullptr) return aes::fail(AES_ERR_INVALID_ARG, "%s: zero is NULL for the affine scheme", what);
+    if (n_rows == 0) return AES_OK;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    const bool fast = aes::aligned(Xq, 4) && aes::aligned(Y, 16) && F % 4 == 0 && ldq % 4 == 0 && ldy % 4 == 0;
+    QParams qp = {scale, zero, granularity, affine ? 1 : 0};
+    const bool per_row = granularity == AES_Q_PER_ROW;
+    if (affine) {
+        if (per_row)
+            return dispatch<FeatQ8<4, false>, FeatQ8<1, false>, kQRowScale, true>(
+                fast, n_rows, s_rowptr, s_col, s_val, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
+        return dispatch<FeatQ8<4, false>, FeatQ8<1, false>, kQNone, true>(fast, n_rows, s_rowptr, s_col, s_val, row_perm,
+                                                                          Xq, ldq, F, qp, Y, ldy, stream, what);
+    }
+    if (per_row)
+        return dispatch<FeatQ8<4, true>, FeatQ8<1, true>, kQRowScale, true>(fast, n_rows, s_rowptr, s_col, s_val, row_perm,
+                                                                            Xq, ldq, F, qp, Y, ldy, stream, what);
+    return dispatch<FeatQ8<4, true>, FeatQ8<1, true>, kQNone, true>(fast, n_rows, s_rowptr, s_col, s_val, row_perm, Xq,
+                                                                    ldq, F, qp, Y, ldy, stream, what);
+}

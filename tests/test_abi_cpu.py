@@ -1,0 +1,106 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the
+header declares, and rejects bad arguments on the host before any launch."""
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2503_18427_amd as aes
+    return aes.library()
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "aes_spmm.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(aes_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_symbols_exported(lib):
+    from paper_2503_18427_amd import binding
+    names = _declared_functions()
+    assert set(names) == set(binding.SIGNATURES), "binding and header disagree"
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_no_oracle_in_product():
+    """The product package must not reach the oracle (or any CPU fallback)."""
+    pkg = os.path.join(ROOT, "paper_2503_18427_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".cpp", ".hpp", ".h")):
+                src = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in src.lower(), f
+
+
+def test_capacity_and_workspace(lib):
+    import paper_2503_18427_amd as aes
+    assert aes.aes_sample_capacity(10, 100, 4) == 40
+    assert aes.aes_sample_capacity(10, 30, 4) == 30
+    assert aes.aes_sample_capacity(10, 100, 0) == 100
+    assert aes.aes_sample_capacity(0, 0, 16) == 0
+    with pytest.raises(aes.AesError) as e:
+        aes.aes_sample_capacity(-1, 5, 4)
+    assert e.value.code == -1
+    with pytest.raises(aes.AesError):
+        aes.aes_sample_capacity(1, 5, (1 << 20) + 1)
+    assert aes.aes_sample_workspace_bytes(0) == 8
+    assert aes.aes_sample_workspace_bytes(1025) == 8 * 3 + 4 * 32 * 2
+    assert aes.aes_quantize_workspace_bytes(1000, 128, aes.AES_Q_PER_ROW) == 0
+    assert aes.aes_quantize_workspace_bytes(1000, 128, aes.AES_Q_PER_COLUMN) > 0
+
+
+def test_argument_errors_are_host_side(lib):
+    """Every call below must fail before touching the GPU (there is none here)."""
+    import paper_2503_18427_amd as aes
+    fake = 0x1000  # never dereferenced: argument checks come first
+    sb = lib.aes_sample_build
+    assert sb(-1, 1, 0, fake, fake, fake, 4, 0, fake, fake, fake, None, None, fake, 1 << 20, None) == -1
+    assert "negative" in aes.aes_last_error()
+    assert sb(4, 1 << 31, 0, fake, fake, fake, 4, 0, fake, fake, fake, None, None, fake, 1 << 20, None) == -2
+    assert sb(4, 4, 8, fake, fake, fake, -3, 0, fake, fake, fake, None, None, fake, 1 << 20, None) == -1
+    assert sb(4, 4, 8, None, fake, fake, 4, 0, fake, fake, fake, None, None, fake, 1 << 20, None) == -1
+    assert sb(4, 4, 8, fake, None, fake, 4, 0, fake, fake, fake, None, None, fake, 1 << 20, None) == -1
+    assert sb(4, 4, 8, fake, fake, fake, 4, 0, fake, fake, fake, None, None, None, 0, None) == -3
+    assert sb(4, 4, 8, fake, fake, fake, 4, 0, fake, fake, fake, None, None, fake, 8, None) == -3
+    assert "workspace" in aes.aes_last_error()
+    assert sb(4, 4, 8, fake, fake, fake, 4, 0, fake, fake, fake, None, None, fake + 4, 1 << 20, None) == -3
+
+    f32 = lib.aes_spmm_f32
+    assert f32(-1, 4, fake, fake, fake, None, fake, 8, 8, fake, 8, None) == -1
+    assert f32(4, 4, fake, fake, fake, None, fake, 8, 0, fake, 8, None) == -1
+    assert f32(4, 4, fake, fake, fake, None, fake, 4, 8, fake, 8, None) == -1      # ldx < F
+    assert f32(4, 4, fake, fake, fake, None, fake, 8, 8, fake, 4, None) == -1      # ldy < F
+    assert f32(4, 4, None, fake, fake, None, fake, 8, 8, fake, 8, None) == -1
+    assert f32(4, 4, fake, fake, fake, None, None, 8, 8, fake, 8, None) == -1
+    assert f32(4, 4, fake, fake, fake, None, fake, 8, 8, None, 8, None) == -1
+    assert f32(0, 4, fake, fake, fake, None, fake, 8, 8, None, 8, None) == 0       # nothing to do
+
+    q = lib.aes_quantize_features
+    assert q(-1, 8, fake, 8, 1, 1, fake, 8, fake, fake, fake, 1 << 20, None) == -1
+    assert q(4, 8, fake, 8, 7, 1, fake, 8, fake, fake, fake, 1 << 20, None) == -1
+    assert q(4, 8, fake, 8, 1, 9, fake, 8, fake, fake, fake, 1 << 20, None) == -1
+    assert q(4, 8, fake, 4, 1, 1, fake, 8, fake, fake, fake, 1 << 20, None) == -1
+    assert q(4, 8, fake, 8, 0, 1, fake, 8, fake, None, fake, 1 << 20, None) == -1  # affine needs zero
+    assert q(4, 8, fake, 8, 1, 1, fake, 8, fake, None, None, 0, None) == -3
+    assert q(4, 8, None, 8, 1, 2, fake, 8, fake, None, None, 0, None) == -1
+
+    q8 = lib.aes_spmm_q8
+    assert q8(4, 4, fake, fake, fake, None, fake, 8, 8, 5, 1, fake, fake, fake, 8, None) == -1
+    assert q8(4, 4, fake, fake, fake, None, fake, 8, 8, 1, 5, fake, fake, fake, 8, None) == -1
+    assert q8(4, 4, fake, fake, fake, None, fake, 8, 8, 1, 1, None, fake, fake, 8, None) == -1
+    assert q8(4, 4, fake, fake, fake, None, fake, 8, 8, 0, 1, fake, None, fake, 8, None) == -1
+    assert q8(0, 4, fake, fake, fake, None, fake, 8, 8, 1, 1, fake, None, None, 8, None) == 0
+
+
+def test_binding_rejects_host_tensors():
+    import torch
+    import paper_2503_18427_amd as aes
+    with pytest.raises(TypeError):
+        aes.aes_sample_build(torch.zeros(3, dtype=torch.int64), torch.zeros(2, dtype=torch.int32),
+                             torch.zeros(2), 2, 4)

@@ -1,0 +1,170 @@
+"""GPU parity: the HIP path through the C-ABI against the CPU oracle, element
+by element, on seeded inputs that span several tiles and ragged tails, plus the
+method's edge cases."""
+import numpy as np
+import pytest
+import torch
+
+from helpers import random_csr
+
+pytestmark = pytest.mark.gpu
+
+AFF, SYM = 0, 1
+TENSOR, COLUMN, ROW = 0, 1, 2
+
+
+@pytest.fixture(scope="module")
+def G():
+    import gpu_common
+    import paper_2503_18427_amd as aes
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    aes.library()
+    return gpu_common
+
+
+def _workload(name):
+    from workloads import configs
+    d = configs.make(name, "cpu")
+    return (d["rowptr"].numpy(), d["colidx"].numpy(), d["val"].numpy(), d["X"].numpy(), d["workload"])
+
+
+def _ragged_case(seed, W, n=700, F=64):
+    rng = np.random.default_rng(seed)
+    deg = rng.integers(0, 3 * max(W, 1) + 3, size=n)
+    special = [0, 0, 1, max(W, 1), max(W, 1) + 1, 2 * max(W, 1), 2 * max(W, 1) + 1, 36 * max(W, 1),
+               36 * max(W, 1) + 1, 54 * max(W, 1), 54 * max(W, 1) + 1, 1436, 5000]
+    deg[:len(special)] = special
+    rng.shuffle(deg)
+    n_cols = 900
+    rowptr, col, val = random_csr(n, n_cols, deg, rng)
+    X = rng.standard_normal((n_cols, F)).astype(np.float32)
+    return rowptr, col, val, X, n_cols
+
+
+@pytest.mark.parametrize("W", [1, 2, 4, 7, 16, 32, 48, 64, 100, 128, 256, 1024, 0])
+@pytest.mark.parametrize("seed", [0, 0x9E3779B97F4A7C15])
+def test_sample_build_bit_exact(G, W, seed):
+    rowptr, col, val, X, n_cols = _ragged_case(W + 1, W)
+    plan, ref = G.check_plan(rowptr, col, val, n_cols, W, seed)
+    G.check_f32(plan, ref, X)
+    G.check_f32(plan, ref, X, use_perm=False)
+
+
+@pytest.mark.parametrize("name", ["tiny", "arxiv_small", "reddit_small", "products_small", "rmat12"])
+def test_small_workloads(G, name):
+    rowptr, col, val, X, w = _workload(name)
+    xq = {}
+    for scheme in (SYM, AFF):
+        xq[scheme] = G.check_quantize(X, scheme, w.q_granularity)
+    for W in w.widths + (0,):
+        plan, ref = G.check_plan(rowptr, col, val, w.n, W, 0)
+        Y1, c1, g1 = G.check_f32(plan, ref, X)
+        Y2, _, _ = G.check_f32(plan, ref, X, use_perm=False)
+        assert torch.equal(Y1, Y2)                   # row order does not change any sum
+        for scheme in (SYM, AFF):
+            G.check_q8(plan, ref, xq[scheme][0], xq[scheme][1], scheme, w.q_granularity)
+
+
+@pytest.mark.parametrize("F", [1, 3, 4, 8, 20, 32, 50, 64, 100, 128, 192, 256, 260, 320, 512, 777])
+def test_feature_widths_and_alignment(G, F):
+    rowptr, col, val, _, n_cols = _ragged_case(F, 32, n=300)
+    rng = np.random.default_rng(F)
+    X = rng.standard_normal((n_cols, F)).astype(np.float32)
+    plan, ref = G.check_plan(rowptr, col, val, n_cols, 32, 0)
+    G.check_f32(plan, ref, X)
+    # padded leading dimension, and a misaligned view (element-wise kernel)
+    import paper_2503_18427_amd as aes
+    buf = torch.zeros((n_cols, F + 9), device="cuda")
+    buf[:, 1:F + 1] = G.to_dev(X)
+    Yb = torch.full((rowptr.size - 1, F + 5), 7.0, device="cuda")
+    aes.aes_spmm_f32(plan, buf[:, 1:F + 1], Yb[:, 2:F + 2])
+    Y = aes.aes_spmm_f32(plan, G.to_dev(X))
+    torch.cuda.synchronize()
+    assert torch.equal(Yb[:, 2:F + 2], Y)
+    assert torch.all(Yb[:, :2] == 7.0) and torch.all(Yb[:, F + 2:] == 7.0)   # padding untouched
+    for scheme in (SYM, AFF):
+        for gran in (TENSOR, COLUMN, ROW):
+            qd, qr = G.check_quantize(X, scheme, gran)
+            G.check_q8(plan, ref, qd, qr, scheme, gran)
+
+
+def test_quantize_layouts_and_constants(G):
+    import paper_2503_18427_amd as aes
+    rng = np.random.default_rng(9)
+    n, F = 1000, 96
+    X = (rng.standard_normal((n, F)) * 5).astype(np.float32)
+    X[5, :] = 0.0                  # an all-zero row: scale 1 (symmetric), range 0 (affine)
+    X[:, 7] = -2.5                 # a constant column
+    X[17, 3] = 40.0
+    for scheme in (SYM, AFF):
+        for gran in (TENSOR, COLUMN, ROW):
+            G.check_quantize(X, scheme, gran)
+    # strided input and output
+    big = torch.zeros((n, F + 12), device="cuda")
+    big[:, 4:F + 4] = G.to_dev(X)
+    outq = torch.zeros((n, F + 8), dtype=torch.int8, device="cuda")
+    sc = torch.empty(n, device="cuda")
+    zr = torch.empty(n, device="cuda")
+    aes.aes_quantize_features(big[:, 4:F + 4], SYM, ROW, out=(outq[:, 4:F + 4], sc, zr))
+    ref = aes.aes_quantize_features(G.to_dev(X), SYM, ROW)
+    torch.cuda.synchronize()
+    assert torch.equal(outq[:, 4:F + 4], ref[0]) and torch.equal(sc, ref[1])
+    assert torch.all(outq[:, :4] == 0) and torch.all(outq[:, F + 4:] == 0)
+    # constant tensor
+    C = np.full((33, 8), 1.25, dtype=np.float32)
+    G.check_quantize(C, AFF, TENSOR)
+    G.check_quantize(np.zeros((33, 8), dtype=np.float32), SYM, COLUMN)
+
+
+def test_empty_and_degenerate(G):
+    import paper_2503_18427_amd as aes
+    # no rows
+    plan = aes.aes_sample_build(torch.zeros(1, dtype=torch.int64, device="cuda"),
+                                torch.zeros(0, dtype=torch.int32, device="cuda"),
+                                torch.zeros(0, device="cuda"), 5, 16)
+    torch.cuda.synchronize()
+    assert plan.s_rowptr.tolist() == [0]
+    Y = aes.aes_spmm_f32(plan, torch.ones((5, 8), device="cuda"))
+    assert Y.shape == (0, 8)
+    # rows but no entries: zero output
+    rowptr = np.zeros(1501, dtype=np.int64)
+    plan, ref = G.check_plan(rowptr, np.zeros(0, np.int32), np.zeros(0, np.float32), 5, 16)
+    Y = aes.aes_spmm_f32(plan, torch.ones((5, 8), device="cuda"), torch.full((1500, 8), 3.0, device="cuda"))
+    torch.cuda.synchronize()
+    assert torch.all(Y == 0)
+    # one very long row and the all-starts-coincide row (modulus 1429)
+    for nnz, W in [(100000, 64), (1436, 64), (1 << 17, 1024)]:
+        rp = np.array([0, nnz], dtype=np.int64)
+        rng = np.random.default_rng(nnz)
+        col = rng.integers(0, 300, size=nnz).astype(np.int32)
+        val = rng.standard_normal(nnz).astype(np.float32)
+        X = rng.standard_normal((300, 128)).astype(np.float32)
+        plan, ref = G.check_plan(rp, col, val, 300, W)
+        G.check_f32(plan, ref, X)
+        plan0, ref0 = G.check_plan(rp, col, val, 300, 0)
+        G.check_f32(plan0, ref0, X)
+
+
+def test_bit_reproducible(G):
+    import paper_2503_18427_amd as aes
+    rowptr, col, val, X, w = _workload("products_small")
+    plan, _ = G.check_plan(rowptr, col, val, w.n, 64)
+    Xd = G.to_dev(X)
+    Y1 = aes.aes_spmm_f32(plan, Xd).clone()
+    Y2 = aes.aes_spmm_f32(plan, Xd)
+    torch.cuda.synchronize()
+    assert torch.equal(Y1, Y2)
+
+
+def test_side_stream(G):
+    import paper_2503_18427_amd as aes
+    rowptr, col, val, X, w = _workload("arxiv_small")
+    plan, ref = G.check_plan(rowptr, col, val, w.n, 32)
+    Xd = G.to_dev(X)
+    Y0 = aes.aes_spmm_f32(plan, Xd)
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        Y1 = aes.aes_spmm_f32(plan, Xd)
+    s.synchronize()
+    assert torch.equal(Y0, Y1)
