@@ -55,7 +55,11 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="products_like")
     ap.add_argument("--width", type=int, default=0, help="sampling width W (default: the workload's first)")
-    ap.add_argument("--cpu-rows", type=int, default=200_000, help="rows in the CPU oracle's sample (0: skip)")
+    ap.add_argument("--cpu-rows", type=int, default=-1,
+                    help="rows in the CPU oracle's sample (-1: all rows, 0: skip the CPU baseline)")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also launch a plain 1 GiB read + 1 GiB write elementwise kernel three times "
+                         "(the known-size reference for scaling rocprofv3 HBM counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -187,9 +191,18 @@ def main() -> int:
         "roofline": roofline,
     }
 
-    if args.cpu_rows > 0:
+    if args.copy_probe:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.mul(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
+
+    if args.cpu_rows != 0:
+        n_cpu = n if args.cpu_rows < 0 else min(args.cpu_rows, n)
         out["cpu_baseline"], out["max_rel_err"] = cpu_baseline(
-            d, plan, Y, Yq, qbuf, W, scheme, gran, min(args.cpu_rows, n), leg_bytes, total_bytes, S)
+            d, plan, Y, Yq, qbuf, W, scheme, gran, n_cpu, leg_bytes, total_bytes, S)
     print(json.dumps(out))
     return 0
 
@@ -206,7 +219,10 @@ def cpu_baseline(d, plan, Y, Yq, qbuf, W, scheme, gran, n_rows_sample, leg_bytes
     rowptr, colidx, val = (d[k].cpu().numpy() for k in ("rowptr", "colidx", "val"))
     X = d["X"].cpu().numpy()
     rng = np.random.default_rng(0)
-    rows = np.sort(rng.choice(n, size=n_rows_sample, replace=False)).astype(np.int64)
+    if n_rows_sample >= n:
+        rows = np.arange(n, dtype=np.int64)
+    else:
+        rows = np.sort(rng.choice(n, size=n_rows_sample, replace=False)).astype(np.int64)
 
     t = time.perf_counter()
     ref = orc.sample_build(rowptr, colidx, val, W, 0, want_eid=False)
@@ -250,7 +266,7 @@ def cpu_baseline(d, plan, Y, Yq, qbuf, W, scheme, gran, n_rows_sample, leg_bytes
         "unit": "GB/s",
         "cores": orc.num_threads(),
         "kind": "oracle",
-        "sample": f"sample build on all rows; fp32 and int8 SpMM on {n_rows_sample} random rows "
+        "sample": f"sample build on all rows; fp32 and int8 SpMM on {n_rows_sample} of {n} rows "
                   f"({slots_rows} slots; the int8 leg dequantises all of X first, as the oracle defines it); "
                   f"quantise on the first {nq} rows; each leg's rate scaled to the full step's bytes",
         "seconds": {"sample_build": t_build, "spmm_f32": t_f32, "quantize": t_quant, "spmm_q8": t_q8},

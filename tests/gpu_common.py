@@ -12,7 +12,13 @@ Q8_TOL = 1e-2       # same for the 8-bit path, against the oracle's own dequanti
 
 
 def to_dev(a):
+    if isinstance(a, torch.Tensor):
+        return a.cuda()
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def to_host(a):
+    return a.cpu().numpy() if isinstance(a, torch.Tensor) else a
 
 
 def class_order(slots):
@@ -25,7 +31,7 @@ def class_order(slots):
 
 def check_plan(rowptr, colidx, val, n_cols, W, seed=0):
     """aes_sample_build against the oracle, bit for bit.  Returns (plan, oracle plan)."""
-    ref = orc.sample_build(rowptr, colidx, val, W, seed=seed)
+    ref = orc.sample_build(to_host(rowptr), to_host(colidx), to_host(val), W, seed=seed)
     plan = aes.aes_sample_build(to_dev(rowptr), to_dev(colidx), to_dev(val), n_cols, W, seed,
                                 want_eid=True, want_perm=True)
     torch.cuda.synchronize()
