@@ -195,7 +195,8 @@ int aes_quantize_features(int64_t n, int32_t F, const float *X, int64_t ldx,
  *   scale, zero [dev]  as written by aes_quantize_features; zero may be NULL
  *                for SYMMETRIC_RNE_I8
  * Other arguments as aes_spmm_f32.  The fast path needs Xq 4-byte aligned,
- * F and ldq multiples of 4, Y 16-byte aligned and ldy a multiple of 4.
+ * F and ldq multiples of 4, Y 16-byte aligned and ldy a multiple of 4;
+ * anything else runs the element-wise kernel.
  */
 int aes_spmm_q8(int64_t n_rows, int64_t n_cols,
                 const int64_t *s_rowptr, const int32_t *s_col, const float *s_val,

@@ -119,8 +119,11 @@ def aes_quantize_workspace_bytes(n: int, F: int, granularity: int) -> int:
 
 
 def aes_sample_build(rowptr, colidx, val, n_cols: int, W: int, seed: int = 0, *, want_eid: bool = False,
-                     want_perm: bool = True, out: Optional[Plan] = None, workspace=None, stream=None) -> Plan:
-    """Build the sampled plan of a CSR matrix.  `out` reuses the buffers of an earlier plan."""
+                     want_perm: bool = False, out: Optional[Plan] = None, workspace=None, stream=None) -> Plan:
+    """Build the sampled plan of a CSR matrix.  `out` reuses the buffers of an earlier plan.
+    `want_perm` also asks for the class-ordered row permutation (a scheduling hint
+    the SpMM calls use when `use_perm` is set; natural order measured faster on
+    MI355X, so it is off by default)."""
     rowptr = _dev(rowptr, torch.int64, "rowptr")
     colidx = _dev(colidx, torch.int32, "colidx")
     val = _dev(val, torch.float32, "val")

@@ -13,7 +13,8 @@
 //                        shuffles, then encode; the row stays in registers
 //                        when it fits one chunk)
 //   per column / tensor: column-wise partial min/max over row slabs, a small
-//                        finalise kernel, then an element-wise encode kernel
+//                        finalise kernel (plus a one-workgroup fold for per
+//                        tensor), then an element-wise encode kernel
 #include <cmath>
 
 #include "aes_common.hpp"
@@ -25,7 +26,7 @@ using aes::kWave;
 
 constexpr int kColsPerBlock = 64;                  // partial kernel: 64 columns x 4 row lanes
 constexpr int kRowLanes = kBlock / kColsPerBlock;  // 4
-constexpr int kMaxSlabs = 1024;
+constexpr int kMaxSlabs = 512;
 
 __device__ inline uint32_t encode(float x, float lo, float d, float scale, bool affine)
 {
@@ -140,8 +141,17 @@ column_partials_kernel(int64_t n, int32_t F, const float *__restrict__ X, int64_
     const int32_t c = blockIdx.y * kColsPerBlock + tx;
     float lo = INFINITY, hi = -INFINITY;
     if (c < F) {
-        for (int64_t r = static_cast<int64_t>(blockIdx.x) * kRowLanes + ty; r < n;
-             r += static_cast<int64_t>(gridDim.x) * kRowLanes) {
+        const int64_t step = static_cast<int64_t>(gridDim.x) * kRowLanes;
+        int64_t r = static_cast<int64_t>(blockIdx.x) * kRowLanes + ty;
+        for (; r + 3 * step < n; r += 4 * step) {     // four independent loads in flight
+            const float x0 = X[r * ldx + c], x1 = X[(r + step) * ldx + c];
+            const float x2 = X[(r + 2 * step) * ldx + c], x3 = X[(r + 3 * step) * ldx + c];
+            const float a0 = affine ? x0 : fabsf(x0), a1 = affine ? x1 : fabsf(x1);
+            const float a2 = affine ? x2 : fabsf(x2), a3 = affine ? x3 : fabsf(x3);
+            lo = fminf(fminf(lo, a0), fminf(a1, fminf(a2, a3)));
+            hi = fmaxf(fmaxf(hi, a0), fmaxf(a1, fmaxf(a2, a3)));
+        }
+        for (; r < n; r += step) {
             const float x = X[r * ldx + c];
             const float a = affine ? x : fabsf(x);
             lo = fminf(lo, a);
@@ -161,42 +171,65 @@ column_partials_kernel(int64_t n, int32_t F, const float *__restrict__ X, int64_
     }
 }
 
-// One thread per column folds the slabs; per tensor, one workgroup then folds the
-// columns.  Besides (scale, zero) it keeps x_min and d = x_max - x_min per group
-// for the encode kernel, which must divide by exactly the d that Eq. 1 names
-// (scale * 255 would have been rounded twice).
+// Folds the slab partials of 64 columns per workgroup (4 lanes per column).
+// Per column: writes (scale, zero) and keeps x_min and d = x_max - x_min for the
+// encode kernel, which must divide by exactly the d that Eq. 1 names (scale * 255
+// would have been rounded twice).  Per tensor: leaves the column's (min, max) in
+// lo_out / d_out for tensor_fold_kernel.
 __global__ void __launch_bounds__(kBlock)
 finalise_kernel(int32_t F, int n_slabs, int empty, const float *__restrict__ partial, int affine_, int per_tensor,
                 float *__restrict__ scale_out, float *__restrict__ zero_out, float *__restrict__ lo_out,
                 float *__restrict__ d_out)
 {
-    __shared__ float sh_lo[kBlock];
-    __shared__ float sh_hi[kBlock];
+    __shared__ float sh_lo[kRowLanes][kColsPerBlock];
+    __shared__ float sh_hi[kRowLanes][kColsPerBlock];
     const bool affine = affine_ != 0;
-    float tlo = INFINITY, thi = -INFINITY;
-    const int32_t first = per_tensor ? threadIdx.x : blockIdx.x * kBlock + threadIdx.x;
-    const int32_t step = per_tensor ? kBlock : F;   // per column: exactly one column per thread
-    for (int32_t c = first; c < F; c += step) {
-        float lo = INFINITY, hi = -INFINITY;
-        for (int s = 0; s < n_slabs; ++s) {
+    const int tx = threadIdx.x % kColsPerBlock, ty = threadIdx.x / kColsPerBlock;
+    const int32_t c = blockIdx.x * kColsPerBlock + tx;
+    float lo = INFINITY, hi = -INFINITY;
+    if (c < F) {
+        for (int s = ty; s < n_slabs; s += kRowLanes) {
             lo = fminf(lo, partial[(static_cast<int64_t>(s) * 2 + 0) * F + c]);
             hi = fmaxf(hi, partial[(static_cast<int64_t>(s) * 2 + 1) * F + c]);
         }
-        if (empty) { lo = 0.0f; hi = 0.0f; }
-        if (!per_tensor) {
-            float d, scale, zero;
-            group_constants(lo, hi, affine, d, scale, zero);
-            scale_out[c] = scale;
-            if (zero_out) zero_out[c] = zero;
-            lo_out[c] = lo;
-            d_out[c] = d;
-        }
-        tlo = fminf(tlo, lo);
-        thi = fmaxf(thi, hi);
     }
-    if (!per_tensor) return;
-    sh_lo[threadIdx.x] = tlo;
-    sh_hi[threadIdx.x] = thi;
+    sh_lo[ty][tx] = lo;
+    sh_hi[ty][tx] = hi;
+    __syncthreads();
+    if (ty != 0 || c >= F) return;
+    for (int j = 1; j < kRowLanes; ++j) {
+        lo = fminf(lo, sh_lo[j][tx]);
+        hi = fmaxf(hi, sh_hi[j][tx]);
+    }
+    if (empty) { lo = 0.0f; hi = 0.0f; }
+    if (per_tensor) {
+        lo_out[c] = lo;
+        d_out[c] = hi;
+        return;
+    }
+    float d, scale, zero;
+    group_constants(lo, hi, affine, d, scale, zero);
+    scale_out[c] = scale;
+    if (zero_out) zero_out[c] = zero;
+    lo_out[c] = lo;
+    d_out[c] = d;
+}
+
+// Per tensor: one workgroup folds the F per-column (min, max) pairs left in
+// lo_io / hi_io and replaces entry 0 by the tensor's x_min and d.
+__global__ void __launch_bounds__(kBlock)
+tensor_fold_kernel(int32_t F, int affine_, float *__restrict__ lo_io, float *__restrict__ hi_io,
+                   float *__restrict__ scale_out, float *__restrict__ zero_out)
+{
+    __shared__ float sh_lo[kBlock];
+    __shared__ float sh_hi[kBlock];
+    float lo = INFINITY, hi = -INFINITY;
+    for (int32_t c = threadIdx.x; c < F; c += kBlock) {
+        lo = fminf(lo, lo_io[c]);
+        hi = fmaxf(hi, hi_io[c]);
+    }
+    sh_lo[threadIdx.x] = lo;
+    sh_hi[threadIdx.x] = hi;
     __syncthreads();
     for (int s = kBlock / 2; s >= 1; s >>= 1) {
         if (threadIdx.x < s) {
@@ -207,11 +240,11 @@ finalise_kernel(int32_t F, int n_slabs, int empty, const float *__restrict__ par
     }
     if (threadIdx.x == 0) {
         float d, scale, zero;
-        group_constants(sh_lo[0], sh_hi[0], affine, d, scale, zero);
+        group_constants(sh_lo[0], sh_hi[0], affine_ != 0, d, scale, zero);
         scale_out[0] = scale;
         if (zero_out) zero_out[0] = zero;
-        lo_out[0] = sh_lo[0];
-        d_out[0] = d;
+        lo_io[0] = sh_lo[0];
+        hi_io[0] = d;
     }
 }
 
@@ -333,10 +366,13 @@ extern "C" int aes_quantize_features(int64_t n, int32_t F, const float *X, int64
         if (int rc = aes::check_launch("aes_quantize_features/partials")) return rc;
     }
     const int empty = n == 0 ? 1 : 0;
-    const unsigned fin_blocks = per_tensor ? 1u : static_cast<unsigned>(aes::ceil_div(F, kBlock));
-    finalise_kernel<<<dim3(fin_blocks), dim3(kBlock), 0, stream>>>(F, empty ? 0 : n_slabs, empty, partial, affine,
+    finalise_kernel<<<dim3(col_blocks), dim3(kBlock), 0, stream>>>(F, empty ? 0 : n_slabs, empty, partial, affine,
                                                                    per_tensor, scale, zero, group_lo, group_d);
     if (int rc = aes::check_launch("aes_quantize_features/finalise")) return rc;
+    if (per_tensor) {
+        tensor_fold_kernel<<<dim3(1), dim3(kBlock), 0, stream>>>(F, affine, group_lo, group_d, scale, zero);
+        if (int rc = aes::check_launch("aes_quantize_features/tensor_fold")) return rc;
+    }
     if (n == 0) return AES_OK;
     const int64_t items = n * (vec ? F / 4 : F);
     int64_t blocks = aes::ceil_div(items, kBlock);

@@ -9,7 +9,7 @@
 //   1 classify : per 1024-row block, slot total and slot-count-class histogram
 //   2 scan     : exclusive scans of the block totals and of the histogram
 //   3 offsets  : s_rowptr and the class-ordered row permutation
-//   4 sample   : one lane group per row copies / samples (col, val) pairs
+//   4 sample   : one thread per output slot copies / samples a (col, val) pair
 #include "aes_common.hpp"
 
 namespace {
@@ -217,69 +217,68 @@ offsets_kernel(int64_t n_rows, const int64_t *__restrict__ rowptr, int32_t W, in
 }
 
 // ---- kernel 4 ---------------------------------------------------------------
-// One group of L lanes per row.  Rows that fit are copied; longer rows take
-// sample_cnt runs of N consecutive entries, run i starting at Eq. 3's
-// start_i, entry j of run i going to slot i + j*sample_cnt.
-template <int L>
-__global__ void __launch_bounds__(kBlock)
-sample_kernel(int64_t n_rows, const int64_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
-              const float *__restrict__ val, int32_t W, uint64_t seed,
-              const int64_t *__restrict__ s_rowptr, int32_t *__restrict__ s_col,
-              float *__restrict__ s_val, int64_t *__restrict__ s_eid)
+// One thread per OUTPUT SLOT.  A workgroup owns kSampleRows consecutive rows:
+// their rowptr / s_rowptr segments sit in LDS, every thread finds the row of its
+// slot by binary search there, then copies (row fits) or samples: slot k of a
+// sampled row is entry j = k / sample_cnt of run i = k % sample_cnt, the run
+// starting at Eq. 3's start_i.  Writes are perfectly coalesced and the work per
+// thread does not depend on the degree distribution.
+constexpr int kSampleRows = 256;
+
+__device__ inline int64_t hash_start(uint64_t current_ind, int64_t row_nnz, int32_t N)
 {
-    constexpr int kGroups = kBlock / L;
-    const int lane = threadIdx.x % L;
-    const int64_t r = static_cast<int64_t>(blockIdx.x) * kGroups + threadIdx.x / L;
-    if (r >= n_rows) return;
-    const int64_t row_begin = rowptr[r];
-    const int64_t row_nnz = rowptr[r + 1] - row_begin;
-    const int64_t out = s_rowptr[r];
-    if (W == 0 || row_nnz <= W) {
-        for (int64_t k = lane; k < row_nnz; k += L) {
-            s_col[out + k] = colidx[row_begin + k];
-            s_val[out + k] = val[row_begin + k];
-            if (s_eid) s_eid[out + k] = row_begin + k;
-        }
-        return;
-    }
-    int32_t N, cnt;
-    sample_strategy(row_nnz, W, N, cnt);
-    // lane i < sample_cnt owns sample i's start index (sample_cnt <= min(32, W) <= L)
-    const uint32_t s_r = static_cast<uint32_t>(seed * (2ull * static_cast<uint64_t>(r) + 1ull) * 2654435761ull);
     const uint64_t modulus = static_cast<uint64_t>(row_nnz - N + 1);
-    const uint64_t prod = (static_cast<uint64_t>(lane) + s_r) * 1429ull;
-    int64_t my_start;
-    if (prod < modulus)
-        my_start = static_cast<int64_t>(prod);
-    else if ((prod | modulus) >> 32 == 0)
-        my_start = static_cast<int64_t>(static_cast<uint32_t>(prod) % static_cast<uint32_t>(modulus));
-    else
-        my_start = static_cast<int64_t>(prod % modulus);
-    const int32_t total = N * cnt;
-    for (int32_t base = 0; base < total; base += L) {
-        const int32_t k = base + lane;
-        const bool valid = k < total;
-        const int32_t i = valid ? k % cnt : 0;
-        const int32_t j = k / cnt;
-        const int64_t start = __shfl(my_start, i, L);
-        if (valid) {
-            const int64_t e = row_begin + start + j;
-            s_col[out + k] = colidx[e];
-            s_val[out + k] = val[e];
-            if (s_eid) s_eid[out + k] = e;
-        }
-    }
+    const uint64_t prod = current_ind * 1429ull;
+    if (prod < modulus) return static_cast<int64_t>(prod);
+    if (((prod | modulus) >> 32) == 0)
+        return static_cast<int64_t>(static_cast<uint32_t>(prod) % static_cast<uint32_t>(modulus));
+    return static_cast<int64_t>(prod % modulus);
 }
 
-template <int L>
-void launch_sample(int64_t n_rows, const int64_t *rowptr, const int32_t *colidx, const float *val,
-                   int32_t W, uint64_t seed, const int64_t *s_rowptr, int32_t *s_col, float *s_val,
-                   int64_t *s_eid, hipStream_t stream)
+__global__ void __launch_bounds__(kBlock)
+sample_slots_kernel(int64_t n_rows, const int64_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
+                    const float *__restrict__ val, int32_t W, uint64_t seed,
+                    const int64_t *__restrict__ s_rowptr, int32_t *__restrict__ s_col,
+                    float *__restrict__ s_val, int64_t *__restrict__ s_eid)
 {
-    constexpr int kGroups = kBlock / L;
-    const int64_t grid = aes::ceil_div(n_rows, kGroups);
-    sample_kernel<L><<<dim3(static_cast<unsigned>(grid)), dim3(kBlock), 0, stream>>>(
-        n_rows, rowptr, colidx, val, W, seed, s_rowptr, s_col, s_val, s_eid);
+    __shared__ int64_t sh_out[kSampleRows + 1];
+    __shared__ int64_t sh_in[kSampleRows + 1];
+    const int64_t r_lo = static_cast<int64_t>(blockIdx.x) * kSampleRows;
+    const int nr = static_cast<int>(n_rows - r_lo < kSampleRows ? n_rows - r_lo : kSampleRows);
+    for (int i = threadIdx.x; i <= nr; i += kBlock) {
+        sh_out[i] = s_rowptr[r_lo + i];
+        sh_in[i] = rowptr[r_lo + i];
+    }
+    __syncthreads();
+    const int64_t base = sh_out[0];
+    const int64_t total = sh_out[nr] - base;
+    for (int64_t t = threadIdx.x; t < total; t += kBlock) {
+        // largest q in [0, nr) with sh_out[q] - base <= t (empty rows are skipped by construction)
+        int lo = 0, hi = nr;
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (sh_out[mid] - base <= t) lo = mid; else hi = mid;
+        }
+        const int64_t r = r_lo + lo;
+        const int64_t k = t - (sh_out[lo] - base);
+        const int64_t row_begin = sh_in[lo];
+        const int64_t row_nnz = sh_in[lo + 1] - row_begin;
+        int64_t e;
+        if (W == 0 || row_nnz <= W) {
+            e = row_begin + k;
+        } else {
+            int32_t N, cnt;
+            sample_strategy(row_nnz, W, N, cnt);
+            const int32_t k32 = static_cast<int32_t>(k);
+            const int32_t i = k32 % cnt;
+            const int32_t j = k32 / cnt;
+            const uint32_t s_r = static_cast<uint32_t>(seed * (2ull * static_cast<uint64_t>(r) + 1ull) * 2654435761ull);
+            e = row_begin + hash_start(static_cast<uint64_t>(i) + s_r, row_nnz, N) + j;
+        }
+        s_col[base + t] = colidx[e];
+        s_val[base + t] = val[e];
+        if (s_eid) s_eid[base + t] = e;
+    }
 }
 
 int bit_length(int64_t v)
@@ -361,15 +360,10 @@ extern "C" int aes_sample_build(int64_t n_rows, int64_t n_cols, int64_t nnz,
     if (int rc = aes::check_launch("aes_sample_build/offsets")) return rc;
     if (nnz == 0) return AES_OK;
 
-    // lane-group width: wide enough for sample_cnt (<= min(32, W)) and for the typical row
-    const int L = W == 0 ? 64 : aes::pow2_ceil(W) < 8 ? 8 : aes::pow2_ceil(W) > 64 ? 64 : aes::pow2_ceil(W);
-    if (aes::ceil_div(n_rows, kBlock / L) > INT32_MAX)
-        return aes::fail(AES_ERR_UNSUPPORTED, "aes_sample_build: n_rows=%lld too large for W=%d", (long long)n_rows, (int)W);
-    switch (L) {
-        case 8: launch_sample<8>(n_rows, rowptr, colidx, val, W, seed, s_rowptr, s_col, s_val, s_eid, stream); break;
-        case 16: launch_sample<16>(n_rows, rowptr, colidx, val, W, seed, s_rowptr, s_col, s_val, s_eid, stream); break;
-        case 32: launch_sample<32>(n_rows, rowptr, colidx, val, W, seed, s_rowptr, s_col, s_val, s_eid, stream); break;
-        default: launch_sample<64>(n_rows, rowptr, colidx, val, W, seed, s_rowptr, s_col, s_val, s_eid, stream); break;
-    }
+    const int64_t sample_blocks = aes::ceil_div(n_rows, kSampleRows);
+    if (sample_blocks > INT32_MAX)
+        return aes::fail(AES_ERR_UNSUPPORTED, "aes_sample_build: n_rows=%lld too large", (long long)n_rows);
+    sample_slots_kernel<<<dim3(static_cast<unsigned>(sample_blocks)), dim3(kBlock), 0, stream>>>(
+        n_rows, rowptr, colidx, val, W, seed, s_rowptr, s_col, s_val, s_eid);
     return aes::check_launch("aes_sample_build/sample");
 }

@@ -42,8 +42,14 @@ struct QParams {
 };
 
 // ---- feature loaders: VEC consecutive features of one row of X --------------
-template <int VEC> struct FeatF32;
+// fma(acc, v, x) adds v * (feature + kBias) to acc; the kernel removes
+// kBias * sum(v) in its epilogue.  kBias = 128 lets signed 8-bit codes be
+// converted as unsigned bytes (one conversion instruction per byte, after one
+// XOR per four bytes) instead of sign-extending each byte first.
+template <int VEC_> struct FeatF32;
 template <> struct FeatF32<4> {
+    static constexpr int VEC = 4;
+    static constexpr int kBias = 0;
     using elem_t = float;
     using raw_t = float4;
     static __device__ inline raw_t load(const elem_t *p) { return *reinterpret_cast<const float4 *>(p); }
@@ -56,31 +62,37 @@ template <> struct FeatF32<4> {
     }
 };
 template <> struct FeatF32<1> {
+    static constexpr int VEC = 1;
+    static constexpr int kBias = 0;
     using elem_t = float;
     using raw_t = float;
     static __device__ inline raw_t load(const elem_t *p) { return *p; }
     static __device__ inline void fma(float (&acc)[1], float v, const raw_t &x) { acc[0] = __builtin_fmaf(v, x, acc[0]); }
 };
 
-template <int VEC, bool SIGNED> struct FeatQ8;
+// Four packed bytes -> four floats (unsigned; signed codes arrive biased by 128).
+template <bool SIGNED>
+__device__ inline void fma_bytes(float *acc, float v, uint32_t w)
+{
+    if (SIGNED) w ^= 0x80808080u;
+    acc[0] = __builtin_fmaf(v, static_cast<float>(w & 0xffu), acc[0]);
+    acc[1] = __builtin_fmaf(v, static_cast<float>((w >> 8) & 0xffu), acc[1]);
+    acc[2] = __builtin_fmaf(v, static_cast<float>((w >> 16) & 0xffu), acc[2]);
+    acc[3] = __builtin_fmaf(v, static_cast<float>(w >> 24), acc[3]);
+}
+
+template <int VEC_, bool SIGNED> struct FeatQ8;
 template <bool SIGNED> struct FeatQ8<4, SIGNED> {
+    static constexpr int VEC = 4;
+    static constexpr int kBias = SIGNED ? 128 : 0;
     using elem_t = int8_t;
     using raw_t = uint32_t;
     static __device__ inline raw_t load(const elem_t *p) { return *reinterpret_cast<const uint32_t *>(p); }
-    static __device__ inline float cvt(uint32_t w, int byte)
-    {
-        if (SIGNED) return static_cast<float>(static_cast<int8_t>((w >> (8 * byte)) & 0xffu));
-        return static_cast<float>((w >> (8 * byte)) & 0xffu);
-    }
-    static __device__ inline void fma(float (&acc)[4], float v, const raw_t &x)
-    {
-        acc[0] = __builtin_fmaf(v, cvt(x, 0), acc[0]);
-        acc[1] = __builtin_fmaf(v, cvt(x, 1), acc[1]);
-        acc[2] = __builtin_fmaf(v, cvt(x, 2), acc[2]);
-        acc[3] = __builtin_fmaf(v, cvt(x, 3), acc[3]);
-    }
+    static __device__ inline void fma(float (&acc)[4], float v, const raw_t &x) { fma_bytes<SIGNED>(acc, v, x); }
 };
 template <bool SIGNED> struct FeatQ8<1, SIGNED> {
+    static constexpr int VEC = 1;
+    static constexpr int kBias = 0;
     using elem_t = int8_t;
     using raw_t = int8_t;
     static __device__ inline raw_t load(const elem_t *p) { return *p; }
@@ -102,15 +114,17 @@ __device__ inline void wave_lds_sync()
 
 // ---- the kernel ---------------------------------------------------------------
 // LPR   lanes per output row (8, 16, 32 or 64); a wavefront holds 64/LPR rows
-// VEC   features per lane per chunk (4 on the aligned fast path, 1 otherwise)
-// Feat  feature loader; QMODE see above; QUANT: apply the 8-bit epilogue
-template <int LPR, int VEC, int UNROLL, typename Feat, int QMODE, bool QUANT>
+// Feat  feature loader: Feat::VEC features per lane per chunk (4 on the aligned
+//       fast paths, 1 otherwise)
+// QMODE see above; QUANT: apply the 8-bit epilogue
+template <int LPR, int UNROLL, typename Feat, int QMODE, bool QUANT>
 __global__ void __launch_bounds__(kBlock)
 spmm_rows_kernel(int64_t n_rows, const int64_t *__restrict__ s_rowptr, const int32_t *__restrict__ s_col,
                  const float *__restrict__ s_val, const int32_t *__restrict__ row_perm,
                  const typename Feat::elem_t *__restrict__ X, int64_t ldx, int32_t F, QParams qp,
                  float *__restrict__ Y, int64_t ldy)
 {
+    constexpr int VEC = Feat::VEC;
     constexpr int kGroups = kWave / LPR;                 // rows per wavefront
     constexpr int kRowsPerBlock = kGroups * aes::kWavesPerBlock;
     constexpr int kStride = kTile + 1;                   // +1 slot: groups start in different LDS banks
@@ -133,6 +147,7 @@ spmm_rows_kernel(int64_t n_rows, const int64_t *__restrict__ s_rowptr, const int
 #pragma unroll
         for (int i = 0; i < VEC; ++i) acc[i] = 0.0f;
         float side = 0.0f;      // this lane's share of sum(val * zero-point weight), see epilogue
+        float vsum = 0.0f;      // sum of the staged edge values (only when the loader is biased)
 
         for (int64_t t0 = 0; t0 < n_slots; t0 += kTile) {
             const int m = static_cast<int>(n_slots - t0 < kTile ? n_slots - t0 : kTile);
@@ -155,6 +170,7 @@ spmm_rows_kernel(int64_t n_rows, const int64_t *__restrict__ s_rowptr, const int
             }
             wave_lds_sync();                             // tile visible to the whole group
             if (lane_on) {
+                // UNROLL gathers are issued back to back before the first one is consumed.
                 int k = 0;
                 for (; k + UNROLL <= m; k += UNROLL) {
                     int2 cv[UNROLL];
@@ -164,16 +180,36 @@ spmm_rows_kernel(int64_t n_rows, const int64_t *__restrict__ s_rowptr, const int
 #pragma unroll
                     for (int u = 0; u < UNROLL; ++u) x[u] = Feat::load(X + static_cast<int64_t>(cv[u].x) * ldx + f);
 #pragma unroll
-                    for (int u = 0; u < UNROLL; ++u) Feat::fma(acc, __int_as_float(cv[u].y), x[u]);
+                    for (int u = 0; u < UNROLL; ++u) {
+                        Feat::fma(acc, __int_as_float(cv[u].y), x[u]);
+                        if (Feat::kBias != 0) vsum += __int_as_float(cv[u].y);
+                    }
                 }
-                for (; k < m; ++k) {
-                    const int2 cv = my_stage[k];
-                    const typename Feat::raw_t x = Feat::load(X + static_cast<int64_t>(cv.x) * ldx + f);
-                    Feat::fma(acc, __int_as_float(cv.y), x);
+                // Ragged last round: the missing slots are predicated off (value 0, no load), so
+                // short rows and row tails keep their gathers in flight together as well.
+                if (k < m) {
+                    int2 cv[UNROLL];
+                    typename Feat::raw_t x[UNROLL];
+#pragma unroll
+                    for (int u = 0; u < UNROLL; ++u) cv[u] = (k + u < m) ? my_stage[k + u] : make_int2(-1, 0);
+#pragma unroll
+                    for (int u = 0; u < UNROLL; ++u) {
+                        x[u] = typename Feat::raw_t{};
+                        if (cv[u].x >= 0) x[u] = Feat::load(X + static_cast<int64_t>(cv[u].x) * ldx + f);
+                    }
+#pragma unroll
+                    for (int u = 0; u < UNROLL; ++u) {
+                        Feat::fma(acc, __int_as_float(cv[u].y), x[u]);
+                        if (Feat::kBias != 0) vsum += __int_as_float(cv[u].y);
+                    }
                 }
             }
         }
 
+        if (Feat::kBias != 0) {
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) acc[i] = __builtin_fmaf(-static_cast<float>(Feat::kBias), vsum, acc[i]);
+        }
         if (QUANT) {
             // x_hat = q*scale_g + zero_g, with the group constants taken out of the sum:
             //   per tensor / column: Y = scale_c * sum(v*q) + zero_c * sum(v)
@@ -197,8 +233,10 @@ spmm_rows_kernel(int64_t n_rows, const int64_t *__restrict__ s_rowptr, const int
         }
         if (lane_on) {
             float *y = Y + r * ldy + f;
-            if (VEC == 4) {
-                *reinterpret_cast<float4 *>(y) = make_float4(acc[0], acc[1 % VEC], acc[2 % VEC], acc[3 % VEC]);
+            if constexpr (VEC % 4 == 0) {
+#pragma unroll
+                for (int i = 0; i < VEC; i += 4)
+                    *reinterpret_cast<float4 *>(y + i) = make_float4(acc[i], acc[i + 1], acc[i + 2], acc[i + 3]);
             } else {
 #pragma unroll
                 for (int i = 0; i < VEC; ++i) y[i] = acc[i];
@@ -207,7 +245,7 @@ spmm_rows_kernel(int64_t n_rows, const int64_t *__restrict__ s_rowptr, const int
     }
 }
 
-template <int LPR, int VEC, int UNROLL, typename Feat, int QMODE, bool QUANT>
+template <int LPR, int UNROLL, typename Feat, int QMODE, bool QUANT>
 int launch_rows(int64_t n_rows, const int64_t *s_rowptr, const int32_t *s_col, const float *s_val,
                 const int32_t *row_perm, const typename Feat::elem_t *X, int64_t ldx, int32_t F, QParams qp,
                 float *Y, int64_t ldy, hipStream_t stream, const char *what)
@@ -215,41 +253,52 @@ int launch_rows(int64_t n_rows, const int64_t *s_rowptr, const int32_t *s_col, c
     constexpr int kRowsPerBlock = (kWave / LPR) * aes::kWavesPerBlock;
     const int64_t grid = aes::ceil_div(n_rows, kRowsPerBlock);
     if (grid > INT32_MAX) return aes::fail(AES_ERR_UNSUPPORTED, "%s: n_rows=%lld too large", what, (long long)n_rows);
-    spmm_rows_kernel<LPR, VEC, UNROLL, Feat, QMODE, QUANT>
+    spmm_rows_kernel<LPR, UNROLL, Feat, QMODE, QUANT>
         <<<dim3(static_cast<unsigned>(grid)), dim3(kBlock), 0, stream>>>(n_rows, s_rowptr, s_col, s_val, row_perm,
                                                                            X, ldx, F, qp, Y, ldy);
     return aes::check_launch(what);
 }
 
-// Lanes per row for the 4-features-per-lane path.
-int lanes_per_row(int32_t F)
+// Lanes per row when every lane owns `vec` consecutive features.
+int lanes_per_row(int32_t F, int vec)
 {
-    int l = aes::pow2_ceil(aes::ceil_div(F, 4));
+    int l = aes::pow2_ceil(aes::ceil_div(F, vec));
     return l < 8 ? 8 : l > 64 ? 64 : l;
 }
 
-template <typename FeatVec, typename FeatScalar, int QMODE, bool QUANT>
-int dispatch(bool fast, int64_t n_rows, const int64_t *s_rowptr, const int32_t *s_col, const float *s_val,
-             const int32_t *row_perm, const typename FeatVec::elem_t *X, int64_t ldx, int32_t F, QParams qp,
-             float *Y, int64_t ldy, hipStream_t stream, const char *what)
+// Vector path: pick the lane-group width from F.
+template <typename Feat, int QMODE, bool QUANT>
+int dispatch_lanes(int64_t n_rows, const int64_t *s_rowptr, const int32_t *s_col, const float *s_val,
+                   const int32_t *row_perm, const typename Feat::elem_t *X, int64_t ldx, int32_t F, QParams qp,
+                   float *Y, int64_t ldy, hipStream_t stream, const char *what)
 {
-    if (!fast)
-        return launch_rows<64, 1, 4, FeatScalar, QMODE, QUANT>(n_rows, s_rowptr, s_col, s_val, row_perm, X, ldx, F,
-                                                                qp, Y, ldy, stream, what);
-    switch (lanes_per_row(F)) {
+    switch (lanes_per_row(F, Feat::VEC)) {
         case 8:
-            return launch_rows<8, 4, 8, FeatVec, QMODE, QUANT>(n_rows, s_rowptr, s_col, s_val, row_perm, X, ldx, F, qp,
-                                                                Y, ldy, stream, what);
+            return launch_rows<8, 8, Feat, QMODE, QUANT>(n_rows, s_rowptr, s_col, s_val, row_perm, X, ldx, F, qp, Y, ldy,
+                                                         stream, what);
         case 16:
-            return launch_rows<16, 4, 8, FeatVec, QMODE, QUANT>(n_rows, s_rowptr, s_col, s_val, row_perm, X, ldx, F, qp,
-                                                                 Y, ldy, stream, what);
+            return launch_rows<16, 8, Feat, QMODE, QUANT>(n_rows, s_rowptr, s_col, s_val, row_perm, X, ldx, F, qp, Y, ldy,
+                                                          stream, what);
         case 32:
-            return launch_rows<32, 4, 8, FeatVec, QMODE, QUANT>(n_rows, s_rowptr, s_col, s_val, row_perm, X, ldx, F, qp,
-                                                                 Y, ldy, stream, what);
+            return launch_rows<32, 8, Feat, QMODE, QUANT>(n_rows, s_rowptr, s_col, s_val, row_perm, X, ldx, F, qp, Y, ldy,
+                                                          stream, what);
         default:
-            return launch_rows<64, 4, 8, FeatVec, QMODE, QUANT>(n_rows, s_rowptr, s_col, s_val, row_perm, X, ldx, F, qp,
-                                                                 Y, ldy, stream, what);
+            return launch_rows<64, 8, Feat, QMODE, QUANT>(n_rows, s_rowptr, s_col, s_val, row_perm, X, ldx, F, qp, Y, ldy,
+                                                          stream, what);
     }
+}
+
+// 8-bit features: 4 codes per lane when rows are 4-byte aligned, else element-wise.
+template <bool SIGNED, int QMODE>
+int dispatch_q8(int vec, int64_t n_rows, const int64_t *s_rowptr, const int32_t *s_col, const float *s_val,
+                const int32_t *row_perm, const int8_t *Xq, int64_t ldq, int32_t F, QParams qp, float *Y, int64_t ldy,
+                hipStream_t stream, const char *what)
+{
+    if (vec == 4)
+        return dispatch_lanes<FeatQ8<4, SIGNED>, QMODE, true>(n_rows, s_rowptr, s_col, s_val, row_perm, Xq, ldq, F, qp,
+                                                              Y, ldy, stream, what);
+    return launch_rows<64, 4, FeatQ8<1, SIGNED>, QMODE, true>(n_rows, s_rowptr, s_col, s_val, row_perm, Xq, ldq, F, qp,
+                                                              Y, ldy, stream, what);
 }
 
 int check_common(const char *what, int64_t n_rows, int64_t n_cols, const int64_t *s_rowptr, const int32_t *s_col,
@@ -276,15 +325,19 @@ extern "C" int aes_spmm_f32(int64_t n_rows, int64_t n_cols,
                             const int64_t *s_rowptr, const int32_t *s_col, const float *s_val,
                             const int32_t *row_perm,
                             const float *X, int64_t ldx, int32_t F,
-                            float *Y, int64_t ldy, void *stream)
+                            float *Y, int64_t ldy, void *stream_)
 {
     const char *what = "aes_spmm_f32";
     if (int rc = check_common(what, n_rows, n_cols, s_rowptr, s_col, s_val, X, ldx, F, Y, ldy)) return rc;
     if (n_rows == 0) return AES_OK;
     const bool fast = aes::aligned(X, 16) && aes::aligned(Y, 16) && F % 4 == 0 && ldx % 4 == 0 && ldy % 4 == 0;
     QParams qp = {nullptr, nullptr, 0, 0};
-    return dispatch<FeatF32<4>, FeatF32<1>, kQNone, false>(fast, n_rows, s_rowptr, s_col, s_val, row_perm, X, ldx, F,
-                                                           qp, Y, ldy, static_cast<hipStream_t>(stream), what);
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    if (fast)
+        return dispatch_lanes<FeatF32<4>, kQNone, false>(n_rows, s_rowptr, s_col, s_val, row_perm, X, ldx, F, qp, Y,
+                                                         ldy, stream, what);
+    return launch_rows<64, 4, FeatF32<1>, kQNone, false>(n_rows, s_rowptr, s_col, s_val, row_perm, X, ldx, F, qp, Y, ldy,
+                                                         stream, what);
 }
 
 extern "C" int aes_spmm_q8(int64_t n_rows, int64_t n_cols,
@@ -306,19 +359,19 @@ extern "C" int aes_spmm_q8(int64_t n_rows, int64_t n_cols,
     if (affine && zero == nullptr) return aes::fail(AES_ERR_INVALID_ARG, "%s: zero is NULL for the affine scheme", what);
     if (n_rows == 0) return AES_OK;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
-    const bool fast = aes::aligned(Xq, 4) && aes::aligned(Y, 16) && F % 4 == 0 && ldq % 4 == 0 && ldy % 4 == 0;
+    const bool fast = aes::aligned(Y, 16) && ldy % 4 == 0 && aes::aligned(Xq, 4) && F % 4 == 0 && ldq % 4 == 0;
+    const int vec = fast ? 4 : 1;
     QParams qp = {scale, zero, granularity, affine ? 1 : 0};
     const bool per_row = granularity == AES_Q_PER_ROW;
     if (affine) {
         if (per_row)
-            return dispatch<FeatQ8<4, false>, FeatQ8<1, false>, kQRowScale, true>(
-                fast, n_rows, s_rowptr, s_col, s_val, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
-        return dispatch<FeatQ8<4, false>, FeatQ8<1, false>, kQNone, true>(fast, n_rows, s_rowptr, s_col, s_val, row_perm,
-                                                                          Xq, ldq, F, qp, Y, ldy, stream, what);
+            return dispatch_q8<false, kQRowScale>(vec, n_rows, s_rowptr, s_col, s_val, row_perm, Xq, ldq, F, qp, Y, ldy,
+                                                  stream, what);
+        return dispatch_q8<false, kQNone>(vec, n_rows, s_rowptr, s_col, s_val, row_perm, Xq, ldq, F, qp, Y, ldy, stream,
+                                          what);
     }
     if (per_row)
-        return dispatch<FeatQ8<4, true>, FeatQ8<1, true>, kQRowScale, true>(fast, n_rows, s_rowptr, s_col, s_val, row_perm,
-                                                                            Xq, ldq, F, qp, Y, ldy, stream, what);
-    return dispatch<FeatQ8<4, true>, FeatQ8<1, true>, kQNone, true>(fast, n_rows, s_rowptr, s_col, s_val, row_perm, Xq,
-                                                                    ldq, F, qp, Y, ldy, stream, what);
+        return dispatch_q8<true, kQRowScale>(vec, n_rows, s_rowptr, s_col, s_val, row_perm, Xq, ldq, F, qp, Y, ldy,
+                                             stream, what);
+    return dispatch_q8<true, kQNone>(vec, n_rows, s_rowptr, s_col, s_val, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
 }
