@@ -64,6 +64,14 @@ typedef enum aes_q_scheme {
     AES_Q_SYMMETRIC_RNE_I8 = 1
 } aes_q_scheme;
 
+/* How a row with more than W entries is sampled (Sec. 3.3). */
+typedef enum aes_strategy {
+    AES_STRATEGY_ADAPTIVE = 0, /* Table 1: (N, sample_cnt) from R = row_nnz / W    */
+    AES_STRATEGY_AFS = 1,      /* N = 1, sample_cnt = W: fine-grained, the paper's  */
+                               /* description of ES-SpMM's accuracy-first strategy  */
+    AES_STRATEGY_SFS = 2       /* N = W, sample_cnt = 1: coarse-grained, speed-first */
+} aes_strategy;
+
 enum { AES_MAX_W = 1 << 20 };
 
 /* Message of the calling thread's last failing call ("" if none). */
@@ -106,6 +114,8 @@ size_t aes_sample_workspace_bytes(int64_t n_rows);
  *   val      [dev]  nnz float32
  *   W               sampling width, 0 or 1..AES_MAX_W (any integer)
  *   seed            see above
+ *   strategy        aes_strategy; ADAPTIVE is the paper's method, AFS / SFS
+ *                   replace Table 1 by the fixed (N, sample_cnt) named there
  *   s_rowptr [dev]  out, n_rows+1 int64
  *   s_col    [dev]  out, aes_sample_capacity() int32
  *   s_val    [dev]  out, same count, float32 (bit copies of val)
@@ -119,7 +129,7 @@ size_t aes_sample_workspace_bytes(int64_t n_rows);
  */
 int aes_sample_build(int64_t n_rows, int64_t n_cols, int64_t nnz,
                      const int64_t *rowptr, const int32_t *colidx, const float *val,
-                     int32_t W, uint64_t seed,
+                     int32_t W, uint64_t seed, int32_t strategy,
                      int64_t *s_rowptr, int32_t *s_col, float *s_val, int64_t *s_eid,
                      int32_t *row_perm,
                      void *workspace, size_t workspace_bytes, void *stream);
@@ -180,6 +190,22 @@ int aes_quantize_features(int64_t n, int32_t F, const float *X, int64_t ldx,
                           int8_t *Xq, int64_t ldq, float *scale, float *zero,
                           void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Sec. 2.3 Eq. 2 as a stand-alone pass, where the paper places it (after the
+ * 8-bit features have been loaded, before the SpMM): X[i, c] = q*scale_g +
+ * zero_g (AFFINE_FLOOR_U8) or q*scale_g (SYMMETRIC_RNE_I8); multiply, then add,
+ * in binary32, so the result is bit-reproducible.  aes_spmm_q8 makes this pass
+ * unnecessary; it exists to measure what the fusion saves.
+ *
+ *   Xq [dev] n x F bytes (ldq); scale, zero [dev] as written by
+ *   aes_quantize_features (zero may be NULL for SYMMETRIC_RNE_I8);
+ *   X [dev] out, n x F float32 (ldx)
+ */
+int aes_dequantize_features(int64_t n, int32_t F, const int8_t *Xq, int64_t ldq,
+                            int32_t scheme, int32_t granularity,
+                            const float *scale, const float *zero,
+                            float *X, int64_t ldx, void *stream);
+
 /* ------------------------------------------------------------------------- */
 /* Multiply stage with the dequantisation of Eq. 2 fused into the gather       */
 
@@ -205,6 +231,31 @@ int aes_spmm_q8(int64_t n_rows, int64_t n_cols,
                 int32_t scheme, int32_t granularity,
                 const float *scale, const float *zero,
                 float *Y, int64_t ldy, void *stream);
+
+/* ------------------------------------------------------------------------- */
+/* Algorithm 1 as one kernel: sample each row on the fly, then multiply        */
+
+/*
+ * Same result as aes_sample_build followed by aes_spmm_f32 / aes_spmm_q8 (bit
+ * for bit: same slots, same summation order), without materialising the plan:
+ * each lane group evaluates Table 1 and Eq. 3 for its row and stages the
+ * sampled (col, val) pairs straight from the CSR arrays into LDS - the single
+ * kernel shape of Sec. 3.2.  Saves the plan's write and read when a plan would
+ * be used once.  Arguments as in the calls named above.
+ */
+int aes_spmm_fused_f32(int64_t n_rows, int64_t n_cols,
+                       const int64_t *rowptr, const int32_t *colidx, const float *val,
+                       int32_t W, uint64_t seed, int32_t strategy,
+                       const float *X, int64_t ldx, int32_t F,
+                       float *Y, int64_t ldy, void *stream);
+
+int aes_spmm_fused_q8(int64_t n_rows, int64_t n_cols,
+                      const int64_t *rowptr, const int32_t *colidx, const float *val,
+                      int32_t W, uint64_t seed, int32_t strategy,
+                      const int8_t *Xq, int64_t ldq, int32_t F,
+                      int32_t scheme, int32_t granularity,
+                      const float *scale, const float *zero,
+                      float *Y, int64_t ldy, void *stream);
 
 #ifdef __cplusplus
 }

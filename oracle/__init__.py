@@ -18,6 +18,7 @@ _LIB = os.path.join(_HERE, "libaes_oracle.so")
 
 Q_PER_TENSOR, Q_PER_COLUMN, Q_PER_ROW = 0, 1, 2
 Q_AFFINE_FLOOR_U8, Q_SYMMETRIC_RNE_I8 = 0, 1
+STRATEGY_ADAPTIVE, STRATEGY_AFS, STRATEGY_SFS = 0, 1, 2
 
 _lib = None
 
@@ -40,16 +41,17 @@ def _load():
         lib.orc_num_threads.restype = i32
         lib.orc_set_num_threads.argtypes = [i32]
         lib.orc_strategy.argtypes = [i64, i64, vp, vp]
+        lib.orc_strategy_mode.argtypes = [i64, i64, i32, vp, vp]
         lib.orc_row_offset.argtypes = [u64, i64]
         lib.orc_row_offset.restype = ctypes.c_uint32
         lib.orc_hash.argtypes = [u64, i64, i64]
         lib.orc_hash.restype = i64
-        lib.orc_row_slots.argtypes = [i64, i64]
+        lib.orc_row_slots.argtypes = [i64, i64, i32]
         lib.orc_row_slots.restype = i64
-        lib.orc_sample_rowptr.argtypes = [i64, vp, i64, vp]
-        lib.orc_sample_build.argtypes = [i64, vp, vp, vp, i64, u64, vp, vp, vp, vp]
+        lib.orc_sample_rowptr.argtypes = [i64, vp, i64, i32, vp]
+        lib.orc_sample_build.argtypes = [i64, vp, vp, vp, i64, u64, i32, vp, vp, vp, vp]
         lib.orc_spmm_plan.argtypes = [i64, vp, vp, vp, vp, vp, i64, i64, vp, vp, i64]
-        lib.orc_aes_spmm.argtypes = [i64, vp, vp, vp, vp, i64, u64, vp, i64, i64, vp, vp, i64]
+        lib.orc_aes_spmm.argtypes = [i64, vp, vp, vp, vp, i64, u64, i32, vp, i64, i64, vp, vp, i64]
         lib.orc_aes_spmm.restype = i32
         lib.orc_quantize.argtypes = [i64, i64, vp, i64, i32, i32, vp, i64, vp, vp]
         lib.orc_quantize.restype = i32
@@ -76,11 +78,14 @@ def set_num_threads(n: int) -> None:
     _load().orc_set_num_threads(int(n))
 
 
-def strategy(row_nnz: int, W: int):
-    """(N, sample_cnt) of Table 1."""
+def strategy(row_nnz: int, W: int, mode: int = STRATEGY_ADAPTIVE):
+    """(N, sample_cnt): Table 1 (mode 0) or the fixed AFS / SFS granularities."""
     n = ctypes.c_int64()
     c = ctypes.c_int64()
-    _load().orc_strategy(int(row_nnz), int(W), ctypes.addressof(n), ctypes.addressof(c))
+    if mode == STRATEGY_ADAPTIVE:
+        _load().orc_strategy(int(row_nnz), int(W), ctypes.addressof(n), ctypes.addressof(c))
+    else:
+        _load().orc_strategy_mode(int(row_nnz), int(W), int(mode), ctypes.addressof(n), ctypes.addressof(c))
     return int(n.value), int(c.value)
 
 
@@ -93,11 +98,12 @@ def hash_start(current_ind: int, row_nnz: int, N: int) -> int:
     return int(_load().orc_hash(int(current_ind), int(row_nnz), int(N)))
 
 
-def row_slots(row_nnz: int, W: int) -> int:
-    return int(_load().orc_row_slots(int(row_nnz), int(W)))
+def row_slots(row_nnz: int, W: int, mode: int = STRATEGY_ADAPTIVE) -> int:
+    return int(_load().orc_row_slots(int(row_nnz), int(W), int(mode)))
 
 
-def sample_build(rowptr, colidx, val, W: int, seed: int = 0, want_eid: bool = True):
+def sample_build(rowptr, colidx, val, W: int, seed: int = 0, want_eid: bool = True,
+                 mode: int = STRATEGY_ADAPTIVE):
     """Materialised sampled matrix.  Returns (s_rowptr, s_col, s_val, s_eid)."""
     lib = _load()
     rowptr = _c(rowptr, np.int64)
@@ -105,12 +111,12 @@ def sample_build(rowptr, colidx, val, W: int, seed: int = 0, want_eid: bool = Tr
     val = _c(val, np.float32)
     n = rowptr.shape[0] - 1
     s_rowptr = np.empty(n + 1, dtype=np.int64)
-    lib.orc_sample_rowptr(n, _p(rowptr), int(W), _p(s_rowptr))
+    lib.orc_sample_rowptr(n, _p(rowptr), int(W), int(mode), _p(s_rowptr))
     S = int(s_rowptr[n])
     s_col = np.empty(S, dtype=np.int32)
     s_val = np.empty(S, dtype=np.float32)
     s_eid = np.empty(S, dtype=np.int64) if want_eid else None
-    lib.orc_sample_build(n, _p(rowptr), _p(colidx), _p(val), int(W), int(seed),
+    lib.orc_sample_build(n, _p(rowptr), _p(colidx), _p(val), int(W), int(seed), int(mode),
                          _p(s_rowptr), _p(s_col), _p(s_val), _p(s_eid))
     return s_rowptr, s_col, s_val, s_eid
 
@@ -136,7 +142,8 @@ def spmm_plan(s_rowptr, s_col, s_val, X, rows=None, want_abs: bool = False):
     return (Y, Yabs) if want_abs else Y
 
 
-def aes_spmm(rowptr, colidx, val, W: int, X, seed: int = 0, rows=None, want_abs: bool = False):
+def aes_spmm(rowptr, colidx, val, W: int, X, seed: int = 0, rows=None, want_abs: bool = False,
+             mode: int = STRATEGY_ADAPTIVE):
     """Algorithm 1 in one pass from the CSR.  W <= 0: exact SpMM."""
     lib = _load()
     rowptr = _c(rowptr, np.int64)
@@ -152,7 +159,7 @@ def aes_spmm(rowptr, colidx, val, W: int, X, seed: int = 0, rows=None, want_abs:
         n = rowptr.shape[0] - 1
     Y = np.empty((n, F), dtype=np.float64)
     Yabs = np.empty((n, F), dtype=np.float64) if want_abs else None
-    rc = lib.orc_aes_spmm(n, _p(rows), _p(rowptr), _p(colidx), _p(val), int(W), int(seed),
+    rc = lib.orc_aes_spmm(n, _p(rows), _p(rowptr), _p(colidx), _p(val), int(W), int(seed), int(mode),
                           _p(X), ldx, F, _p(Y), _p(Yabs), F)
     if rc != 0:
         raise MemoryError("oracle scratch allocation failed")

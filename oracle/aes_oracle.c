@@ -101,6 +101,26 @@ void orc_strategy(int64_t row_nnz, int64_t sh_width, int64_t *N, int64_t *sample
     *sample_cnt = c;
 }
 
+/*
+ * Sec. 3.3, paragraph before Table 1: the two fixed granularities the paper
+ * compares against.  mode 0: Table 1 (the method).  mode 1, "AFS": N = 1 and
+ * sample_cnt = W.  mode 2, "SFS": N = W and one sample.  Rows that fit are
+ * kept whole in every mode.  (These follow the paper's description of the
+ * strategies; the other system's own code is not available.)
+ */
+void orc_strategy_mode(int64_t row_nnz, int64_t sh_width, int mode, int64_t *N, int64_t *sample_cnt)
+{
+    if (mode == 0 || row_nnz <= sh_width) {
+        orc_strategy(row_nnz, sh_width, N, sample_cnt);
+    } else if (mode == 1) {
+        *N = 1;
+        *sample_cnt = sh_width;
+    } else {
+        *N = sh_width;
+        *sample_cnt = 1;
+    }
+}
+
 /* Per-row offset added to current_ind.  Not in the paper; zero at seed 0. */
 uint32_t orc_row_offset(uint64_t seed, int64_t rid)
 {
@@ -117,10 +137,10 @@ int64_t orc_hash(uint64_t current_ind, int64_t row_nnz, int64_t N)
 }
 
 /* Number of slots row `rid` owns. */
-int64_t orc_row_slots(int64_t row_nnz, int64_t sh_width)
+int64_t orc_row_slots(int64_t row_nnz, int64_t sh_width, int mode)
 {
     int64_t N, sample_cnt;
-    orc_strategy(row_nnz, sh_width, &N, &sample_cnt);
+    orc_strategy_mode(row_nnz, sh_width, mode, &N, &sample_cnt);
     return N * sample_cnt;
 }
 
@@ -130,14 +150,14 @@ int64_t orc_row_slots(int64_t row_nnz, int64_t sh_width)
  * slots.  sh_width <= 0 means "no sampling": every element, in order.
  */
 static int64_t sample_row(int64_t rid, const int64_t *row_ptr, const int32_t *col_ind,
-                          const float *val, int64_t sh_width, uint64_t seed,
+                          const float *val, int64_t sh_width, uint64_t seed, int mode,
                           int32_t *sh_col, float *sh_val, int64_t *sh_eid)
 {
     int64_t row_begin = row_ptr[rid];
     int64_t row_nnz = row_ptr[rid + 1] - row_begin;
     if (sh_width <= 0) sh_width = row_nnz;          /* exact path */
     int64_t N, sample_cnt;
-    orc_strategy(row_nnz, sh_width, &N, &sample_cnt);
+    orc_strategy_mode(row_nnz, sh_width, mode, &N, &sample_cnt);
     uint32_t s_r = orc_row_offset(seed, rid);
     for (int64_t i = 0; i < sample_cnt; ++i) {
         int64_t inc = 0;
@@ -154,14 +174,14 @@ static int64_t sample_row(int64_t rid, const int64_t *row_ptr, const int32_t *co
 }
 
 /* s_rowptr[r] = number of slots of all rows before r (n_rows + 1 entries). */
-void orc_sample_rowptr(int64_t n_rows, const int64_t *row_ptr, int64_t sh_width,
+void orc_sample_rowptr(int64_t n_rows, const int64_t *row_ptr, int64_t sh_width, int mode,
                        int64_t *s_rowptr)
 {
     int64_t acc = 0;
     for (int64_t r = 0; r < n_rows; ++r) {
         s_rowptr[r] = acc;
         int64_t row_nnz = row_ptr[r + 1] - row_ptr[r];
-        acc += orc_row_slots(row_nnz, sh_width <= 0 ? row_nnz : sh_width);
+        acc += orc_row_slots(row_nnz, sh_width <= 0 ? row_nnz : sh_width, mode);
     }
     s_rowptr[n_rows] = acc;
 }
@@ -171,13 +191,13 @@ void orc_sample_rowptr(int64_t n_rows, const int64_t *row_ptr, int64_t sh_width,
  * s_rowptr must have been filled by orc_sample_rowptr.  s_eid may be NULL.
  */
 void orc_sample_build(int64_t n_rows, const int64_t *row_ptr, const int32_t *col_ind,
-                      const float *val, int64_t sh_width, uint64_t seed,
+                      const float *val, int64_t sh_width, uint64_t seed, int mode,
                       const int64_t *s_rowptr, int32_t *s_col, float *s_val, int64_t *s_eid)
 {
 #pragma omp parallel for schedule(dynamic, 256)
     for (int64_t r = 0; r < n_rows; ++r) {
         int64_t o = s_rowptr[r];
-        sample_row(r, row_ptr, col_ind, val, sh_width, seed, s_col + o, s_val + o,
+        sample_row(r, row_ptr, col_ind, val, sh_width, seed, mode, s_col + o, s_val + o,
                    s_eid ? s_eid + o : NULL);
     }
 }
@@ -219,7 +239,7 @@ void orc_spmm_plan(int64_t n_rows, const int64_t *rows, const int64_t *s_rowptr,
  * Returns 0, or -1 if scratch memory could not be obtained.
  */
 int orc_aes_spmm(int64_t n_rows, const int64_t *rows, const int64_t *row_ptr,
-                 const int32_t *col_ind, const float *val, int64_t sh_width, uint64_t seed,
+                 const int32_t *col_ind, const float *val, int64_t sh_width, uint64_t seed, int mode,
                  const float *X, int64_t ldx, int64_t F, double *Y, double *Yabs, int64_t ldy)
 {
     int failed = 0;
@@ -241,7 +261,7 @@ int orc_aes_spmm(int64_t n_rows, const int64_t *rows, const int64_t *row_ptr,
                 sh_val = (float *)malloc((size_t)cap * sizeof(float));
                 if (!sh_col || !sh_val) { cap = 0; failed = 1; continue; }
             }
-            int64_t W = sample_row(r, row_ptr, col_ind, val, sh_width, seed, sh_col, sh_val, NULL);
+            int64_t W = sample_row(r, row_ptr, col_ind, val, sh_width, seed, mode, sh_col, sh_val, NULL);
             double *y = Y + t * ldy;
             double *ya = Yabs ? Yabs + t * ldy : NULL;
             for (int64_t c = 0; c < F; ++c) {

@@ -12,8 +12,12 @@ from .binding import (  # noqa: F401
     AES_Q_PER_ROW,
     AES_Q_PER_TENSOR,
     AES_Q_SYMMETRIC_RNE_I8,
+    AES_STRATEGY_ADAPTIVE,
+    AES_STRATEGY_AFS,
+    AES_STRATEGY_SFS,
     AesError,
     Plan,
+    aes_dequantize_features,
     aes_last_error,
     aes_quantize_features,
     aes_quantize_workspace_bytes,
@@ -21,6 +25,8 @@ from .binding import (  # noqa: F401
     aes_sample_capacity,
     aes_sample_workspace_bytes,
     aes_spmm_f32,
+    aes_spmm_fused_f32,
+    aes_spmm_fused_q8,
     aes_spmm_q8,
     library,
 )

@@ -12,6 +12,7 @@ from . import build as _build
 AES_OK, AES_ERR_INVALID_ARG, AES_ERR_UNSUPPORTED, AES_ERR_WORKSPACE, AES_ERR_HIP = 0, -1, -2, -3, -4
 AES_Q_PER_TENSOR, AES_Q_PER_COLUMN, AES_Q_PER_ROW = 0, 1, 2
 AES_Q_AFFINE_FLOOR_U8, AES_Q_SYMMETRIC_RNE_I8 = 0, 1
+AES_STRATEGY_ADAPTIVE, AES_STRATEGY_AFS, AES_STRATEGY_SFS = 0, 1, 2
 
 _i64, _i32, _u64, _vp, _sz = ctypes.c_int64, ctypes.c_int32, ctypes.c_uint64, ctypes.c_void_p, ctypes.c_size_t
 
@@ -20,11 +21,16 @@ SIGNATURES = {
     "aes_last_error": (ctypes.c_char_p, []),
     "aes_sample_capacity": (_i64, [_i64, _i64, _i32]),
     "aes_sample_workspace_bytes": (_sz, [_i64]),
-    "aes_sample_build": (ctypes.c_int, [_i64, _i64, _i64, _vp, _vp, _vp, _i32, _u64, _vp, _vp, _vp, _vp, _vp,
+    "aes_sample_build": (ctypes.c_int, [_i64, _i64, _i64, _vp, _vp, _vp, _i32, _u64, _i32, _vp, _vp, _vp, _vp, _vp,
                                         _vp, _sz, _vp]),
+    "aes_spmm_fused_f32": (ctypes.c_int, [_i64, _i64, _vp, _vp, _vp, _i32, _u64, _i32, _vp, _i64, _i32, _vp, _i64,
+                                          _vp]),
+    "aes_spmm_fused_q8": (ctypes.c_int, [_i64, _i64, _vp, _vp, _vp, _i32, _u64, _i32, _vp, _i64, _i32, _i32, _i32,
+                                         _vp, _vp, _vp, _i64, _vp]),
     "aes_spmm_f32": (ctypes.c_int, [_i64, _i64, _vp, _vp, _vp, _vp, _vp, _i64, _i32, _vp, _i64, _vp]),
     "aes_quantize_workspace_bytes": (_sz, [_i64, _i32, _i32]),
     "aes_quantize_features": (ctypes.c_int, [_i64, _i32, _vp, _i64, _i32, _i32, _vp, _i64, _vp, _vp, _vp, _sz, _vp]),
+    "aes_dequantize_features": (ctypes.c_int, [_i64, _i32, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _i64, _vp]),
     "aes_spmm_q8": (ctypes.c_int, [_i64, _i64, _vp, _vp, _vp, _vp, _vp, _i64, _i32, _i32, _i32, _vp, _vp, _vp,
                                    _i64, _vp]),
 }
@@ -118,7 +124,8 @@ def aes_quantize_workspace_bytes(n: int, F: int, granularity: int) -> int:
     return int(library().aes_quantize_workspace_bytes(n, F, granularity))
 
 
-def aes_sample_build(rowptr, colidx, val, n_cols: int, W: int, seed: int = 0, *, want_eid: bool = False,
+def aes_sample_build(rowptr, colidx, val, n_cols: int, W: int, seed: int = 0, *,
+                     strategy: int = AES_STRATEGY_ADAPTIVE, want_eid: bool = False,
                      want_perm: bool = False, out: Optional[Plan] = None, workspace=None, stream=None) -> Plan:
     """Build the sampled plan of a CSR matrix.  `out` reuses the buffers of an earlier plan.
     `want_perm` also asks for the class-ordered row permutation (a scheduling hint
@@ -146,7 +153,7 @@ def aes_sample_build(rowptr, colidx, val, n_cols: int, W: int, seed: int = 0, *,
     if workspace is None:
         workspace = torch.empty(max(need, 8), dtype=torch.uint8, device=dev)
     _check(library().aes_sample_build(n_rows, int(n_cols), nnz, _ptr(rowptr), _ptr(colidx), _ptr(val), int(W),
-                                      int(seed) & (2 ** 64 - 1), _ptr(out.s_rowptr), _ptr(out.s_col),
+                                      int(seed) & (2 ** 64 - 1), int(strategy), _ptr(out.s_rowptr), _ptr(out.s_col),
                                       _ptr(out.s_val), _ptr(out.s_eid), _ptr(out.row_perm), _ptr(workspace),
                                       workspace.numel(), _stream(stream)))
     return out._replace(n_rows=n_rows, n_cols=int(n_cols), W=int(W))
@@ -215,3 +222,81 @@ def aes_spmm_q8(plan: Plan, Xq, scheme: int, granularity: int, scale, zero=None,
                                  _ptr(perm), _ptr(Xq), _ld(Xq), F, int(scheme), int(granularity), _ptr(scale),
                                  _ptr(zero), _ptr(Y), _ld(Y), _stream(stream)))
     return Y
+
+
+def _csr(rowptr, colidx, val):
+    rowptr = _dev(rowptr, torch.int64, "rowptr")
+    colidx = _dev(colidx, torch.int32, "colidx")
+    val = _dev(val, torch.float32, "val")
+    if val.numel() != colidx.numel():
+        raise ValueError("colidx and val differ in length")
+    return rowptr, colidx, val
+
+
+def aes_spmm_fused_f32(rowptr, colidx, val, n_cols: int, W: int, X, seed: int = 0, *,
+                       strategy: int = AES_STRATEGY_ADAPTIVE, Y=None, stream=None):
+    """Y = A_s X with the sampling done inside the SpMM kernel (no plan)."""
+    rowptr, colidx, val = _csr(rowptr, colidx, val)
+    X = _dev(X, torch.float32, "X", 2)
+    n_rows, F = rowptr.numel() - 1, X.shape[1]
+    if X.shape[0] != n_cols:
+        raise ValueError("X must have n_cols rows")
+    if Y is None:
+        Y = torch.empty((n_rows, F), dtype=torch.float32, device=X.device)
+    Y = _dev(Y, torch.float32, "Y", 2)
+    if Y.shape[0] != n_rows or Y.shape[1] != F:
+        raise ValueError("Y has the wrong shape")
+    _check(library().aes_spmm_fused_f32(n_rows, int(n_cols), _ptr(rowptr), _ptr(colidx), _ptr(val), int(W),
+                                        int(seed) & (2 ** 64 - 1), int(strategy), _ptr(X), _ld(X), F, _ptr(Y),
+                                        _ld(Y), _stream(stream)))
+    return Y
+
+
+def aes_spmm_fused_q8(rowptr, colidx, val, n_cols: int, W: int, Xq, scheme: int, granularity: int, scale,
+                      zero=None, seed: int = 0, *, strategy: int = AES_STRATEGY_ADAPTIVE, Y=None, stream=None):
+    """Fused sampling + 8-bit SpMM (no plan)."""
+    rowptr, colidx, val = _csr(rowptr, colidx, val)
+    if not isinstance(Xq, torch.Tensor) or Xq.dtype not in (torch.int8, torch.uint8):
+        raise TypeError("Xq: int8 / uint8 tensor required")
+    Xq = _dev(Xq, Xq.dtype, "Xq", 2)
+    scale = _dev(scale, torch.float32, "scale")
+    if zero is not None:
+        zero = _dev(zero, torch.float32, "zero")
+    n_rows, F = rowptr.numel() - 1, Xq.shape[1]
+    if Xq.shape[0] != n_cols:
+        raise ValueError("Xq must have n_cols rows")
+    groups = {AES_Q_PER_TENSOR: 1, AES_Q_PER_COLUMN: F, AES_Q_PER_ROW: int(n_cols)}.get(granularity)
+    if groups is not None and (scale.numel() < groups or (zero is not None and zero.numel() < groups)):
+        raise ValueError("scale / zero too short for this granularity")
+    if Y is None:
+        Y = torch.empty((n_rows, F), dtype=torch.float32, device=Xq.device)
+    Y = _dev(Y, torch.float32, "Y", 2)
+    if Y.shape[0] != n_rows or Y.shape[1] != F:
+        raise ValueError("Y has the wrong shape")
+    _check(library().aes_spmm_fused_q8(n_rows, int(n_cols), _ptr(rowptr), _ptr(colidx), _ptr(val), int(W),
+                                       int(seed) & (2 ** 64 - 1), int(strategy), _ptr(Xq), _ld(Xq), F, int(scheme),
+                                       int(granularity), _ptr(scale), _ptr(zero), _ptr(Y), _ld(Y),
+                                       _stream(stream)))
+    return Y
+
+
+def aes_dequantize_features(Xq, scheme: int, granularity: int, scale, zero=None, X=None, *, stream=None):
+    """Eq. 2 as a separate pass: float32 features from 8-bit codes."""
+    if not isinstance(Xq, torch.Tensor) or Xq.dtype not in (torch.int8, torch.uint8):
+        raise TypeError("Xq: int8 / uint8 tensor required")
+    Xq = _dev(Xq, Xq.dtype, "Xq", 2)
+    scale = _dev(scale, torch.float32, "scale")
+    if zero is not None:
+        zero = _dev(zero, torch.float32, "zero")
+    n, F = Xq.shape
+    groups = {AES_Q_PER_TENSOR: 1, AES_Q_PER_COLUMN: F, AES_Q_PER_ROW: n}.get(granularity)
+    if groups is not None and (scale.numel() < groups or (zero is not None and zero.numel() < groups)):
+        raise ValueError("scale / zero too short for this granularity")
+    if X is None:
+        X = torch.empty((n, F), dtype=torch.float32, device=Xq.device)
+    X = _dev(X, torch.float32, "X", 2)
+    if X.shape != Xq.shape:
+        raise ValueError("X has the wrong shape")
+    _check(library().aes_dequantize_features(n, F, _ptr(Xq), _ld(Xq), int(scheme), int(granularity), _ptr(scale),
+                                             _ptr(zero), _ptr(X), _ld(X), _stream(stream)))
+    return X

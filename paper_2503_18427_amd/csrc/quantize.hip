@@ -280,6 +280,42 @@ encode_kernel(int64_t n, int32_t F, const float *__restrict__ X, int64_t ldx, in
     }
 }
 
+// Eq. 2 as a stand-alone pass (the paper's placement: dequantise after loading,
+// before the SpMM): x_hat = q * scale_g + zero_g, multiply then add, binary32.
+template <int VEC>
+__global__ void __launch_bounds__(kBlock)
+dequantize_kernel(int64_t n, int32_t F, const int8_t *__restrict__ Xq, int64_t ldq, int affine_, int granularity,
+                  const float *__restrict__ scale, const float *__restrict__ zero, float *__restrict__ X, int64_t ldx)
+{
+    const bool affine = affine_ != 0;
+    const int64_t per_row = F / VEC;
+    const int64_t items = n * per_row;
+    for (int64_t it = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; it < items;
+         it += static_cast<int64_t>(gridDim.x) * kBlock) {
+        const int64_t r = it / per_row;
+        const int32_t f = static_cast<int32_t>(it - r * per_row) * VEC;
+        uint32_t w;
+        if constexpr (VEC == 4)
+            w = *reinterpret_cast<const uint32_t *>(Xq + r * ldq + f);
+        else
+            w = static_cast<uint8_t>(Xq[r * ldq + f]);
+        float out[VEC];
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) {
+            const uint32_t byte = (w >> (8 * i)) & 0xffu;
+            const float q = affine ? static_cast<float>(byte) : static_cast<float>(static_cast<int8_t>(byte));
+            const int64_t g = granularity == AES_Q_PER_TENSOR ? 0 : granularity == AES_Q_PER_COLUMN ? f + i : r;
+            float t = q * scale[g];
+            if (affine) t = t + zero[g];
+            out[i] = t;
+        }
+        if constexpr (VEC == 4)
+            *reinterpret_cast<float4 *>(X + r * ldx + f) = make_float4(out[0], out[1], out[2], out[3]);
+        else
+            X[r * ldx + f] = out[0];
+    }
+}
+
 int slabs_for(int64_t n)
 {
     int64_t s = aes::ceil_div(n, static_cast<int64_t>(kRowLanes) * 16);
@@ -384,4 +420,38 @@ extern "C" int aes_quantize_features(int64_t n, int32_t F, const float *X, int64
         encode_kernel<1><<<dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, stream>>>(
             n, F, X, ldx, affine, per_tensor, scale, group_lo, group_d, Xq, ldq);
     return aes::check_launch("aes_quantize_features/encode");
+}
+
+extern "C" int aes_dequantize_features(int64_t n, int32_t F, const int8_t *Xq, int64_t ldq,
+                                       int32_t scheme, int32_t granularity,
+                                       const float *scale, const float *zero,
+                                       float *X, int64_t ldx, void *stream_)
+{
+    const char *what = "aes_dequantize_features";
+    if (n < 0) return aes::fail(AES_ERR_INVALID_ARG, "%s: n=%lld is negative", what, (long long)n);
+    if (F < 1 || F >= (1 << 24)) return aes::fail(AES_ERR_INVALID_ARG, "%s: F=%d outside 1..2^24-1", what, (int)F);
+    if (ldx < F || ldq < F)
+        return aes::fail(AES_ERR_INVALID_ARG, "%s: leading dimension smaller than F (ldx=%lld ldq=%lld F=%d)", what,
+                         (long long)ldx, (long long)ldq, (int)F);
+    if (scheme != AES_Q_AFFINE_FLOOR_U8 && scheme != AES_Q_SYMMETRIC_RNE_I8)
+        return aes::fail(AES_ERR_INVALID_ARG, "%s: unknown scheme %d", what, (int)scheme);
+    if (granularity < AES_Q_PER_TENSOR || granularity > AES_Q_PER_ROW)
+        return aes::fail(AES_ERR_INVALID_ARG, "%s: unknown granularity %d", what, (int)granularity);
+    const int affine = scheme == AES_Q_AFFINE_FLOOR_U8 ? 1 : 0;
+    if (scale == nullptr || (affine && zero == nullptr))
+        return aes::fail(AES_ERR_INVALID_ARG, "%s: scale (or zero, affine scheme) is NULL", what);
+    if (n == 0) return AES_OK;
+    if (Xq == nullptr || X == nullptr) return aes::fail(AES_ERR_INVALID_ARG, "%s: Xq / X is NULL", what);
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    const bool vec = aes::aligned(X, 16) && aes::aligned(Xq, 4) && F % 4 == 0 && ldx % 4 == 0 && ldq % 4 == 0;
+    const int64_t items = n * (vec ? F / 4 : F);
+    int64_t blocks = aes::ceil_div(items, kBlock);
+    if (blocks > 256 * 64) blocks = 256 * 64;
+    if (vec)
+        dequantize_kernel<4><<<dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, stream>>>(
+            n, F, Xq, ldq, affine, granularity, scale, zero, X, ldx);
+    else
+        dequantize_kernel<1><<<dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, stream>>>(
+            n, F, Xq, ldq, affine, granularity, scale, zero, X, ldx);
+    return aes::check_launch(what);
 }

@@ -11,44 +11,19 @@
 //   3 offsets  : s_rowptr and the class-ordered row permutation
 //   4 sample   : one thread per output slot copies / samples a (col, val) pair
 #include "aes_common.hpp"
+#include "aes_sampling.hpp"
 
 namespace {
 
 using aes::kBlock;
 using aes::kWave;
+using aes::row_slot_count;
 
 constexpr int kSubTiles = 4;                          // rows per thread in kernels 1 and 3
 constexpr int kRowsPerBlock = kBlock * kSubTiles;     // 1024
 constexpr int kClasses = 32;                          // class = bit length of the slot count
 constexpr int kScanThreads = 1024;
 constexpr int kScanItems = 8;
-
-// Table 1 with R = row_nnz / W as a real ratio (integer cross-multiplication),
-// N >= 1 and sample_cnt <= W.  Only called for row_nnz > W >= 1.
-__device__ inline void sample_strategy(int64_t row_nnz, int64_t W, int32_t &N, int32_t &sample_cnt)
-{
-    int32_t c;
-    if (row_nnz <= 2 * W)
-        c = 4;
-    else if (row_nnz <= 36 * W)
-        c = 8;
-    else if (row_nnz <= 54 * W)
-        c = 16;
-    else
-        c = 32;
-    int32_t n = static_cast<int32_t>(W) / c;
-    N = n < 1 ? 1 : n;
-    sample_cnt = c > W ? static_cast<int32_t>(W) : c;
-}
-
-// Slots owned by a row: the whole row if it fits (or W == 0), else N*sample_cnt.
-__device__ inline int64_t row_slot_count(int64_t row_nnz, int32_t W)
-{
-    if (W == 0 || row_nnz <= W) return row_nnz;
-    int32_t N, cnt;
-    sample_strategy(row_nnz, W, N, cnt);
-    return static_cast<int64_t>(N) * cnt;
-}
 
 __device__ inline int slot_class(int64_t slots)
 {
@@ -76,7 +51,7 @@ __device__ inline int64_t wave_inclusive_scan(int64_t v, int lane)
 
 // ---- kernel 1 ---------------------------------------------------------------
 __global__ void __launch_bounds__(kBlock)
-classify_kernel(int64_t n_rows, const int64_t *__restrict__ rowptr, int32_t W, int64_t nblk,
+classify_kernel(int64_t n_rows, const int64_t *__restrict__ rowptr, int32_t W, int strategy, int64_t nblk,
                 int64_t *__restrict__ blk_slots, int32_t *__restrict__ hist, int want_hist)
 {
     __shared__ int32_t sh_hist[kClasses];
@@ -89,7 +64,7 @@ classify_kernel(int64_t n_rows, const int64_t *__restrict__ rowptr, int32_t W, i
     for (int q = 0; q < kSubTiles; ++q) {
         int64_t r = blk * kRowsPerBlock + q * kBlock + t;
         if (r < n_rows) {
-            int64_t s = row_slot_count(rowptr[r + 1] - rowptr[r], W);
+            int64_t s = row_slot_count(rowptr[r + 1] - rowptr[r], W, strategy);
             mine += s;
             if (want_hist) atomicAdd(&sh_hist[slot_class(s)], 1);
         }
@@ -166,7 +141,7 @@ scan_kernel(int64_t n_rows, int64_t nblk, int64_t *__restrict__ blk_slots,
 
 // ---- kernel 3 ---------------------------------------------------------------
 __global__ void __launch_bounds__(kBlock)
-offsets_kernel(int64_t n_rows, const int64_t *__restrict__ rowptr, int32_t W, int64_t nblk,
+offsets_kernel(int64_t n_rows, const int64_t *__restrict__ rowptr, int32_t W, int strategy, int64_t nblk,
                const int64_t *__restrict__ blk_slots, const int32_t *__restrict__ hist,
                int n_classes, int64_t *__restrict__ s_rowptr, int32_t *__restrict__ row_perm)
 {
@@ -180,7 +155,7 @@ offsets_kernel(int64_t n_rows, const int64_t *__restrict__ rowptr, int32_t W, in
     for (int q = 0; q < kSubTiles; ++q) {
         const int64_t r = blk * kRowsPerBlock + q * kBlock + t;
         const bool valid = r < n_rows;
-        int64_t s = valid ? row_slot_count(rowptr[r + 1] - rowptr[r], W) : 0;
+        int64_t s = valid ? row_slot_count(rowptr[r + 1] - rowptr[r], W, strategy) : 0;
         int64_t incl = wave_inclusive_scan(s, lane);
         if (lane == kWave - 1) sh_part[wave] = incl;
         const int cls = valid ? slot_class(s) : -1;
@@ -225,19 +200,9 @@ offsets_kernel(int64_t n_rows, const int64_t *__restrict__ rowptr, int32_t W, in
 // thread does not depend on the degree distribution.
 constexpr int kSampleRows = 256;
 
-__device__ inline int64_t hash_start(uint64_t current_ind, int64_t row_nnz, int32_t N)
-{
-    const uint64_t modulus = static_cast<uint64_t>(row_nnz - N + 1);
-    const uint64_t prod = current_ind * 1429ull;
-    if (prod < modulus) return static_cast<int64_t>(prod);
-    if (((prod | modulus) >> 32) == 0)
-        return static_cast<int64_t>(static_cast<uint32_t>(prod) % static_cast<uint32_t>(modulus));
-    return static_cast<int64_t>(prod % modulus);
-}
-
 __global__ void __launch_bounds__(kBlock)
 sample_slots_kernel(int64_t n_rows, const int64_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
-                    const float *__restrict__ val, int32_t W, uint64_t seed,
+                    const float *__restrict__ val, int32_t W, uint64_t seed, int strategy,
                     const int64_t *__restrict__ s_rowptr, int32_t *__restrict__ s_col,
                     float *__restrict__ s_val, int64_t *__restrict__ s_eid)
 {
@@ -268,12 +233,8 @@ sample_slots_kernel(int64_t n_rows, const int64_t *__restrict__ rowptr, const in
             e = row_begin + k;
         } else {
             int32_t N, cnt;
-            sample_strategy(row_nnz, W, N, cnt);
-            const int32_t k32 = static_cast<int32_t>(k);
-            const int32_t i = k32 % cnt;
-            const int32_t j = k32 / cnt;
-            const uint32_t s_r = static_cast<uint32_t>(seed * (2ull * static_cast<uint64_t>(r) + 1ull) * 2654435761ull);
-            e = row_begin + hash_start(static_cast<uint64_t>(i) + s_r, row_nnz, N) + j;
+            aes::sample_strategy(row_nnz, W, strategy, N, cnt);
+            e = aes::sampled_entry(row_begin, row_nnz, N, cnt, aes::row_offset(seed, r), static_cast<int32_t>(k));
         }
         s_col[base + t] = colidx[e];
         s_val[base + t] = val[e];
@@ -311,7 +272,7 @@ extern "C" size_t aes_sample_workspace_bytes(int64_t n_rows)
 
 extern "C" int aes_sample_build(int64_t n_rows, int64_t n_cols, int64_t nnz,
                                 const int64_t *rowptr, const int32_t *colidx, const float *val,
-                                int32_t W, uint64_t seed,
+                                int32_t W, uint64_t seed, int32_t strategy,
                                 int64_t *s_rowptr, int32_t *s_col, float *s_val, int64_t *s_eid,
                                 int32_t *row_perm,
                                 void *workspace, size_t workspace_bytes, void *stream_)
@@ -324,6 +285,8 @@ extern "C" int aes_sample_build(int64_t n_rows, int64_t n_cols, int64_t nnz,
                          (long long)n_cols);
     if (W < 0 || W > AES_MAX_W)
         return aes::fail(AES_ERR_INVALID_ARG, "aes_sample_build: W=%d outside 0..%d", (int)W, (int)AES_MAX_W);
+    if (strategy < AES_STRATEGY_ADAPTIVE || strategy > AES_STRATEGY_SFS)
+        return aes::fail(AES_ERR_INVALID_ARG, "aes_sample_build: unknown strategy %d", (int)strategy);
     if (rowptr == nullptr || s_rowptr == nullptr)
         return aes::fail(AES_ERR_INVALID_ARG, "aes_sample_build: rowptr / s_rowptr is NULL");
     if (nnz > 0 && (colidx == nullptr || val == nullptr || s_col == nullptr || s_val == nullptr))
@@ -348,7 +311,7 @@ extern "C" int aes_sample_build(int64_t n_rows, int64_t n_cols, int64_t nnz,
 
     if (nblk > 0) {
         classify_kernel<<<dim3(static_cast<unsigned>(nblk)), dim3(kBlock), 0, stream>>>(
-            n_rows, rowptr, W, nblk, blk_slots, hist, want_hist);
+            n_rows, rowptr, W, strategy, nblk, blk_slots, hist, want_hist);
         if (int rc = aes::check_launch("aes_sample_build/classify")) return rc;
     }
     scan_kernel<<<dim3(1), dim3(kScanThreads), 0, stream>>>(n_rows, nblk, blk_slots,
@@ -356,7 +319,7 @@ extern "C" int aes_sample_build(int64_t n_rows, int64_t n_cols, int64_t nnz,
     if (int rc = aes::check_launch("aes_sample_build/scan")) return rc;
     if (nblk == 0) return AES_OK;
     offsets_kernel<<<dim3(static_cast<unsigned>(nblk)), dim3(kBlock), 0, stream>>>(
-        n_rows, rowptr, W, nblk, blk_slots, hist, n_classes, s_rowptr, row_perm);
+        n_rows, rowptr, W, strategy, nblk, blk_slots, hist, n_classes, s_rowptr, row_perm);
     if (int rc = aes::check_launch("aes_sample_build/offsets")) return rc;
     if (nnz == 0) return AES_OK;
 
@@ -364,6 +327,6 @@ extern "C" int aes_sample_build(int64_t n_rows, int64_t n_cols, int64_t nnz,
     if (sample_blocks > INT32_MAX)
         return aes::fail(AES_ERR_UNSUPPORTED, "aes_sample_build: n_rows=%lld too large", (long long)n_rows);
     sample_slots_kernel<<<dim3(static_cast<unsigned>(sample_blocks)), dim3(kBlock), 0, stream>>>(
-        n_rows, rowptr, colidx, val, W, seed, s_rowptr, s_col, s_val, s_eid);
+        n_rows, rowptr, colidx, val, W, seed, strategy, s_rowptr, s_col, s_val, s_eid);
     return aes::check_launch("aes_sample_build/sample");
 }

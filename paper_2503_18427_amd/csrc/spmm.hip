@@ -21,6 +21,7 @@
 // The kernel is bound by the gather traffic (about 2 flop per 4 bytes), not by
 // arithmetic, so there is no MFMA here.
 #include "aes_common.hpp"
+#include "aes_sampling.hpp"
 
 namespace {
 
@@ -32,6 +33,18 @@ constexpr int kTile = 64;          // slots staged in LDS per group per round
 enum QMode {
     kQNone = 0,      // float32 features, or 8-bit features with per-tensor / per-column constants
     kQRowScale = 1   // 8-bit features with per-row constants: folded into the staged edge value
+};
+
+// Where a row's (col, val) slots come from: a materialised plan (FUSED = false: the
+// three arrays are s_rowptr / s_col / s_val) or the CSR matrix itself, sampled on
+// the fly by Table 1 and Eq. 3 (FUSED = true).
+struct SlotSource {
+    const int64_t *rowptr;
+    const int32_t *col;
+    const float *val;
+    int32_t W;
+    int32_t strategy;
+    uint64_t seed;
 };
 
 struct QParams {
@@ -116,11 +129,10 @@ __device__ inline void wave_lds_sync()
 // LPR   lanes per output row (8, 16, 32 or 64); a wavefront holds 64/LPR rows
 // Feat  feature loader: Feat::VEC features per lane per chunk (4 on the aligned
 //       fast paths, 1 otherwise)
-// QMODE see above; QUANT: apply the 8-bit epilogue
-template <int LPR, int UNROLL, typename Feat, int QMODE, bool QUANT>
+// QMODE see above; QUANT: apply the 8-bit epilogue; FUSED: sample from the CSR on the fly
+template <int LPR, int UNROLL, typename Feat, int QMODE, bool QUANT, bool FUSED>
 __global__ void __launch_bounds__(kBlock)
-spmm_rows_kernel(int64_t n_rows, const int64_t *__restrict__ s_rowptr, const int32_t *__restrict__ s_col,
-                 const float *__restrict__ s_val, const int32_t *__restrict__ row_perm,
+spmm_rows_kernel(int64_t n_rows, SlotSource src, const int32_t *__restrict__ row_perm,
                  const typename Feat::elem_t *__restrict__ X, int64_t ldx, int32_t F, QParams qp,
                  float *__restrict__ Y, int64_t ldy)
 {
@@ -136,8 +148,19 @@ spmm_rows_kernel(int64_t n_rows, const int64_t *__restrict__ s_rowptr, const int
     const int64_t slot_in_order = static_cast<int64_t>(blockIdx.x) * kRowsPerBlock + wave * kGroups + group;
     if (slot_in_order >= n_rows) return;                 // whole group leaves together
     const int64_t r = row_perm ? static_cast<int64_t>(row_perm[slot_in_order]) : slot_in_order;
-    const int64_t k_begin = s_rowptr[r];
-    const int64_t n_slots = s_rowptr[r + 1] - k_begin;
+    const int64_t k_begin = src.rowptr[r];
+    int64_t n_slots = src.rowptr[r + 1] - k_begin;
+    // FUSED: a row longer than W is sampled; slot k then maps to a CSR entry by Eq. 3
+    [[maybe_unused]] const int64_t row_nnz = n_slots;
+    [[maybe_unused]] bool sampled = false;
+    [[maybe_unused]] int32_t samp_n = 0, samp_cnt = 1;
+    [[maybe_unused]] uint32_t s_r = 0;
+    if (FUSED && src.W != 0 && row_nnz > src.W) {
+        sampled = true;
+        aes::sample_strategy(row_nnz, src.W, src.strategy, samp_n, samp_cnt);
+        n_slots = static_cast<int64_t>(samp_n) * samp_cnt;
+        s_r = aes::row_offset(src.seed, r);
+    }
     int2 *my_stage = stage[wave][group];
 
     for (int32_t f0 = 0; f0 < F; f0 += LPR * VEC) {
@@ -155,8 +178,11 @@ spmm_rows_kernel(int64_t n_rows, const int64_t *__restrict__ s_rowptr, const int
 #pragma unroll
             for (int s = lane; s < kTile; s += LPR) {
                 if (s < m) {
-                    const int32_t c = s_col[k_begin + t0 + s];
-                    float v = s_val[k_begin + t0 + s];
+                    int64_t e = k_begin + t0 + s;
+                    if (FUSED && sampled)
+                        e = aes::sampled_entry(k_begin, row_nnz, samp_n, samp_cnt, s_r, static_cast<int32_t>(t0) + s);
+                    const int32_t c = src.col[e];
+                    float v = src.val[e];
                     if (QUANT) {
                         if (QMODE == kQRowScale) {
                             if (qp.affine) side = __builtin_fmaf(v, qp.zero[c], side);
@@ -245,17 +271,16 @@ spmm_rows_kernel(int64_t n_rows, const int64_t *__restrict__ s_rowptr, const int
     }
 }
 
-template <int LPR, int UNROLL, typename Feat, int QMODE, bool QUANT>
-int launch_rows(int64_t n_rows, const int64_t *s_rowptr, const int32_t *s_col, const float *s_val,
+template <int LPR, int UNROLL, typename Feat, int QMODE, bool QUANT, bool FUSED>
+int launch_rows(int64_t n_rows, const SlotSource &src,
                 const int32_t *row_perm, const typename Feat::elem_t *X, int64_t ldx, int32_t F, QParams qp,
                 float *Y, int64_t ldy, hipStream_t stream, const char *what)
 {
     constexpr int kRowsPerBlock = (kWave / LPR) * aes::kWavesPerBlock;
     const int64_t grid = aes::ceil_div(n_rows, kRowsPerBlock);
     if (grid > INT32_MAX) return aes::fail(AES_ERR_UNSUPPORTED, "%s: n_rows=%lld too large", what, (long long)n_rows);
-    spmm_rows_kernel<LPR, UNROLL, Feat, QMODE, QUANT>
-        <<<dim3(static_cast<unsigned>(grid)), dim3(kBlock), 0, stream>>>(n_rows, s_rowptr, s_col, s_val, row_perm,
-                                                                           X, ldx, F, qp, Y, ldy);
+    spmm_rows_kernel<LPR, UNROLL, Feat, QMODE, QUANT, FUSED>
+        <<<dim3(static_cast<unsigned>(grid)), dim3(kBlock), 0, stream>>>(n_rows, src, row_perm, X, ldx, F, qp, Y, ldy);
     return aes::check_launch(what);
 }
 
@@ -267,38 +292,68 @@ int lanes_per_row(int32_t F, int vec)
 }
 
 // Vector path: pick the lane-group width from F.
-template <typename Feat, int QMODE, bool QUANT>
-int dispatch_lanes(int64_t n_rows, const int64_t *s_rowptr, const int32_t *s_col, const float *s_val,
-                   const int32_t *row_perm, const typename Feat::elem_t *X, int64_t ldx, int32_t F, QParams qp,
-                   float *Y, int64_t ldy, hipStream_t stream, const char *what)
+template <typename Feat, int QMODE, bool QUANT, bool FUSED>
+int dispatch_lanes(int64_t n_rows, const SlotSource &src, const int32_t *row_perm, const typename Feat::elem_t *X,
+                   int64_t ldx, int32_t F, QParams qp, float *Y, int64_t ldy, hipStream_t stream, const char *what)
 {
     switch (lanes_per_row(F, Feat::VEC)) {
-        case 8:
-            return launch_rows<8, 8, Feat, QMODE, QUANT>(n_rows, s_rowptr, s_col, s_val, row_perm, X, ldx, F, qp, Y, ldy,
-                                                         stream, what);
-        case 16:
-            return launch_rows<16, 8, Feat, QMODE, QUANT>(n_rows, s_rowptr, s_col, s_val, row_perm, X, ldx, F, qp, Y, ldy,
-                                                          stream, what);
-        case 32:
-            return launch_rows<32, 8, Feat, QMODE, QUANT>(n_rows, s_rowptr, s_col, s_val, row_perm, X, ldx, F, qp, Y, ldy,
-                                                          stream, what);
-        default:
-            return launch_rows<64, 8, Feat, QMODE, QUANT>(n_rows, s_rowptr, s_col, s_val, row_perm, X, ldx, F, qp, Y, ldy,
-                                                          stream, what);
+        case 8: return launch_rows<8, 8, Feat, QMODE, QUANT, FUSED>(n_rows, src, row_perm, X, ldx, F, qp, Y, ldy, stream, what);
+        case 16: return launch_rows<16, 8, Feat, QMODE, QUANT, FUSED>(n_rows, src, row_perm, X, ldx, F, qp, Y, ldy, stream, what);
+        case 32: return launch_rows<32, 8, Feat, QMODE, QUANT, FUSED>(n_rows, src, row_perm, X, ldx, F, qp, Y, ldy, stream, what);
+        default: return launch_rows<64, 8, Feat, QMODE, QUANT, FUSED>(n_rows, src, row_perm, X, ldx, F, qp, Y, ldy, stream, what);
     }
 }
 
-// 8-bit features: 4 codes per lane when rows are 4-byte aligned, else element-wise.
-template <bool SIGNED, int QMODE>
-int dispatch_q8(int vec, int64_t n_rows, const int64_t *s_rowptr, const int32_t *s_col, const float *s_val,
-                const int32_t *row_perm, const int8_t *Xq, int64_t ldq, int32_t F, QParams qp, float *Y, int64_t ldy,
-                hipStream_t stream, const char *what)
+template <bool FUSED>
+int run_f32(const char *what, int64_t n_rows, const SlotSource &src, const int32_t *row_perm, const float *X,
+            int64_t ldx, int32_t F, float *Y, int64_t ldy, hipStream_t stream)
 {
-    if (vec == 4)
-        return dispatch_lanes<FeatQ8<4, SIGNED>, QMODE, true>(n_rows, s_rowptr, s_col, s_val, row_perm, Xq, ldq, F, qp,
-                                                              Y, ldy, stream, what);
-    return launch_rows<64, 4, FeatQ8<1, SIGNED>, QMODE, true>(n_rows, s_rowptr, s_col, s_val, row_perm, Xq, ldq, F, qp,
-                                                              Y, ldy, stream, what);
+    const bool fast = aes::aligned(X, 16) && aes::aligned(Y, 16) && F % 4 == 0 && ldx % 4 == 0 && ldy % 4 == 0;
+    QParams qp = {nullptr, nullptr, 0, 0};
+    if (fast) return dispatch_lanes<FeatF32<4>, kQNone, false, FUSED>(n_rows, src, row_perm, X, ldx, F, qp, Y, ldy, stream, what);
+    return launch_rows<64, 4, FeatF32<1>, kQNone, false, FUSED>(n_rows, src, row_perm, X, ldx, F, qp, Y, ldy, stream, what);
+}
+
+// 8-bit features: 4 codes per lane when rows are 4-byte aligned, else element-wise.
+template <bool SIGNED, int QMODE, bool FUSED>
+int dispatch_q8(bool fast, int64_t n_rows, const SlotSource &src, const int32_t *row_perm, const int8_t *Xq,
+                int64_t ldq, int32_t F, QParams qp, float *Y, int64_t ldy, hipStream_t stream, const char *what)
+{
+    if (fast)
+        return dispatch_lanes<FeatQ8<4, SIGNED>, QMODE, true, FUSED>(n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
+    return launch_rows<64, 4, FeatQ8<1, SIGNED>, QMODE, true, FUSED>(n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
+}
+
+template <bool FUSED>
+int run_q8(const char *what, int64_t n_rows, const SlotSource &src, const int32_t *row_perm, const int8_t *Xq,
+           int64_t ldq, int32_t F, int32_t scheme, int32_t granularity, const float *scale, const float *zero,
+           float *Y, int64_t ldy, hipStream_t stream)
+{
+    if (scheme != AES_Q_AFFINE_FLOOR_U8 && scheme != AES_Q_SYMMETRIC_RNE_I8)
+        return aes::fail(AES_ERR_INVALID_ARG, "%s: unknown scheme %d", what, (int)scheme);
+    if (granularity < AES_Q_PER_TENSOR || granularity > AES_Q_PER_ROW)
+        return aes::fail(AES_ERR_INVALID_ARG, "%s: unknown granularity %d", what, (int)granularity);
+    if (scale == nullptr) return aes::fail(AES_ERR_INVALID_ARG, "%s: scale is NULL", what);
+    const bool affine = scheme == AES_Q_AFFINE_FLOOR_U8;
+    if (affine && zero == nullptr) return aes::fail(AES_ERR_INVALID_ARG, "%s: zero is NULL for the affine scheme", what);
+    if (n_rows == 0) return AES_OK;
+    const bool fast = aes::aligned(Y, 16) && ldy % 4 == 0 && aes::aligned(Xq, 4) && F % 4 == 0 && ldq % 4 == 0;
+    QParams qp = {scale, zero, granularity, affine ? 1 : 0};
+    const bool per_row = granularity == AES_Q_PER_ROW;
+    if (affine) {
+        if (per_row) return dispatch_q8<false, kQRowScale, FUSED>(fast, n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
+        return dispatch_q8<false, kQNone, FUSED>(fast, n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
+    }
+    if (per_row) return dispatch_q8<true, kQRowScale, FUSED>(fast, n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
+    return dispatch_q8<true, kQNone, FUSED>(fast, n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
+}
+
+int check_sampling(const char *what, int32_t W, int32_t strategy)
+{
+    if (W < 0 || W > AES_MAX_W) return aes::fail(AES_ERR_INVALID_ARG, "%s: W=%d outside 0..%d", what, (int)W, (int)AES_MAX_W);
+    if (strategy < AES_STRATEGY_ADAPTIVE || strategy > AES_STRATEGY_SFS)
+        return aes::fail(AES_ERR_INVALID_ARG, "%s: unknown strategy %d", what, (int)strategy);
+    return AES_OK;
 }
 
 int check_common(const char *what, int64_t n_rows, int64_t n_cols, const int64_t *s_rowptr, const int32_t *s_col,
@@ -325,19 +380,13 @@ extern "C" int aes_spmm_f32(int64_t n_rows, int64_t n_cols,
                             const int64_t *s_rowptr, const int32_t *s_col, const float *s_val,
                             const int32_t *row_perm,
                             const float *X, int64_t ldx, int32_t F,
-                            float *Y, int64_t ldy, void *stream_)
+                            float *Y, int64_t ldy, void *stream)
 {
     const char *what = "aes_spmm_f32";
     if (int rc = check_common(what, n_rows, n_cols, s_rowptr, s_col, s_val, X, ldx, F, Y, ldy)) return rc;
     if (n_rows == 0) return AES_OK;
-    const bool fast = aes::aligned(X, 16) && aes::aligned(Y, 16) && F % 4 == 0 && ldx % 4 == 0 && ldy % 4 == 0;
-    QParams qp = {nullptr, nullptr, 0, 0};
-    hipStream_t stream = static_cast<hipStream_t>(stream_);
-    if (fast)
-        return dispatch_lanes<FeatF32<4>, kQNone, false>(n_rows, s_rowptr, s_col, s_val, row_perm, X, ldx, F, qp, Y,
-                                                         ldy, stream, what);
-    return launch_rows<64, 4, FeatF32<1>, kQNone, false>(n_rows, s_rowptr, s_col, s_val, row_perm, X, ldx, F, qp, Y, ldy,
-                                                         stream, what);
+    const SlotSource src = {s_rowptr, s_col, s_val, 0, 0, 0};
+    return run_f32<false>(what, n_rows, src, row_perm, X, ldx, F, Y, ldy, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int aes_spmm_q8(int64_t n_rows, int64_t n_cols,
@@ -346,32 +395,41 @@ extern "C" int aes_spmm_q8(int64_t n_rows, int64_t n_cols,
                            const int8_t *Xq, int64_t ldq, int32_t F,
                            int32_t scheme, int32_t granularity,
                            const float *scale, const float *zero,
-                           float *Y, int64_t ldy, void *stream_)
+                           float *Y, int64_t ldy, void *stream)
 {
     const char *what = "aes_spmm_q8";
     if (int rc = check_common(what, n_rows, n_cols, s_rowptr, s_col, s_val, Xq, ldq, F, Y, ldy)) return rc;
-    if (scheme != AES_Q_AFFINE_FLOOR_U8 && scheme != AES_Q_SYMMETRIC_RNE_I8)
-        return aes::fail(AES_ERR_INVALID_ARG, "%s: unknown scheme %d", what, (int)scheme);
-    if (granularity < AES_Q_PER_TENSOR || granularity > AES_Q_PER_ROW)
-        return aes::fail(AES_ERR_INVALID_ARG, "%s: unknown granularity %d", what, (int)granularity);
-    if (scale == nullptr) return aes::fail(AES_ERR_INVALID_ARG, "%s: scale is NULL", what);
-    const bool affine = scheme == AES_Q_AFFINE_FLOOR_U8;
-    if (affine && zero == nullptr) return aes::fail(AES_ERR_INVALID_ARG, "%s: zero is NULL for the affine scheme", what);
+    const SlotSource src = {s_rowptr, s_col, s_val, 0, 0, 0};
+    return run_q8<false>(what, n_rows, src, row_perm, Xq, ldq, F, scheme, granularity, scale, zero, Y, ldy,
+                         static_cast<hipStream_t>(stream));
+}
+
+extern "C" int aes_spmm_fused_f32(int64_t n_rows, int64_t n_cols,
+                                  const int64_t *rowptr, const int32_t *colidx, const float *val,
+                                  int32_t W, uint64_t seed, int32_t strategy,
+                                  const float *X, int64_t ldx, int32_t F,
+                                  float *Y, int64_t ldy, void *stream)
+{
+    const char *what = "aes_spmm_fused_f32";
+    if (int rc = check_common(what, n_rows, n_cols, rowptr, colidx, val, X, ldx, F, Y, ldy)) return rc;
+    if (int rc = check_sampling(what, W, strategy)) return rc;
     if (n_rows == 0) return AES_OK;
-    hipStream_t stream = static_cast<hipStream_t>(stream_);
-    const bool fast = aes::aligned(Y, 16) && ldy % 4 == 0 && aes::aligned(Xq, 4) && F % 4 == 0 && ldq % 4 == 0;
-    const int vec = fast ? 4 : 1;
-    QParams qp = {scale, zero, granularity, affine ? 1 : 0};
-    const bool per_row = granularity == AES_Q_PER_ROW;
-    if (affine) {
-        if (per_row)
-            return dispatch_q8<false, kQRowScale>(vec, n_rows, s_rowptr, s_col, s_val, row_perm, Xq, ldq, F, qp, Y, ldy,
-                                                  stream, what);
-        return dispatch_q8<false, kQNone>(vec, n_rows, s_rowptr, s_col, s_val, row_perm, Xq, ldq, F, qp, Y, ldy, stream,
-                                          what);
-    }
-    if (per_row)
-        return dispatch_q8<true, kQRowScale>(vec, n_rows, s_rowptr, s_col, s_val, row_perm, Xq, ldq, F, qp, Y, ldy,
-                                             stream, what);
-    return dispatch_q8<true, kQNone>(vec, n_rows, s_rowptr, s_col, s_val, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
+    const SlotSource src = {rowptr, colidx, val, W, strategy, seed};
+    return run_f32<true>(what, n_rows, src, nullptr, X, ldx, F, Y, ldy, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int aes_spmm_fused_q8(int64_t n_rows, int64_t n_cols,
+                                 const int64_t *rowptr, const int32_t *colidx, const float *val,
+                                 int32_t W, uint64_t seed, int32_t strategy,
+                                 const int8_t *Xq, int64_t ldq, int32_t F,
+                                 int32_t scheme, int32_t granularity,
+                                 const float *scale, const float *zero,
+                                 float *Y, int64_t ldy, void *stream)
+{
+    const char *what = "aes_spmm_fused_q8";
+    if (int rc = check_common(what, n_rows, n_cols, rowptr, colidx, val, Xq, ldq, F, Y, ldy)) return rc;
+    if (int rc = check_sampling(what, W, strategy)) return rc;
+    const SlotSource src = {rowptr, colidx, val, W, strategy, seed};
+    return run_q8<true>(what, n_rows, src, nullptr, Xq, ldq, F, scheme, granularity, scale, zero, Y, ldy,
+                        static_cast<hipStream_t>(stream));
 }

@@ -1,0 +1,170 @@
+"""Measurement studies around the hot path, on one MI355X.
+
+    python -m paper_2503_18427_amd.studies width-sweep [workload]
+    python -m paper_2503_18427_amd.studies strategies  [workload]
+    python -m paper_2503_18427_amd.studies loading     [workload]
+
+They reproduce the *shape* of the paper's evaluation on the synthetic workloads
+(the paper's datasets are not available): kernel time and error against the
+exact product per width W (Sec. 4.2), the per-row sampling-rate distribution
+(Fig. 5), the adaptive strategy against the fixed AFS / SFS granularities
+(Sec. 3.3), and what 8-bit features save when they are loaded from the host
+(Sec. 3.1, Table 3).  Every product of the method is computed by the library's
+kernels; torch is only used for norms, quantiles and host-to-device copies.
+Output: markdown tables on stdout.
+"""
+from __future__ import annotations
+
+import os
+import sys
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import torch  # noqa: E402
+
+import paper_2503_18427_amd as aes  # noqa: E402
+from workloads import configs  # noqa: E402
+
+
+def _time_ms(fn, iters: int = 10, warmup: int = 2) -> float:
+    """Median HIP-event time of fn() on the current stream."""
+    for _ in range(warmup):
+        fn()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(iters + 1)]
+    ev[0].record()
+    for i in range(iters):
+        fn()
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    ts = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(iters))
+    return ts[len(ts) // 2]
+
+
+def _rel_fro(Y: torch.Tensor, Yex: torch.Tensor) -> float:
+    return float(torch.linalg.vector_norm((Y - Yex).double()) / torch.linalg.vector_norm(Yex.double()))
+
+
+def _bytes(n, S, F, e, per_row_scale=False):
+    return 8 * S + S * F * e + 4 * n * F + 12 * n + (4 * S if per_row_scale else 0)
+
+
+def width_sweep(name: str) -> None:
+    d = configs.make(name, "cuda")
+    w = d["workload"]
+    n, F, X = d["n"], d["F"], d["X"]
+    scheme, gran = w.q_scheme, w.q_granularity
+    q = aes.aes_quantize_features(X, scheme, gran)
+    csr = (d["rowptr"], d["colidx"], d["val"])
+    exact = aes.aes_sample_build(*csr, n, 0)
+    Yex = aes.aes_spmm_f32(exact, X)
+    t_ex = _time_ms(lambda: aes.aes_spmm_f32(exact, X, Yex))
+    deg = (d["rowptr"][1:] - d["rowptr"][:-1]).double()
+    print(f"### width sweep, `{name}`: n = {n}, nnz = {d['nnz']}, F = {F}, exact SpMM {t_ex:.3f} ms "
+          f"({_bytes(n, d['nnz'], F, 4) / t_ex / 1e6:.0f} GB/s effective)\n")
+    print("| W | slots S | sampled rows | median / mean row sampling rate | build ms | fp32 ms | fp32 GB/s | "
+          "fused fp32 ms | int8 ms | int8 GB/s | speedup vs exact | rel. Frobenius error fp32 | int8 |")
+    print("|---|---|---|---|---|---|---|---|---|---|---|---|---|")
+    Y = torch.empty_like(Yex)
+    for W in w.widths:
+        plan = aes.aes_sample_build(*csr, n, W)
+        S = int(plan.s_rowptr[-1])
+        slots = (plan.s_rowptr[1:] - plan.s_rowptr[:-1]).double()
+        rate = torch.where(deg > 0, slots / deg.clamp(min=1), torch.ones_like(deg))
+        t_b = _time_ms(lambda: aes.aes_sample_build(*csr, n, W, out=plan))
+        t32 = _time_ms(lambda: aes.aes_spmm_f32(plan, X, Y))
+        e32 = _rel_fro(Y, Yex)
+        t_f = _time_ms(lambda: aes.aes_spmm_fused_f32(*csr, n, W, X, Y=Y))
+        t8 = _time_ms(lambda: aes.aes_spmm_q8(plan, q[0], scheme, gran, q[1], q[2], Y))
+        e8 = _rel_fro(Y, Yex)
+        print(f"| {W} | {S} | {float((deg > W).double().mean()) * 100:.1f} % | "
+              f"{float(rate.median()):.3f} / {float(rate.mean()):.3f} | {t_b:.3f} | {t32:.3f} | "
+              f"{_bytes(n, S, F, 4) / t32 / 1e6:.0f} | {t_f:.3f} | {t8:.3f} | "
+              f"{_bytes(n, S, F, 1, gran == 2) / t8 / 1e6:.0f} | {t_ex / t32:.2f}x | {e32:.4f} | {e8:.4f} |")
+    print()
+
+
+def strategies(name: str) -> None:
+    d = configs.make(name, "cuda")
+    w = d["workload"]
+    n, F, X = d["n"], d["F"], d["X"]
+    csr = (d["rowptr"], d["colidx"], d["val"])
+    exact = aes.aes_sample_build(*csr, n, 0)
+    Yex = aes.aes_spmm_f32(exact, X)
+    Y = torch.empty_like(Yex)
+    print(f"### adaptive vs fixed granularity, `{name}` (error = relative Frobenius distance to the exact product; "
+          f"times: plan build / fused single kernel, ms)\n")
+    print("| W | adaptive err | AFS err | SFS err | adaptive build / fused | AFS build / fused | SFS build / fused |")
+    print("|---|---|---|---|---|---|---|")
+    for W in w.widths:
+        row = [f"| {W} "]
+        errs, times = [], []
+        for strat in (aes.AES_STRATEGY_ADAPTIVE, aes.AES_STRATEGY_AFS, aes.AES_STRATEGY_SFS):
+            plan = aes.aes_sample_build(*csr, n, W, strategy=strat)
+            aes.aes_spmm_f32(plan, X, Y)
+            errs.append(_rel_fro(Y, Yex))
+            tb = _time_ms(lambda: aes.aes_sample_build(*csr, n, W, strategy=strat, out=plan))
+            tf = _time_ms(lambda: aes.aes_spmm_fused_f32(*csr, n, W, X, strategy=strat, Y=Y))
+            times.append(f"{tb:.3f} / {tf:.3f}")
+        print(f"| {W} | " + " | ".join(f"{e:.4f}" for e in errs) + " | " + " | ".join(times) + " |")
+    print()
+
+
+def loading(name: str) -> None:
+    """Host-to-device feature loading: float32 vs 8-bit (+ stand-alone Eq. 2 pass) vs 8-bit fused."""
+    d = configs.make(name, "cuda")
+    w = d["workload"]
+    n, F, X = d["n"], d["F"], d["X"]
+    scheme, gran = w.q_scheme, w.q_granularity
+    W = w.widths[0]
+    plan = aes.aes_sample_build(d["rowptr"], d["colidx"], d["val"], n, W)
+    q = aes.aes_quantize_features(X, scheme, gran)
+    X_host = X.cpu().pin_memory()
+    Xq_host = q[0].cpu().pin_memory()
+    sc_host, zr_host = q[1].cpu().pin_memory(), q[2].cpu().pin_memory()
+    X_dev = torch.empty_like(X)
+    Xq_dev = torch.empty_like(q[0])
+    sc_dev, zr_dev = torch.empty_like(q[1]), torch.empty_like(q[2])
+    Y = torch.empty((n, F), device="cuda")
+
+    def load_f32():
+        X_dev.copy_(X_host, non_blocking=True)
+
+    def load_q8():
+        Xq_dev.copy_(Xq_host, non_blocking=True)
+        sc_dev.copy_(sc_host, non_blocking=True)
+        zr_dev.copy_(zr_host, non_blocking=True)
+
+    t_l32 = _time_ms(load_f32, iters=5)
+    t_l8 = _time_ms(load_q8, iters=5)
+    t_dq = _time_ms(lambda: aes.aes_dequantize_features(Xq_dev, scheme, gran, sc_dev, zr_dev, X_dev))
+    t_s32 = _time_ms(lambda: aes.aes_spmm_f32(plan, X_dev, Y))
+    t_s8 = _time_ms(lambda: aes.aes_spmm_q8(plan, Xq_dev, scheme, gran, sc_dev, zr_dev, Y))
+    print(f"### feature loading, `{name}` (n = {n}, F = {F}, W = {W}; pinned host memory, one stream; ms)\n")
+    print("| pipeline | load | dequantise | SpMM | total | loading share | load time saved vs fp32 |")
+    print("|---|---|---|---|---|---|---|")
+    rows = [("fp32 features", t_l32, 0.0, t_s32),
+            ("8-bit load + stand-alone Eq. 2 pass + fp32 SpMM (the paper's pipeline)", t_l8, t_dq, t_s32),
+            ("8-bit load + fused dequantising SpMM", t_l8, 0.0, t_s8)]
+    for label, tl, td, ts in rows:
+        tot = tl + td + ts
+        print(f"| {label} | {tl:.3f} | {td:.3f} | {ts:.3f} | {tot:.3f} | {tl / tot * 100:.1f} % | "
+              f"{(1 - tl / t_l32) * 100:.1f} % |")
+    print(f"\nhost-to-device rates: fp32 {X.numel() * 4 / t_l32 / 1e6:.1f} GB/s, "
+          f"8-bit {(q[0].numel() + 8 * q[1].numel()) / t_l8 / 1e6:.1f} GB/s\n")
+
+
+def main(argv) -> int:
+    if len(argv) < 2 or argv[1] not in ("width-sweep", "strategies", "loading"):
+        print(__doc__)
+        return 2
+    assert torch.cuda.is_available(), "the studies need a GPU"
+    name = argv[2] if len(argv) > 2 else {"width-sweep": "rmat20", "strategies": "reddit_like",
+                                          "loading": "products_like"}[argv[1]]
+    {"width-sweep": width_sweep, "strategies": strategies, "loading": loading}[argv[1]](name)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main(sys.argv))

@@ -29,11 +29,11 @@ def class_order(slots):
     return np.argsort(-cls, kind="stable").astype(np.int32)
 
 
-def check_plan(rowptr, colidx, val, n_cols, W, seed=0):
+def check_plan(rowptr, colidx, val, n_cols, W, seed=0, strategy=0):
     """aes_sample_build against the oracle, bit for bit.  Returns (plan, oracle plan)."""
-    ref = orc.sample_build(to_host(rowptr), to_host(colidx), to_host(val), W, seed=seed)
+    ref = orc.sample_build(to_host(rowptr), to_host(colidx), to_host(val), W, seed=seed, mode=strategy)
     plan = aes.aes_sample_build(to_dev(rowptr), to_dev(colidx), to_dev(val), n_cols, W, seed,
-                                want_eid=True, want_perm=True)
+                                strategy=strategy, want_eid=True, want_perm=True)
     torch.cuda.synchronize()
     S = int(ref[0][-1])
     assert np.array_equal(plan.s_rowptr.cpu().numpy(), ref[0]), "s_rowptr"
@@ -69,6 +69,11 @@ def check_quantize(X, scheme, gran):
     assert np.array_equal(Xq.cpu().numpy(), rq), "codes"
     assert np.array_equal(scale.cpu().numpy().view(np.uint32), rs.view(np.uint32)), "scale"
     assert np.array_equal(zero.cpu().numpy(), rz), "zero"
+    # Eq. 2 as a stand-alone pass: bit-identical to the oracle's dequantisation
+    Xhat = aes.aes_dequantize_features(Xq, scheme, gran, scale, zero)
+    torch.cuda.synchronize()
+    ref_hat = orc.dequantize(rq, scheme, gran, rs, rz)
+    assert np.array_equal(Xhat.cpu().numpy().view(np.uint32), ref_hat.view(np.uint32)), "x_hat"
     return (Xq, scale, zero), (rq, rs, rz)
 
 
@@ -80,6 +85,15 @@ def check_q8(plan, ref, q_dev, q_ref, scheme, gran, rows=None, use_perm=True, to
     Yh = Y.cpu().numpy()
     Yref, Yabs = orc.spmm_q8(ref[0], ref[1], ref[2], q_ref[0], scheme, gran, q_ref[1], q_ref[2], rows=rows,
                              want_abs=True)
+    if scheme == orc.Q_AFFINE_FLOOR_U8:
+        # x_hat = q*scale + zero is itself a difference of two rounded terms, so the
+        # rounding error of a row scales with sum |v| (|q*scale| + |zero|), not with the
+        # (possibly cancelling) |v * x_hat|: that is the denominator for this scheme.
+        n, F = q_ref[0].shape
+        sc = {0: q_ref[1][0], 1: q_ref[1][None, :], 2: q_ref[1][:, None]}[gran]
+        zr = {0: q_ref[2][0], 1: q_ref[2][None, :], 2: q_ref[2][:, None]}[gran]
+        mag = (np.abs(q_ref[0].astype(np.float32) * sc) + np.abs(zr)).astype(np.float32)
+        Yabs = orc.spmm_plan(ref[0], ref[1], np.abs(ref[2]), np.ascontiguousarray(mag), rows=rows)
     got = Yh if rows is None else Yh[rows]
     comp, glob = rel_err(got, Yref, Yabs)
     assert comp <= tol and glob <= tol, (comp, glob)

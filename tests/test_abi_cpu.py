@@ -60,16 +60,28 @@ def test_argument_errors_are_host_side(lib):
     import paper_2503_18427_amd as aes
     fake = 0x1000  # never dereferenced: argument checks come first
     sb = lib.aes_sample_build
-    assert sb(-1, 1, 0, fake, fake, fake, 4, 0, fake, fake, fake, None, None, fake, 1 << 20, None) == -1
+    assert sb(-1, 1, 0, fake, fake, fake, 4, 0, 0, fake, fake, fake, None, None, fake, 1 << 20, None) == -1
     assert "negative" in aes.aes_last_error()
-    assert sb(4, 1 << 31, 0, fake, fake, fake, 4, 0, fake, fake, fake, None, None, fake, 1 << 20, None) == -2
-    assert sb(4, 4, 8, fake, fake, fake, -3, 0, fake, fake, fake, None, None, fake, 1 << 20, None) == -1
-    assert sb(4, 4, 8, None, fake, fake, 4, 0, fake, fake, fake, None, None, fake, 1 << 20, None) == -1
-    assert sb(4, 4, 8, fake, None, fake, 4, 0, fake, fake, fake, None, None, fake, 1 << 20, None) == -1
-    assert sb(4, 4, 8, fake, fake, fake, 4, 0, fake, fake, fake, None, None, None, 0, None) == -3
-    assert sb(4, 4, 8, fake, fake, fake, 4, 0, fake, fake, fake, None, None, fake, 8, None) == -3
+    assert sb(4, 1 << 31, 0, fake, fake, fake, 4, 0, 0, fake, fake, fake, None, None, fake, 1 << 20, None) == -2
+    assert sb(4, 4, 8, fake, fake, fake, -3, 0, 0, fake, fake, fake, None, None, fake, 1 << 20, None) == -1
+    assert sb(4, 4, 8, None, fake, fake, 4, 0, 0, fake, fake, fake, None, None, fake, 1 << 20, None) == -1
+    assert sb(4, 4, 8, fake, None, fake, 4, 0, 0, fake, fake, fake, None, None, fake, 1 << 20, None) == -1
+    assert sb(4, 4, 8, fake, fake, fake, 4, 0, 0, fake, fake, fake, None, None, None, 0, None) == -3
+    assert sb(4, 4, 8, fake, fake, fake, 4, 0, 0, fake, fake, fake, None, None, fake, 8, None) == -3
     assert "workspace" in aes.aes_last_error()
-    assert sb(4, 4, 8, fake, fake, fake, 4, 0, fake, fake, fake, None, None, fake + 4, 1 << 20, None) == -3
+    assert sb(4, 4, 8, fake, fake, fake, 4, 0, 0, fake, fake, fake, None, None, fake + 4, 1 << 20, None) == -3
+
+    assert sb(4, 4, 8, fake, fake, fake, 4, 0, 3, fake, fake, fake, None, None, fake, 1 << 20, None) == -1
+    assert "strategy" in aes.aes_last_error()
+    ff = lib.aes_spmm_fused_f32
+    assert ff(4, 4, fake, fake, fake, -1, 0, 0, fake, 8, 8, fake, 8, None) == -1
+    assert ff(4, 4, fake, fake, fake, 16, 0, 5, fake, 8, 8, fake, 8, None) == -1
+    assert ff(4, 4, None, fake, fake, 16, 0, 0, fake, 8, 8, fake, 8, None) == -1
+    assert ff(4, 4, fake, fake, fake, 16, 0, 0, fake, 4, 8, fake, 8, None) == -1
+    fq = lib.aes_spmm_fused_q8
+    assert fq(4, 4, fake, fake, fake, 16, 0, 0, fake, 8, 8, 9, 1, fake, fake, fake, 8, None) == -1
+    assert fq(4, 4, fake, fake, fake, 16, 0, 0, fake, 8, 8, 1, 1, None, fake, fake, 8, None) == -1
+    assert fq(4, 4, fake, fake, fake, 1 << 21, 0, 0, fake, 8, 8, 1, 1, fake, fake, fake, 8, None) == -1
 
     f32 = lib.aes_spmm_f32
     assert f32(-1, 4, fake, fake, fake, None, fake, 8, 8, fake, 8, None) == -1
@@ -89,6 +101,14 @@ def test_argument_errors_are_host_side(lib):
     assert q(4, 8, fake, 8, 0, 1, fake, 8, fake, None, fake, 1 << 20, None) == -1  # affine needs zero
     assert q(4, 8, fake, 8, 1, 1, fake, 8, fake, None, None, 0, None) == -3
     assert q(4, 8, None, 8, 1, 2, fake, 8, fake, None, None, 0, None) == -1
+
+    dq = lib.aes_dequantize_features
+    assert dq(-1, 8, fake, 8, 1, 1, fake, None, fake, 8, None) == -1
+    assert dq(4, 8, fake, 4, 1, 1, fake, None, fake, 8, None) == -1
+    assert dq(4, 8, fake, 8, 0, 1, fake, None, fake, 8, None) == -1     # affine needs zero
+    assert dq(4, 8, fake, 8, 1, 1, None, None, fake, 8, None) == -1
+    assert dq(4, 8, None, 8, 1, 1, fake, None, fake, 8, None) == -1
+    assert dq(0, 8, None, 8, 1, 1, fake, None, None, 8, None) == 0
 
     q8 = lib.aes_spmm_q8
     assert q8(4, 4, fake, fake, fake, None, fake, 8, 8, 5, 1, fake, fake, fake, 8, None) == -1

@@ -50,6 +50,37 @@ def test_sample_build_bit_exact(G, W, seed):
     G.check_f32(plan, ref, X, use_perm=False)
 
 
+@pytest.mark.parametrize("strategy", [0, 1, 2])
+@pytest.mark.parametrize("W", [1, 4, 16, 48, 64, 256, 0])
+@pytest.mark.parametrize("seed", [0, 77])
+def test_strategies_and_fused_kernels(G, strategy, W, seed):
+    """The fixed AFS / SFS granularities, and the single-kernel (sample on the
+    fly) form: same slots and the same summation order as build + multiply, so
+    the outputs must be bit-identical to the plan path."""
+    import paper_2503_18427_amd as aes
+    rowptr, col, val, X, n_cols = _ragged_case(W + 100 * strategy, W, n=500, F=96)
+    plan, ref = G.check_plan(rowptr, col, val, n_cols, W, seed, strategy)
+    Y, _, _ = G.check_f32(plan, ref, X, use_perm=False)
+    d = [G.to_dev(a) for a in (rowptr, col, val)]
+    Xd = G.to_dev(X)
+    Yf = aes.aes_spmm_fused_f32(d[0], d[1], d[2], n_cols, W, Xd, seed, strategy=strategy)
+    torch.cuda.synchronize()
+    assert torch.equal(Yf, Y)
+    for scheme, gran in ((SYM, ROW), (AFF, COLUMN), (SYM, TENSOR)):
+        qd, qr = G.check_quantize(X, scheme, gran)
+        Yq, _, _ = G.check_q8(plan, ref, qd, qr, scheme, gran, use_perm=False)
+        Yqf = aes.aes_spmm_fused_q8(d[0], d[1], d[2], n_cols, W, qd[0], scheme, gran, qd[1], qd[2], seed,
+                                    strategy=strategy)
+        torch.cuda.synchronize()
+        assert torch.equal(Yqf, Yq)
+    # and against the oracle's own one-pass form
+    import oracle as orc
+    Yo, Yabs = orc.aes_spmm(rowptr, col, val, W, X, seed=seed, want_abs=True, mode=strategy)
+    from helpers import rel_err
+    comp, glob = rel_err(Yf.cpu().numpy(), Yo, Yabs)
+    assert comp <= G.F32_TOL and glob <= G.F32_TOL
+
+
 @pytest.mark.parametrize("name", ["tiny", "arxiv_small", "reddit_small", "products_small", "rmat12"])
 def test_small_workloads(G, name):
     rowptr, col, val, X, w = _workload(name)

@@ -135,3 +135,48 @@ def test_exact_path_is_identity(oracle):
     assert np.array_equal(s_rowptr, rowptr)
     assert np.array_equal(s_col, col)
     assert np.array_equal(s_eid, np.arange(col.size))
+
+
+def test_fixed_granularities_golden(oracle):
+    for ln in golden_lines("afs_sfs_vectors.txt"):
+        a, b, c = [p.split() for p in ln.split("|")]
+        mode, W, nnz = map(int, a)
+        N, cnt = map(int, b)
+        offs = [int(x) for x in c]
+        assert oracle.strategy(nnz, W, mode) == (N, cnt)
+        rowptr = np.array([0, nnz], dtype=np.int64)
+        col = np.arange(nnz, dtype=np.int32)
+        val = np.ones(nnz, dtype=np.float32)
+        s = oracle.sample_build(rowptr, col, val, W, seed=0, mode=mode)
+        assert s[3].tolist() == offs
+
+
+def test_speed_first_is_row_truncation(oracle):
+    """SFS keeps the first W entries of every long row: the product equals the
+    exact SpMM of the truncated matrix (scipy), an independent route."""
+    import scipy.sparse as sp
+    rng = np.random.default_rng(21)
+    deg = rng.integers(0, 120, size=150)
+    rowptr, col, val = random_csr(150, 300, deg, rng)
+    X = rng.standard_normal((300, 10)).astype(np.float32)
+    W = 16
+    keep = np.concatenate([np.arange(rowptr[r], min(rowptr[r + 1], rowptr[r] + W)) for r in range(150)])
+    t_rowptr = np.concatenate([[0], np.cumsum(np.minimum(deg, W))])
+    A = sp.csr_matrix((val[keep].astype(np.float64), col[keep], t_rowptr), shape=(150, 300))
+    Y = oracle.aes_spmm(rowptr, col, val, W, X, mode=2)
+    assert np.allclose(Y, A @ X.astype(np.float64), rtol=0, atol=1e-12)
+
+
+def test_accuracy_first_invariants(oracle):
+    rng = np.random.default_rng(22)
+    deg = rng.integers(0, 400, size=120)
+    rowptr, col, val = random_csr(120, 500, deg, rng)
+    for W in (4, 16, 48):
+        s_rowptr, s_col, s_val, s_eid = oracle.sample_build(rowptr, col, val, W, seed=0, mode=1)
+        for r in range(120):
+            nnz = int(deg[r])
+            e = s_eid[s_rowptr[r]:s_rowptr[r + 1]] - rowptr[r]
+            if nnz <= W:
+                assert e.tolist() == list(range(nnz))
+            else:
+                assert e.tolist() == [(i * 1429) % nnz for i in range(W)]
