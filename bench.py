@@ -58,8 +58,8 @@ def main() -> int:
     ap.add_argument("--cpu-rows", type=int, default=-1,
                     help="rows in the CPU oracle's sample (-1: all rows, 0: skip the CPU baseline)")
     ap.add_argument("--copy-probe", action="store_true",
-                    help="also launch a plain 1 GiB read + 1 GiB write elementwise kernel three times "
-                         "(the known-size reference for scaling rocprofv3 HBM counters)")
+                    help="mark the run as a counter-calibration run (kept for the rocprofv3 command lines; the "
+                         "plain 1 GiB read + 1 GiB write elementwise kernel they scale against always runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -191,13 +191,29 @@ def main() -> int:
         "roofline": roofline,
     }
 
-    if args.copy_probe:
-        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            torch.mul(src, 1.0, out=dst)
+    # Outside the timed step: the single-kernel (sample on the fly) forms of both multiplies, and a
+    # plain elementwise kernel that reads 1 GiB and writes 1 GiB (the stream ceiling of this machine, and
+    # the known-size reference the rocprofv3 HBM counters are scaled with).
+    def timed(fn, iters=5):
+        fn()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(iters + 1)]
+        ev[0].record()
+        for i in range(iters):
+            fn()
+            ev[i + 1].record()
         torch.cuda.synchronize()
-        del src, dst
+        return sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(iters))[iters // 2]
+
+    t_ff = timed(lambda: aes.aes_spmm_fused_f32(rowptr, colidx, val, n, W, X, Y=Y))
+    t_fq = timed(lambda: aes.aes_spmm_fused_q8(rowptr, colidx, val, n, W, qbuf[0], scheme, gran, qbuf[1], qbuf[2],
+                                               Y=Yq))
+    out["fused_single_kernel"] = {"spmm_fused_f32_ms": t_ff, "spmm_fused_q8_ms": t_fq,
+                                  "vs_build_plus_spmm_f32": (leg_ms["sample_build"] + leg_ms["spmm_f32"]) / t_ff}
+    src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+    dst = torch.empty_like(src)
+    t_cp = timed(lambda: torch.mul(src, 1.0, out=dst), iters=3)
+    out["stream_copy_GBps"] = 2.0 * (1 << 30) / (t_cp * 1e-3) / 1e9
+    del src, dst
 
     if args.cpu_rows != 0:
         n_cpu = n if args.cpu_rows < 0 else min(args.cpu_rows, n)
