@@ -145,6 +145,14 @@ int aes_sample_build(int64_t n_rows, int64_t n_cols, int64_t nnz,
  * written; padding columns F..ldy are not touched.
  *
  *   n_rows, n_cols  shape of A_s; X has n_cols rows
+ *   W               the width the plan was built with: an upper bound on the
+ *                   slots of any row, or 0 when there is none (unsampled plan,
+ *                   plain CSR).  It only selects the kernel variant: with
+ *                   W == 0 or W > 2048 rows longer than 2048 slots are shared by
+ *                   all wavefronts of a workgroup (partial sums added in a fixed
+ *                   order) instead of being left to one lane group.  A row with
+ *                   more slots than a non-zero W states is still computed
+ *                   correctly, only without that sharing.
  *   s_rowptr/s_col/s_val [dev]  a plan from aes_sample_build (or any CSR with
  *                   int64 rowptr, int32 colidx, float32 val); s_col / s_val may
  *                   be NULL only when the plan has no slots at all
@@ -157,7 +165,7 @@ int aes_sample_build(int64_t n_rows, int64_t n_cols, int64_t nnz,
  * The fast path needs X and Y 16-byte aligned and F, ldx, ldy multiples of 4;
  * anything else runs a slower element-wise kernel with the same results.
  */
-int aes_spmm_f32(int64_t n_rows, int64_t n_cols,
+int aes_spmm_f32(int64_t n_rows, int64_t n_cols, int32_t W,
                  const int64_t *s_rowptr, const int32_t *s_col, const float *s_val,
                  const int32_t *row_perm,
                  const float *X, int64_t ldx, int32_t F,
@@ -224,7 +232,7 @@ int aes_dequantize_features(int64_t n, int32_t F, const int8_t *Xq, int64_t ldq,
  * F and ldq multiples of 4, Y 16-byte aligned and ldy a multiple of 4;
  * anything else runs the element-wise kernel.
  */
-int aes_spmm_q8(int64_t n_rows, int64_t n_cols,
+int aes_spmm_q8(int64_t n_rows, int64_t n_cols, int32_t W,
                 const int64_t *s_rowptr, const int32_t *s_col, const float *s_val,
                 const int32_t *row_perm,
                 const int8_t *Xq, int64_t ldq, int32_t F,

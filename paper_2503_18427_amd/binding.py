@@ -27,11 +27,11 @@ SIGNATURES = {
                                           _vp]),
     "aes_spmm_fused_q8": (ctypes.c_int, [_i64, _i64, _vp, _vp, _vp, _i32, _u64, _i32, _vp, _i64, _i32, _i32, _i32,
                                          _vp, _vp, _vp, _i64, _vp]),
-    "aes_spmm_f32": (ctypes.c_int, [_i64, _i64, _vp, _vp, _vp, _vp, _vp, _i64, _i32, _vp, _i64, _vp]),
+    "aes_spmm_f32": (ctypes.c_int, [_i64, _i64, _i32, _vp, _vp, _vp, _vp, _vp, _i64, _i32, _vp, _i64, _vp]),
     "aes_quantize_workspace_bytes": (_sz, [_i64, _i32, _i32]),
     "aes_quantize_features": (ctypes.c_int, [_i64, _i32, _vp, _i64, _i32, _i32, _vp, _i64, _vp, _vp, _vp, _sz, _vp]),
     "aes_dequantize_features": (ctypes.c_int, [_i64, _i32, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _i64, _vp]),
-    "aes_spmm_q8": (ctypes.c_int, [_i64, _i64, _vp, _vp, _vp, _vp, _vp, _i64, _i32, _i32, _i32, _vp, _vp, _vp,
+    "aes_spmm_q8": (ctypes.c_int, [_i64, _i64, _i32, _vp, _vp, _vp, _vp, _vp, _i64, _i32, _i32, _i32, _vp, _vp, _vp,
                                    _i64, _vp]),
 }
 
@@ -171,7 +171,7 @@ def aes_spmm_f32(plan: Plan, X, Y=None, *, use_perm: bool = True, stream=None):
     if Y.shape[0] != plan.n_rows or Y.shape[1] != F:
         raise ValueError("Y has the wrong shape")
     perm = plan.row_perm if use_perm else None
-    _check(library().aes_spmm_f32(plan.n_rows, plan.n_cols, _ptr(plan.s_rowptr), _ptr(plan.s_col), _ptr(plan.s_val),
+    _check(library().aes_spmm_f32(plan.n_rows, plan.n_cols, plan.W, _ptr(plan.s_rowptr), _ptr(plan.s_col), _ptr(plan.s_val),
                                   _ptr(perm), _ptr(X), _ld(X), F, _ptr(Y), _ld(Y), _stream(stream)))
     return Y
 
@@ -218,7 +218,7 @@ def aes_spmm_q8(plan: Plan, Xq, scheme: int, granularity: int, scale, zero=None,
     if Y.shape[0] != plan.n_rows or Y.shape[1] != F:
         raise ValueError("Y has the wrong shape")
     perm = plan.row_perm if use_perm else None
-    _check(library().aes_spmm_q8(plan.n_rows, plan.n_cols, _ptr(plan.s_rowptr), _ptr(plan.s_col), _ptr(plan.s_val),
+    _check(library().aes_spmm_q8(plan.n_rows, plan.n_cols, plan.W, _ptr(plan.s_rowptr), _ptr(plan.s_col), _ptr(plan.s_val),
                                  _ptr(perm), _ptr(Xq), _ld(Xq), F, int(scheme), int(granularity), _ptr(scale),
                                  _ptr(zero), _ptr(Y), _ld(Y), _stream(stream)))
     return Y

@@ -128,6 +128,60 @@ quantize_rows_kernel(int64_t n, int32_t F, const float *__restrict__ X, int64_t 
     }
 }
 
+// Rows that fit one chunk (F <= 4 * LPR, aligned): every lane group takes RPG rows and
+// issues all their loads before the first reduction, so several 16-byte loads per lane
+// are in flight; the rows stay in registers until they are encoded.
+template <int LPR, int RPG>
+__global__ void __launch_bounds__(kBlock)
+quantize_rows_batched_kernel(int64_t n, int32_t F, const float *__restrict__ X, int64_t ldx, int affine_,
+                             int8_t *__restrict__ Xq, int64_t ldq, float *__restrict__ scale_out,
+                             float *__restrict__ zero_out)
+{
+    constexpr int kGroups = kBlock / LPR;
+    const bool affine = affine_ != 0;
+    const int lane = threadIdx.x % LPR;
+    const int64_t r0 = (static_cast<int64_t>(blockIdx.x) * kGroups + threadIdx.x / LPR) * RPG;
+    const int32_t f = lane * 4;
+    const bool lane_on = f < F;
+    float4 v[RPG];
+#pragma unroll
+    for (int j = 0; j < RPG; ++j) {
+        v[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (lane_on && r0 + j < n) v[j] = *reinterpret_cast<const float4 *>(X + (r0 + j) * ldx + f);
+    }
+#pragma unroll
+    for (int j = 0; j < RPG; ++j) {
+        const int64_t r = r0 + j;
+        if (r >= n) break;                                    // uniform within the group
+        const float x[4] = {v[j].x, v[j].y, v[j].z, v[j].w};
+        float lo = INFINITY, hi = -INFINITY;
+        if (lane_on) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float a = affine ? x[i] : fabsf(x[i]);
+                lo = fminf(lo, a);
+                hi = fmaxf(hi, a);
+            }
+        }
+#pragma unroll
+        for (int s = LPR / 2; s >= 1; s >>= 1) {
+            lo = fminf(lo, __shfl_xor(lo, s, LPR));
+            hi = fmaxf(hi, __shfl_xor(hi, s, LPR));
+        }
+        float d, scale, zero;
+        group_constants(lo, hi, affine, d, scale, zero);
+        if (lane == 0) {
+            scale_out[r] = scale;
+            if (zero_out) zero_out[r] = zero;
+        }
+        if (lane_on) {
+            const uint32_t w = encode(x[0], lo, d, scale, affine) | (encode(x[1], lo, d, scale, affine) << 8) |
+                               (encode(x[2], lo, d, scale, affine) << 16) | (encode(x[3], lo, d, scale, affine) << 24);
+            *reinterpret_cast<uint32_t *>(Xq + r * ldq + f) = w;
+        }
+    }
+}
+
 // ---- per column / per tensor --------------------------------------------------
 // partial[(slab*2 + 0) * F + c] = min, [(slab*2 + 1) * F + c] = max over the slab's rows
 __global__ void __launch_bounds__(kBlock)
@@ -322,12 +376,18 @@ int slabs_for(int64_t n)
     return static_cast<int>(s < 1 ? 1 : s > kMaxSlabs ? kMaxSlabs : s);
 }
 
+constexpr int kRowsPerGroup = 4;
+
 template <int LPR, int VEC>
 void launch_rows(int64_t n, int32_t F, const float *X, int64_t ldx, int affine, int8_t *Xq, int64_t ldq,
                  float *scale, float *zero, hipStream_t stream)
 {
     const unsigned grid = static_cast<unsigned>(aes::ceil_div(n, kBlock / LPR));
-    if (F <= LPR * VEC)
+    if (VEC == 4 && F <= LPR * VEC) {
+        const unsigned bgrid = static_cast<unsigned>(aes::ceil_div(n, static_cast<int64_t>(kBlock / LPR) * kRowsPerGroup));
+        quantize_rows_batched_kernel<LPR, kRowsPerGroup><<<dim3(bgrid), dim3(kBlock), 0, stream>>>(n, F, X, ldx, affine, Xq,
+                                                                                                   ldq, scale, zero);
+    } else if (F <= LPR * VEC)
         quantize_rows_kernel<LPR, VEC, true><<<dim3(grid), dim3(kBlock), 0, stream>>>(n, F, X, ldx, affine, Xq, ldq, scale, zero);
     else
         quantize_rows_kernel<LPR, VEC, false><<<dim3(grid), dim3(kBlock), 0, stream>>>(n, F, X, ldx, affine, Xq, ldq, scale, zero);

@@ -126,11 +126,166 @@ __device__ inline void wave_lds_sync()
 }
 
 // ---- the kernel ---------------------------------------------------------------
+// What a lane group needs to know about its row.
+struct RowInfo {
+    int64_t k_begin;     // first slot (plan) or first CSR entry (fused)
+    int64_t n_slots;
+    int64_t row_nnz;     // fused only: entries of the CSR row
+    int32_t samp_n;      // fused, sampled row: N and sample_cnt of Table 1, per-row offset
+    int32_t samp_cnt;
+    uint32_t s_r;
+    bool sampled;
+};
+
+template <bool FUSED>
+__device__ inline RowInfo row_info(const SlotSource &src, int64_t r)
+{
+    RowInfo ri;
+    ri.k_begin = src.rowptr[r];
+    ri.n_slots = src.rowptr[r + 1] - ri.k_begin;
+    ri.row_nnz = ri.n_slots;
+    ri.sampled = false;
+    ri.samp_n = 0;
+    ri.samp_cnt = 1;
+    ri.s_r = 0;
+    if (FUSED && src.W != 0 && ri.row_nnz > src.W) {
+        ri.sampled = true;
+        aes::sample_strategy(ri.row_nnz, src.W, src.strategy, ri.samp_n, ri.samp_cnt);
+        ri.n_slots = static_cast<int64_t>(ri.samp_n) * ri.samp_cnt;
+        ri.s_r = aes::row_offset(src.seed, r);
+    }
+    return ri;
+}
+
+// Adds the row's tiles first_tile, first_tile + tile_step, ... into acc (one chunk of
+// features).  side / vsum collect the sums the 8-bit epilogue needs.
+template <int LPR, int UNROLL, typename Feat, int QMODE, bool QUANT, bool FUSED>
+__device__ __forceinline__ void accumulate_tiles(const SlotSource &src, const RowInfo &ri, int2 *my_stage, int lane,
+                                                 bool lane_on, const typename Feat::elem_t *__restrict__ X,
+                                                 int64_t ldx, int32_t f, const QParams &qp, int64_t first_tile,
+                                                 int64_t tile_step, float (&acc)[Feat::VEC], float &side,
+                                                 float &vsum)
+{
+    for (int64_t t0 = first_tile * kTile; t0 < ri.n_slots; t0 += tile_step * kTile) {
+        const int m = static_cast<int>(ri.n_slots - t0 < kTile ? ri.n_slots - t0 : kTile);
+        wave_lds_sync();                             // previous tile fully consumed
+#pragma unroll
+        for (int s = lane; s < kTile; s += LPR) {
+            if (s < m) {
+                int64_t e = ri.k_begin + t0 + s;
+                if (FUSED && ri.sampled)
+                    e = aes::sampled_entry(ri.k_begin, ri.row_nnz, ri.samp_n, ri.samp_cnt, ri.s_r,
+                                           static_cast<int32_t>(t0) + s);
+                const int32_t c = src.col[e];
+                float v = src.val[e];
+                if (QUANT) {
+                    if (QMODE == kQRowScale) {
+                        if (qp.affine) side = __builtin_fmaf(v, qp.zero[c], side);
+                        v *= qp.scale[c];
+                    } else if (qp.affine) {
+                        side += v;
+                    }
+                }
+                my_stage[s] = make_int2(c, __float_as_int(v));
+            }
+        }
+        wave_lds_sync();                             // tile visible to the whole group
+        if (lane_on) {
+            // UNROLL gathers are issued back to back before the first one is consumed.
+            int k = 0;
+            for (; k + UNROLL <= m; k += UNROLL) {
+                int2 cv[UNROLL];
+                typename Feat::raw_t x[UNROLL];
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) cv[u] = my_stage[k + u];
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) x[u] = Feat::load(X + static_cast<int64_t>(cv[u].x) * ldx + f);
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) {
+                    Feat::fma(acc, __int_as_float(cv[u].y), x[u]);
+                    if (Feat::kBias != 0) vsum += __int_as_float(cv[u].y);
+                }
+            }
+            // Ragged last round: the missing slots are predicated off (value 0, no load), so
+            // short rows and row tails keep their gathers in flight together as well.
+            if (k < m) {
+                int2 cv[UNROLL];
+                typename Feat::raw_t x[UNROLL];
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) cv[u] = (k + u < m) ? my_stage[k + u] : make_int2(-1, 0);
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) {
+                    x[u] = typename Feat::raw_t{};
+                    if (cv[u].x >= 0) x[u] = Feat::load(X + static_cast<int64_t>(cv[u].x) * ldx + f);
+                }
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) {
+                    Feat::fma(acc, __int_as_float(cv[u].y), x[u]);
+                    if (Feat::kBias != 0) vsum += __int_as_float(cv[u].y);
+                }
+            }
+        }
+    }
+}
+
+// Removes the loader's bias, applies the 8-bit group constants and stores one chunk of Y[r, :].
+// `side` must already be summed over the lanes of the group.
+template <typename Feat, int QMODE, bool QUANT>
+__device__ __forceinline__ void finish_chunk(float (&acc)[Feat::VEC], float side, float vsum, bool lane_on, int32_t f,
+                                             const QParams &qp, float *__restrict__ y)
+{
+    constexpr int VEC = Feat::VEC;
+    if (Feat::kBias != 0) {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) acc[i] = __builtin_fmaf(-static_cast<float>(Feat::kBias), vsum, acc[i]);
+    }
+    if (!lane_on) return;
+    if (QUANT) {
+        // x_hat = q*scale_g + zero_g, with the group constants taken out of the sum:
+        //   per tensor / column: Y = scale_c * sum(v*q) + zero_c * sum(v)
+        //   per row            : Y = sum((v*scale_col)*q) + sum(v*zero_col)
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) {
+            if (QMODE == kQRowScale) {
+                if (qp.affine) acc[i] += side;
+            } else {
+                const int g = qp.granularity == AES_Q_PER_COLUMN ? f + i : 0;
+                acc[i] *= qp.scale[g];
+                if (qp.affine) acc[i] = __builtin_fmaf(side, qp.zero[g], acc[i]);
+            }
+        }
+    }
+    if constexpr (VEC % 4 == 0) {
+#pragma unroll
+        for (int i = 0; i < VEC; i += 4)
+            *reinterpret_cast<float4 *>(y + i) = make_float4(acc[i], acc[i + 1], acc[i + 2], acc[i + 3]);
+    } else {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) y[i] = acc[i];
+    }
+}
+
+template <int LPR>
+__device__ __forceinline__ float group_sum(float v)
+{
+#pragma unroll
+    for (int d = LPR / 2; d >= 1; d >>= 1) v += __shfl_xor(v, d, LPR);
+    return v;
+}
+
+// Rows with more slots than this are not left to one lane group: all groups of the
+// workgroup share such a row (LONG variant, used when the caller's width allows them).
+constexpr int kLongRow = 2048;
+
 // LPR   lanes per output row (8, 16, 32 or 64); a wavefront holds 64/LPR rows
 // Feat  feature loader: Feat::VEC features per lane per chunk (4 on the aligned
 //       fast paths, 1 otherwise)
 // QMODE see above; QUANT: apply the 8-bit epilogue; FUSED: sample from the CSR on the fly
-template <int LPR, int UNROLL, typename Feat, int QMODE, bool QUANT, bool FUSED>
+// LONG  rows above kLongRow slots are processed by the whole workgroup: its lane groups
+//       take the row's tiles round-robin and their partial sums are added in a fixed
+//       order through LDS, so the result stays bit-reproducible.  Without LONG the
+//       kernel has no workgroup barrier at all.
+template <int LPR, int UNROLL, typename Feat, int QMODE, bool QUANT, bool FUSED, bool LONG>
 __global__ void __launch_bounds__(kBlock)
 spmm_rows_kernel(int64_t n_rows, SlotSource src, const int32_t *__restrict__ row_perm,
                  const typename Feat::elem_t *__restrict__ X, int64_t ldx, int32_t F, QParams qp,
@@ -146,141 +301,91 @@ spmm_rows_kernel(int64_t n_rows, SlotSource src, const int32_t *__restrict__ row
     const int group = (threadIdx.x % kWave) / LPR;
     const int lane = threadIdx.x % LPR;
     const int64_t slot_in_order = static_cast<int64_t>(blockIdx.x) * kRowsPerBlock + wave * kGroups + group;
-    if (slot_in_order >= n_rows) return;                 // whole group leaves together
-    const int64_t r = row_perm ? static_cast<int64_t>(row_perm[slot_in_order]) : slot_in_order;
-    const int64_t k_begin = src.rowptr[r];
-    int64_t n_slots = src.rowptr[r + 1] - k_begin;
-    // FUSED: a row longer than W is sampled; slot k then maps to a CSR entry by Eq. 3
-    [[maybe_unused]] const int64_t row_nnz = n_slots;
-    [[maybe_unused]] bool sampled = false;
-    [[maybe_unused]] int32_t samp_n = 0, samp_cnt = 1;
-    [[maybe_unused]] uint32_t s_r = 0;
-    if (FUSED && src.W != 0 && row_nnz > src.W) {
-        sampled = true;
-        aes::sample_strategy(row_nnz, src.W, src.strategy, samp_n, samp_cnt);
-        n_slots = static_cast<int64_t>(samp_n) * samp_cnt;
-        s_r = aes::row_offset(src.seed, r);
-    }
+    const bool valid = slot_in_order < n_rows;
+    if (!LONG && !valid) return;                         // whole group leaves together
     int2 *my_stage = stage[wave][group];
+    int64_t r = 0;
+    RowInfo ri = {};
+    if (valid) {
+        r = row_perm ? static_cast<int64_t>(row_perm[slot_in_order]) : slot_in_order;
+        ri = row_info<FUSED>(src, r);
+    }
+    const bool is_long = LONG && valid && ri.n_slots > kLongRow;
 
-    for (int32_t f0 = 0; f0 < F; f0 += LPR * VEC) {
-        const int32_t f = f0 + lane * VEC;
-        const bool lane_on = f < F;
-        float acc[VEC];
+    if (valid && !is_long) {
+        for (int32_t f0 = 0; f0 < F; f0 += LPR * VEC) {
+            const int32_t f = f0 + lane * VEC;
+            const bool lane_on = f < F;
+            float acc[VEC];
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) acc[i] = 0.0f;
-        float side = 0.0f;      // this lane's share of sum(val * zero-point weight), see epilogue
-        float vsum = 0.0f;      // sum of the staged edge values (only when the loader is biased)
+            for (int i = 0; i < VEC; ++i) acc[i] = 0.0f;
+            float side = 0.0f;      // this lane's share of sum(val * zero-point weight)
+            float vsum = 0.0f;      // sum of the staged edge values (only when the loader is biased)
+            accumulate_tiles<LPR, UNROLL, Feat, QMODE, QUANT, FUSED>(src, ri, my_stage, lane, lane_on, X, ldx, f, qp, 0,
+                                                                     1, acc, side, vsum);
+            if (QUANT && qp.affine) side = group_sum<LPR>(side);
+            finish_chunk<Feat, QMODE, QUANT>(acc, side, vsum, lane_on, f, qp, Y + r * ldy + f);
+        }
+    }
 
-        for (int64_t t0 = 0; t0 < n_slots; t0 += kTile) {
-            const int m = static_cast<int>(n_slots - t0 < kTile ? n_slots - t0 : kTile);
-            wave_lds_sync();                             // previous tile fully consumed
+    if constexpr (LONG) {
+        __shared__ int sh_n_long;
+        __shared__ int64_t sh_long_row[kRowsPerBlock];
+        __shared__ float sh_part[kRowsPerBlock][LPR][VEC + 2];
+        if (threadIdx.x == 0) sh_n_long = 0;
+        __syncthreads();
+        if (is_long && lane == 0) sh_long_row[atomicAdd(&sh_n_long, 1)] = r;   // order affects no sum
+        __syncthreads();
+        const int n_long = sh_n_long;
+        const int gib = wave * kGroups + group;          // this group's index in the workgroup
+        for (int i = 0; i < n_long; ++i) {
+            const int64_t lr = sh_long_row[i];
+            const RowInfo lri = row_info<FUSED>(src, lr);
+            for (int32_t f0 = 0; f0 < F; f0 += LPR * VEC) {
+                const int32_t f = f0 + lane * VEC;
+                const bool lane_on = f < F;
+                float acc[VEC];
 #pragma unroll
-            for (int s = lane; s < kTile; s += LPR) {
-                if (s < m) {
-                    int64_t e = k_begin + t0 + s;
-                    if (FUSED && sampled)
-                        e = aes::sampled_entry(k_begin, row_nnz, samp_n, samp_cnt, s_r, static_cast<int32_t>(t0) + s);
-                    const int32_t c = src.col[e];
-                    float v = src.val[e];
-                    if (QUANT) {
-                        if (QMODE == kQRowScale) {
-                            if (qp.affine) side = __builtin_fmaf(v, qp.zero[c], side);
-                            v *= qp.scale[c];
-                        } else if (qp.affine) {
-                            side += v;
-                        }
+                for (int j = 0; j < VEC; ++j) acc[j] = 0.0f;
+                float side = 0.0f, vsum = 0.0f;
+                accumulate_tiles<LPR, UNROLL, Feat, QMODE, QUANT, FUSED>(src, lri, my_stage, lane, lane_on, X, ldx, f,
+                                                                         qp, gib, kRowsPerBlock, acc, side, vsum);
+                if (QUANT && qp.affine) side = group_sum<LPR>(side);
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) sh_part[gib][lane][j] = acc[j];
+                sh_part[gib][lane][VEC] = side;
+                sh_part[gib][lane][VEC + 1] = vsum;
+                __syncthreads();
+                if (gib == 0) {
+                    for (int g = 1; g < kRowsPerBlock; ++g) {   // fixed order: bit-reproducible
+#pragma unroll
+                        for (int j = 0; j < VEC; ++j) acc[j] += sh_part[g][lane][j];
+                        side += sh_part[g][lane][VEC];
+                        vsum += sh_part[g][lane][VEC + 1];
                     }
-                    my_stage[s] = make_int2(c, __float_as_int(v));
+                    finish_chunk<Feat, QMODE, QUANT>(acc, side, vsum, lane_on, f, qp, Y + lr * ldy + f);
                 }
-            }
-            wave_lds_sync();                             // tile visible to the whole group
-            if (lane_on) {
-                // UNROLL gathers are issued back to back before the first one is consumed.
-                int k = 0;
-                for (; k + UNROLL <= m; k += UNROLL) {
-                    int2 cv[UNROLL];
-                    typename Feat::raw_t x[UNROLL];
-#pragma unroll
-                    for (int u = 0; u < UNROLL; ++u) cv[u] = my_stage[k + u];
-#pragma unroll
-                    for (int u = 0; u < UNROLL; ++u) x[u] = Feat::load(X + static_cast<int64_t>(cv[u].x) * ldx + f);
-#pragma unroll
-                    for (int u = 0; u < UNROLL; ++u) {
-                        Feat::fma(acc, __int_as_float(cv[u].y), x[u]);
-                        if (Feat::kBias != 0) vsum += __int_as_float(cv[u].y);
-                    }
-                }
-                // Ragged last round: the missing slots are predicated off (value 0, no load), so
-                // short rows and row tails keep their gathers in flight together as well.
-                if (k < m) {
-                    int2 cv[UNROLL];
-                    typename Feat::raw_t x[UNROLL];
-#pragma unroll
-                    for (int u = 0; u < UNROLL; ++u) cv[u] = (k + u < m) ? my_stage[k + u] : make_int2(-1, 0);
-#pragma unroll
-                    for (int u = 0; u < UNROLL; ++u) {
-                        x[u] = typename Feat::raw_t{};
-                        if (cv[u].x >= 0) x[u] = Feat::load(X + static_cast<int64_t>(cv[u].x) * ldx + f);
-                    }
-#pragma unroll
-                    for (int u = 0; u < UNROLL; ++u) {
-                        Feat::fma(acc, __int_as_float(cv[u].y), x[u]);
-                        if (Feat::kBias != 0) vsum += __int_as_float(cv[u].y);
-                    }
-                }
-            }
-        }
-
-        if (Feat::kBias != 0) {
-#pragma unroll
-            for (int i = 0; i < VEC; ++i) acc[i] = __builtin_fmaf(-static_cast<float>(Feat::kBias), vsum, acc[i]);
-        }
-        if (QUANT) {
-            // x_hat = q*scale_g + zero_g, with the group constants taken out of the sum:
-            //   per tensor / column: Y = scale_c * sum(v*q) + zero_c * sum(v)
-            //   per row            : Y = sum((v*scale_col)*q) + sum(v*zero_col)
-            if (qp.affine) {
-#pragma unroll
-                for (int d = LPR / 2; d >= 1; d >>= 1) side += __shfl_xor(side, d, LPR);
-            }
-            if (lane_on) {
-#pragma unroll
-                for (int i = 0; i < VEC; ++i) {
-                    if (QMODE == kQRowScale) {
-                        if (qp.affine) acc[i] += side;
-                    } else {
-                        const int g = qp.granularity == AES_Q_PER_COLUMN ? f + i : 0;
-                        acc[i] *= qp.scale[g];
-                        if (qp.affine) acc[i] = __builtin_fmaf(side, qp.zero[g], acc[i]);
-                    }
-                }
-            }
-        }
-        if (lane_on) {
-            float *y = Y + r * ldy + f;
-            if constexpr (VEC % 4 == 0) {
-#pragma unroll
-                for (int i = 0; i < VEC; i += 4)
-                    *reinterpret_cast<float4 *>(y + i) = make_float4(acc[i], acc[i + 1], acc[i + 2], acc[i + 3]);
-            } else {
-#pragma unroll
-                for (int i = 0; i < VEC; ++i) y[i] = acc[i];
+                __syncthreads();
             }
         }
     }
 }
 
 template <int LPR, int UNROLL, typename Feat, int QMODE, bool QUANT, bool FUSED>
-int launch_rows(int64_t n_rows, const SlotSource &src,
+int launch_rows(bool long_rows, int64_t n_rows, const SlotSource &src,
                 const int32_t *row_perm, const typename Feat::elem_t *X, int64_t ldx, int32_t F, QParams qp,
                 float *Y, int64_t ldy, hipStream_t stream, const char *what)
 {
     constexpr int kRowsPerBlock = (kWave / LPR) * aes::kWavesPerBlock;
     const int64_t grid = aes::ceil_div(n_rows, kRowsPerBlock);
     if (grid > INT32_MAX) return aes::fail(AES_ERR_UNSUPPORTED, "%s: n_rows=%lld too large", what, (long long)n_rows);
-    spmm_rows_kernel<LPR, UNROLL, Feat, QMODE, QUANT, FUSED>
-        <<<dim3(static_cast<unsigned>(grid)), dim3(kBlock), 0, stream>>>(n_rows, src, row_perm, X, ldx, F, qp, Y, ldy);
+    const dim3 g(static_cast<unsigned>(grid)), b(kBlock);
+    if (long_rows)
+        spmm_rows_kernel<LPR, UNROLL, Feat, QMODE, QUANT, FUSED, true>
+            <<<g, b, 0, stream>>>(n_rows, src, row_perm, X, ldx, F, qp, Y, ldy);
+    else
+        spmm_rows_kernel<LPR, UNROLL, Feat, QMODE, QUANT, FUSED, false>
+            <<<g, b, 0, stream>>>(n_rows, src, row_perm, X, ldx, F, qp, Y, ldy);
     return aes::check_launch(what);
 }
 
@@ -291,16 +396,20 @@ int lanes_per_row(int32_t F, int vec)
     return l < 8 ? 8 : l > 64 ? 64 : l;
 }
 
+// Rows can exceed kLongRow slots only without sampling (W == 0) or with a very wide W.
+bool long_rows_possible(int32_t W) { return W == 0 || W > kLongRow; }
+
 // Vector path: pick the lane-group width from F.
 template <typename Feat, int QMODE, bool QUANT, bool FUSED>
-int dispatch_lanes(int64_t n_rows, const SlotSource &src, const int32_t *row_perm, const typename Feat::elem_t *X,
-                   int64_t ldx, int32_t F, QParams qp, float *Y, int64_t ldy, hipStream_t stream, const char *what)
+int dispatch_lanes(bool lr, int64_t n_rows, const SlotSource &src, const int32_t *row_perm,
+                   const typename Feat::elem_t *X, int64_t ldx, int32_t F, QParams qp, float *Y, int64_t ldy,
+                   hipStream_t stream, const char *what)
 {
     switch (lanes_per_row(F, Feat::VEC)) {
-        case 8: return launch_rows<8, 8, Feat, QMODE, QUANT, FUSED>(n_rows, src, row_perm, X, ldx, F, qp, Y, ldy, stream, what);
-        case 16: return launch_rows<16, 8, Feat, QMODE, QUANT, FUSED>(n_rows, src, row_perm, X, ldx, F, qp, Y, ldy, stream, what);
-        case 32: return launch_rows<32, 8, Feat, QMODE, QUANT, FUSED>(n_rows, src, row_perm, X, ldx, F, qp, Y, ldy, stream, what);
-        default: return launch_rows<64, 8, Feat, QMODE, QUANT, FUSED>(n_rows, src, row_perm, X, ldx, F, qp, Y, ldy, stream, what);
+        case 8: return launch_rows<8, 8, Feat, QMODE, QUANT, FUSED>(lr, n_rows, src, row_perm, X, ldx, F, qp, Y, ldy, stream, what);
+        case 16: return launch_rows<16, 8, Feat, QMODE, QUANT, FUSED>(lr, n_rows, src, row_perm, X, ldx, F, qp, Y, ldy, stream, what);
+        case 32: return launch_rows<32, 8, Feat, QMODE, QUANT, FUSED>(lr, n_rows, src, row_perm, X, ldx, F, qp, Y, ldy, stream, what);
+        default: return launch_rows<64, 8, Feat, QMODE, QUANT, FUSED>(lr, n_rows, src, row_perm, X, ldx, F, qp, Y, ldy, stream, what);
     }
 }
 
@@ -309,9 +418,10 @@ int run_f32(const char *what, int64_t n_rows, const SlotSource &src, const int32
             int64_t ldx, int32_t F, float *Y, int64_t ldy, hipStream_t stream)
 {
     const bool fast = aes::aligned(X, 16) && aes::aligned(Y, 16) && F % 4 == 0 && ldx % 4 == 0 && ldy % 4 == 0;
+    const bool lr = long_rows_possible(src.W);
     QParams qp = {nullptr, nullptr, 0, 0};
-    if (fast) return dispatch_lanes<FeatF32<4>, kQNone, false, FUSED>(n_rows, src, row_perm, X, ldx, F, qp, Y, ldy, stream, what);
-    return launch_rows<64, 4, FeatF32<1>, kQNone, false, FUSED>(n_rows, src, row_perm, X, ldx, F, qp, Y, ldy, stream, what);
+    if (fast) return dispatch_lanes<FeatF32<4>, kQNone, false, FUSED>(lr, n_rows, src, row_perm, X, ldx, F, qp, Y, ldy, stream, what);
+    return launch_rows<64, 4, FeatF32<1>, kQNone, false, FUSED>(lr, n_rows, src, row_perm, X, ldx, F, qp, Y, ldy, stream, what);
 }
 
 // 8-bit features: 4 codes per lane when rows are 4-byte aligned, else element-wise.
@@ -319,9 +429,10 @@ template <bool SIGNED, int QMODE, bool FUSED>
 int dispatch_q8(bool fast, int64_t n_rows, const SlotSource &src, const int32_t *row_perm, const int8_t *Xq,
                 int64_t ldq, int32_t F, QParams qp, float *Y, int64_t ldy, hipStream_t stream, const char *what)
 {
+    const bool lr = long_rows_possible(src.W);
     if (fast)
-        return dispatch_lanes<FeatQ8<4, SIGNED>, QMODE, true, FUSED>(n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
-    return launch_rows<64, 4, FeatQ8<1, SIGNED>, QMODE, true, FUSED>(n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
+        return dispatch_lanes<FeatQ8<4, SIGNED>, QMODE, true, FUSED>(lr, n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
+    return launch_rows<64, 4, FeatQ8<1, SIGNED>, QMODE, true, FUSED>(lr, n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
 }
 
 template <bool FUSED>
@@ -376,7 +487,7 @@ int check_common(const char *what, int64_t n_rows, int64_t n_cols, const int64_t
 
 }  // namespace
 
-extern "C" int aes_spmm_f32(int64_t n_rows, int64_t n_cols,
+extern "C" int aes_spmm_f32(int64_t n_rows, int64_t n_cols, int32_t W,
                             const int64_t *s_rowptr, const int32_t *s_col, const float *s_val,
                             const int32_t *row_perm,
                             const float *X, int64_t ldx, int32_t F,
@@ -384,12 +495,13 @@ extern "C" int aes_spmm_f32(int64_t n_rows, int64_t n_cols,
 {
     const char *what = "aes_spmm_f32";
     if (int rc = check_common(what, n_rows, n_cols, s_rowptr, s_col, s_val, X, ldx, F, Y, ldy)) return rc;
+    if (int rc = check_sampling(what, W, AES_STRATEGY_ADAPTIVE)) return rc;
     if (n_rows == 0) return AES_OK;
-    const SlotSource src = {s_rowptr, s_col, s_val, 0, 0, 0};
+    const SlotSource src = {s_rowptr, s_col, s_val, W, 0, 0};   // W: only the bound on slots per row
     return run_f32<false>(what, n_rows, src, row_perm, X, ldx, F, Y, ldy, static_cast<hipStream_t>(stream));
 }
 
-extern "C" int aes_spmm_q8(int64_t n_rows, int64_t n_cols,
+extern "C" int aes_spmm_q8(int64_t n_rows, int64_t n_cols, int32_t W,
                            const int64_t *s_rowptr, const int32_t *s_col, const float *s_val,
                            const int32_t *row_perm,
                            const int8_t *Xq, int64_t ldq, int32_t F,
@@ -399,7 +511,8 @@ extern "C" int aes_spmm_q8(int64_t n_rows, int64_t n_cols,
 {
     const char *what = "aes_spmm_q8";
     if (int rc = check_common(what, n_rows, n_cols, s_rowptr, s_col, s_val, Xq, ldq, F, Y, ldy)) return rc;
-    const SlotSource src = {s_rowptr, s_col, s_val, 0, 0, 0};
+    if (int rc = check_sampling(what, W, AES_STRATEGY_ADAPTIVE)) return rc;
+    const SlotSource src = {s_rowptr, s_col, s_val, W, 0, 0};   // W: only the bound on slots per row
     return run_q8<false>(what, n_rows, src, row_perm, Xq, ldq, F, scheme, granularity, scale, zero, Y, ldy,
                          static_cast<hipStream_t>(stream));
 }

@@ -84,14 +84,15 @@ def test_argument_errors_are_host_side(lib):
     assert fq(4, 4, fake, fake, fake, 1 << 21, 0, 0, fake, 8, 8, 1, 1, fake, fake, fake, 8, None) == -1
 
     f32 = lib.aes_spmm_f32
-    assert f32(-1, 4, fake, fake, fake, None, fake, 8, 8, fake, 8, None) == -1
-    assert f32(4, 4, fake, fake, fake, None, fake, 8, 0, fake, 8, None) == -1
-    assert f32(4, 4, fake, fake, fake, None, fake, 4, 8, fake, 8, None) == -1      # ldx < F
-    assert f32(4, 4, fake, fake, fake, None, fake, 8, 8, fake, 4, None) == -1      # ldy < F
-    assert f32(4, 4, None, fake, fake, None, fake, 8, 8, fake, 8, None) == -1
-    assert f32(4, 4, fake, fake, fake, None, None, 8, 8, fake, 8, None) == -1
-    assert f32(4, 4, fake, fake, fake, None, fake, 8, 8, None, 8, None) == -1
-    assert f32(0, 4, fake, fake, fake, None, fake, 8, 8, None, 8, None) == 0       # nothing to do
+    assert f32(-1, 4, 0, fake, fake, fake, None, fake, 8, 8, fake, 8, None) == -1
+    assert f32(4, 4, 0, fake, fake, fake, None, fake, 8, 0, fake, 8, None) == -1
+    assert f32(4, 4, 0, fake, fake, fake, None, fake, 4, 8, fake, 8, None) == -1      # ldx < F
+    assert f32(4, 4, 0, fake, fake, fake, None, fake, 8, 8, fake, 4, None) == -1      # ldy < F
+    assert f32(4, 4, 0, None, fake, fake, None, fake, 8, 8, fake, 8, None) == -1
+    assert f32(4, 4, 0, fake, fake, fake, None, None, 8, 8, fake, 8, None) == -1
+    assert f32(4, 4, 0, fake, fake, fake, None, fake, 8, 8, None, 8, None) == -1
+    assert f32(0, 4, 0, fake, fake, fake, None, fake, 8, 8, None, 8, None) == 0       # nothing to do
+    assert f32(4, 4, -1, fake, fake, fake, None, fake, 8, 8, fake, 8, None) == -1     # bad W
 
     q = lib.aes_quantize_features
     assert q(-1, 8, fake, 8, 1, 1, fake, 8, fake, fake, fake, 1 << 20, None) == -1
@@ -111,11 +112,11 @@ def test_argument_errors_are_host_side(lib):
     assert dq(0, 8, None, 8, 1, 1, fake, None, None, 8, None) == 0
 
     q8 = lib.aes_spmm_q8
-    assert q8(4, 4, fake, fake, fake, None, fake, 8, 8, 5, 1, fake, fake, fake, 8, None) == -1
-    assert q8(4, 4, fake, fake, fake, None, fake, 8, 8, 1, 5, fake, fake, fake, 8, None) == -1
-    assert q8(4, 4, fake, fake, fake, None, fake, 8, 8, 1, 1, None, fake, fake, 8, None) == -1
-    assert q8(4, 4, fake, fake, fake, None, fake, 8, 8, 0, 1, fake, None, fake, 8, None) == -1
-    assert q8(0, 4, fake, fake, fake, None, fake, 8, 8, 1, 1, fake, None, None, 8, None) == 0
+    assert q8(4, 4, 0, fake, fake, fake, None, fake, 8, 8, 5, 1, fake, fake, fake, 8, None) == -1
+    assert q8(4, 4, 0, fake, fake, fake, None, fake, 8, 8, 1, 5, fake, fake, fake, 8, None) == -1
+    assert q8(4, 4, 0, fake, fake, fake, None, fake, 8, 8, 1, 1, None, fake, fake, 8, None) == -1
+    assert q8(4, 4, 0, fake, fake, fake, None, fake, 8, 8, 0, 1, fake, None, fake, 8, None) == -1
+    assert q8(0, 4, 0, fake, fake, fake, None, fake, 8, 8, 1, 1, fake, None, None, 8, None) == 0
 
 
 def test_binding_rejects_host_tensors():

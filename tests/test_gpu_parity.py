@@ -199,3 +199,83 @@ def test_side_stream(G):
         Y1 = aes.aes_spmm_f32(plan, Xd)
     s.synchronize()
     assert torch.equal(Y0, Y1)
+
+
+def test_hip_graph_capture_replays(G):
+    """Every entry point only enqueues kernels on the caller's stream (no
+    allocation, no memset, no synchronisation), so a whole step can be captured
+    in a HIP graph; each replay must reproduce the eager results."""
+    import paper_2503_18427_amd as aes
+    rowptr, col, val, X, w = _workload("arxiv_small")
+    d = [G.to_dev(a) for a in (rowptr, col, val)]
+    Xd = G.to_dev(X)
+    n, F, W = w.n, w.F, 32
+    plan = aes.aes_sample_build(d[0], d[1], d[2], n, W, 0, want_perm=True)
+    ws_b = torch.empty(aes.aes_sample_workspace_bytes(n), dtype=torch.uint8, device="cuda")
+    ws_q = torch.empty(max(aes.aes_quantize_workspace_bytes(n, F, COLUMN), 8), dtype=torch.uint8, device="cuda")
+    qbuf = (torch.empty((n, F), dtype=torch.int8, device="cuda"), torch.empty(F, device="cuda"),
+            torch.empty(F, device="cuda"))
+    Y, Yq, Yf = (torch.empty((n, F), device="cuda") for _ in range(3))
+
+    def step():
+        aes.aes_sample_build(d[0], d[1], d[2], n, W, 0, out=plan, workspace=ws_b)
+        aes.aes_spmm_f32(plan, Xd, Y)
+        aes.aes_quantize_features(Xd, SYM, COLUMN, out=qbuf, workspace=ws_q)
+        aes.aes_spmm_q8(plan, qbuf[0], SYM, COLUMN, qbuf[1], qbuf[2], Yq)
+        aes.aes_spmm_fused_f32(d[0], d[1], d[2], n, W, Xd, Y=Yf)
+
+    step()
+    torch.cuda.synchronize()
+    eager = [t.clone() for t in (plan.s_rowptr, plan.s_col, plan.s_val, Y, qbuf[0], Yq, Yf)]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                   # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for rep in range(3):
+        for t in (plan.s_col, plan.s_val, Y, Yq, Yf):
+            t.fill_(-1)                          # eager work between replays
+        qbuf[0].zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        now = (plan.s_rowptr, plan.s_col, plan.s_val, Y, qbuf[0], Yq, Yf)
+        S = int(plan.s_rowptr[-1])
+        for a, b in zip(eager, now):
+            if a.numel() == plan.s_col.numel() and a.dim() == 1:
+                assert torch.equal(a[:S], b[:S]), rep
+            else:
+                assert torch.equal(a, b), rep
+
+
+@pytest.mark.parametrize("F", [32, 96, 256, 320, 50])
+@pytest.mark.parametrize("W", [0, 4096])
+def test_long_rows_shared_by_the_workgroup(G, F, W):
+    """Rows above 2048 slots are split over all lane groups of a workgroup and
+    summed in a fixed order: several such rows per workgroup, mixed with short
+    and empty rows, every feature-chunk count, plan and fused forms, fp32 and
+    8-bit, and bit-identical from run to run."""
+    import paper_2503_18427_amd as aes
+    rng = np.random.default_rng(F + W)
+    deg = np.array([5000, 3, 2500, 0, 9000, 2049, 2048, 1, 70000, 64, 2047, 4097, 0, 33, 12000, 7] * 3)
+    n, n_cols = deg.size, 1500
+    rowptr, col, val = random_csr(n, n_cols, deg, rng)
+    X = rng.standard_normal((n_cols, F)).astype(np.float32)
+    plan, ref = G.check_plan(rowptr, col, val, n_cols, W, 0)
+    Y, _, _ = G.check_f32(plan, ref, X, use_perm=False)
+    Y2, _, _ = G.check_f32(plan, ref, X, use_perm=True)
+    assert torch.equal(Y, Y2)
+    d = [G.to_dev(a) for a in (rowptr, col, val)]
+    Yf = aes.aes_spmm_fused_f32(d[0], d[1], d[2], n_cols, W, G.to_dev(X))
+    Yr = aes.aes_spmm_f32(plan, G.to_dev(X), use_perm=False)
+    torch.cuda.synchronize()
+    assert torch.equal(Yf, Y) and torch.equal(Yr, Y)
+    for scheme, gran in ((SYM, ROW), (AFF, ROW), (AFF, COLUMN), (SYM, COLUMN)):
+        qd, qr = G.check_quantize(X, scheme, gran)
+        Yq, _, _ = G.check_q8(plan, ref, qd, qr, scheme, gran, use_perm=False)
+        Yqf = aes.aes_spmm_fused_q8(d[0], d[1], d[2], n_cols, W, qd[0], scheme, gran, qd[1], qd[2])
+        torch.cuda.synchronize()
+        assert torch.equal(Yqf, Yq)
