@@ -154,6 +154,10 @@ def main() -> int:
             traffic = rec["hbm_bytes"] if rec else None
         except (OSError, ValueError, KeyError):
             traffic = None
+    # Compulsory traffic with a perfect cache: every distinct feature row once.
+    distinct_cols = int(torch.unique(plan.s_col[:S]).numel()) if S > 0 else 0
+    compulsory = 8 * S + distinct_cols * F * 4 + 4 * n * F + 12 * n
+    t_min_ms = compulsory / (HBM_PEAK_GBPS * 1e9) * 1e3
     roofline = {
         "kernel": "spmm_rows_kernel (aes_spmm_f32)",
         "bound": "hbm",
@@ -164,6 +168,8 @@ def main() -> int:
         "traffic": traffic,
         "algorithmic_bytes": leg_bytes["spmm_f32"],
         "avg_ms": leg_ms["spmm_f32"],
+        "perfect_cache_model": {"distinct_feature_rows": distinct_cols, "compulsory_bytes": compulsory,
+                                "t_min_ms": t_min_ms, "t_min_over_t": t_min_ms / leg_ms["spmm_f32"]},
     }
 
     out = {

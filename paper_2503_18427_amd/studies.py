@@ -42,6 +42,28 @@ def _time_ms(fn, iters: int = 10, warmup: int = 2) -> float:
     return ts[len(ts) // 2]
 
 
+_evict = None
+
+
+def _time_ms_cold(fn, iters: int = 5) -> float:
+    """Median time of fn() when a 1 GiB buffer is overwritten before every call, so
+    that neither L2 nor the 256 MB Infinity Cache holds the operands."""
+    global _evict
+    if _evict is None:
+        _evict = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
+    ts = []
+    for i in range(iters + 1):
+        _evict.fill_(float(i))
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        fn()
+        b.record()
+        torch.cuda.synchronize()
+        if i > 0:
+            ts.append(a.elapsed_time(b))
+    return sorted(ts)[len(ts) // 2]
+
+
 def _rel_fro(Y: torch.Tensor, Yex: torch.Tensor) -> float:
     return float(torch.linalg.vector_norm((Y - Yex).double()) / torch.linalg.vector_norm(Yex.double()))
 
@@ -63,8 +85,8 @@ def width_sweep(name: str) -> None:
     deg = (d["rowptr"][1:] - d["rowptr"][:-1]).double()
     print(f"### width sweep, `{name}`: n = {n}, nnz = {d['nnz']}, F = {F}, exact SpMM {t_ex:.3f} ms "
           f"({_bytes(n, d['nnz'], F, 4) / t_ex / 1e6:.0f} GB/s effective)\n")
-    print("| W | slots S | sampled rows | median / mean row sampling rate | build ms | fp32 ms | fp32 GB/s | "
-          "fused fp32 ms | int8 ms | int8 GB/s | speedup vs exact | rel. Frobenius error fp32 | int8 |")
+    print("| W | slots S | sampled rows | median / mean row sampling rate | build ms | fp32 ms (cold) | fp32 GB/s | "
+          "fused fp32 ms | int8 ms (cold) | int8 GB/s | speedup vs exact | rel. Frobenius error fp32 | int8 |")
     print("|---|---|---|---|---|---|---|---|---|---|---|---|---|")
     Y = torch.empty_like(Yex)
     for W in w.widths:
@@ -74,13 +96,15 @@ def width_sweep(name: str) -> None:
         rate = torch.where(deg > 0, slots / deg.clamp(min=1), torch.ones_like(deg))
         t_b = _time_ms(lambda: aes.aes_sample_build(*csr, n, W, out=plan))
         t32 = _time_ms(lambda: aes.aes_spmm_f32(plan, X, Y))
+        t32c = _time_ms_cold(lambda: aes.aes_spmm_f32(plan, X, Y))
         e32 = _rel_fro(Y, Yex)
         t_f = _time_ms(lambda: aes.aes_spmm_fused_f32(*csr, n, W, X, Y=Y))
         t8 = _time_ms(lambda: aes.aes_spmm_q8(plan, q[0], scheme, gran, q[1], q[2], Y))
+        t8c = _time_ms_cold(lambda: aes.aes_spmm_q8(plan, q[0], scheme, gran, q[1], q[2], Y))
         e8 = _rel_fro(Y, Yex)
         print(f"| {W} | {S} | {float((deg > W).double().mean()) * 100:.1f} % | "
-              f"{float(rate.median()):.3f} / {float(rate.mean()):.3f} | {t_b:.3f} | {t32:.3f} | "
-              f"{_bytes(n, S, F, 4) / t32 / 1e6:.0f} | {t_f:.3f} | {t8:.3f} | "
+              f"{float(rate.median()):.3f} / {float(rate.mean()):.3f} | {t_b:.3f} | {t32:.3f} ({t32c:.3f}) | "
+              f"{_bytes(n, S, F, 4) / t32 / 1e6:.0f} | {t_f:.3f} | {t8:.3f} ({t8c:.3f}) | "
               f"{_bytes(n, S, F, 1, gran == 2) / t8 / 1e6:.0f} | {t_ex / t32:.2f}x | {e32:.4f} | {e8:.4f} |")
     print()
 
