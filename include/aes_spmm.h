@@ -265,6 +265,30 @@ int aes_spmm_fused_q8(int64_t n_rows, int64_t n_cols,
                       const float *scale, const float *zero,
                       float *Y, int64_t ldy, void *stream);
 
+/* ------------------------------------------------------------------------- */
+/* One GNN layer: aggregation (Sec. 3.2) and combination (Sec. 2.1) fused      */
+
+/*
+ * H = (A_s X) Theta: the sampled aggregation of aes_spmm_f32 followed by the
+ * layer's dense weight matrix, in one kernel.  A workgroup aggregates 32 rows of
+ * A_s X into LDS (float32, same summation order as aes_spmm_f32) and multiplies
+ * them by Theta on the matrix cores (float32 MFMA, float32 accumulate); the
+ * aggregated features are never written to memory.  No bias, no activation.
+ *
+ *   plan, W         as for aes_spmm_f32 (rows are always handled by one lane
+ *                   group here, whatever W says)
+ *   X     [dev]     n_cols x F float32 (ldx); F <= 256, F and ldx multiples of 4,
+ *                   16-byte aligned - otherwise AES_ERR_UNSUPPORTED (run
+ *                   aes_spmm_f32 and a GEMM instead)
+ *   Theta [dev]     F x Fo float32, row-major, leading dimension ldt
+ *   H     [dev]     out, n_rows x Fo float32 (ldh); must not overlap the inputs
+ */
+int aes_gcn_layer_f32(int64_t n_rows, int64_t n_cols, int32_t W,
+                      const int64_t *s_rowptr, const int32_t *s_col, const float *s_val,
+                      const float *X, int64_t ldx, int32_t F,
+                      const float *Theta, int64_t ldt, int32_t Fo,
+                      float *H, int64_t ldh, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

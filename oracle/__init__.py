@@ -53,6 +53,7 @@ def _load():
         lib.orc_spmm_plan.argtypes = [i64, vp, vp, vp, vp, vp, i64, i64, vp, vp, i64]
         lib.orc_aes_spmm.argtypes = [i64, vp, vp, vp, vp, i64, u64, i32, vp, i64, i64, vp, vp, i64]
         lib.orc_aes_spmm.restype = i32
+        lib.orc_combine.argtypes = [i64, i64, i64, vp, i64, vp, i64, vp, i64]
         lib.orc_quantize.argtypes = [i64, i64, vp, i64, i32, i32, vp, i64, vp, vp]
         lib.orc_quantize.restype = i32
         lib.orc_dequantize.argtypes = [i64, i64, vp, i64, i32, i32, vp, vp, vp, i64]
@@ -164,6 +165,19 @@ def aes_spmm(rowptr, colidx, val, W: int, X, seed: int = 0, rows=None, want_abs:
     if rc != 0:
         raise MemoryError("oracle scratch allocation failed")
     return (Y, Yabs) if want_abs else Y
+
+
+def combine(Y, Theta):
+    """H = Y @ Theta in double (the combination phase of a layer)."""
+    lib = _load()
+    Y = np.ascontiguousarray(Y, dtype=np.float64)
+    Theta = np.ascontiguousarray(Theta, dtype=np.float32)
+    n, F = Y.shape
+    Fo = Theta.shape[1]
+    assert Theta.shape[0] == F
+    H = np.empty((n, Fo), dtype=np.float64)
+    lib.orc_combine(n, F, Fo, _p(Y), F, _p(Theta), Fo, _p(H), Fo)
+    return H
 
 
 def _groups(n, F, granularity):

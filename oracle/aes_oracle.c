@@ -11,6 +11,7 @@
  *   - CSR input format ........................ Sec. 2.2
  *   - feature quantisation / dequantisation ... Sec. 2.3, Eq. 1 and Eq. 2
  *   - the kernel's steps ...................... Sec. 3.2, Algorithm 1
+ *   - combination phase (dense weights) ....... Sec. 2.1
  *   - strategy selector ....................... Sec. 3.3, Table 1
  *   - start-index hash ........................ Sec. 3.3, Eq. 3
  *
@@ -279,6 +280,22 @@ int orc_aes_spmm(int64_t n_rows, const int64_t *rows, const int64_t *row_ptr,
         free(sh_val);
     }
     return failed ? -1 : 0;
+}
+
+/*
+ * Sec. 2.1, combination phase of a layer: H = Y * Theta, the aggregated features
+ * times the layer's dense weight matrix (F x Fo, row-major), in double.
+ */
+void orc_combine(int64_t n, int64_t F, int64_t Fo, const double *Y, int64_t ldy, const float *Theta,
+                 int64_t ldt, double *H, int64_t ldh)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < n; ++t)
+        for (int64_t o = 0; o < Fo; ++o) {
+            double acc = 0.0;
+            for (int64_t c = 0; c < F; ++c) acc += Y[t * ldy + c] * (double)Theta[c * ldt + o];
+            H[t * ldh + o] = acc;
+        }
 }
 
 /* ------------------------------------------------------------------------ */

@@ -18,6 +18,7 @@ from .binding import (  # noqa: F401
     AesError,
     Plan,
     aes_dequantize_features,
+    aes_gcn_layer_f32,
     aes_last_error,
     aes_quantize_features,
     aes_quantize_workspace_bytes,

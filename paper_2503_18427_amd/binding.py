@@ -30,6 +30,8 @@ SIGNATURES = {
     "aes_spmm_f32": (ctypes.c_int, [_i64, _i64, _i32, _vp, _vp, _vp, _vp, _vp, _i64, _i32, _vp, _i64, _vp]),
     "aes_quantize_workspace_bytes": (_sz, [_i64, _i32, _i32]),
     "aes_quantize_features": (ctypes.c_int, [_i64, _i32, _vp, _i64, _i32, _i32, _vp, _i64, _vp, _vp, _vp, _sz, _vp]),
+    "aes_gcn_layer_f32": (ctypes.c_int, [_i64, _i64, _i32, _vp, _vp, _vp, _vp, _i64, _i32, _vp, _i64, _i32, _vp, _i64,
+                                         _vp]),
     "aes_dequantize_features": (ctypes.c_int, [_i64, _i32, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _i64, _vp]),
     "aes_spmm_q8": (ctypes.c_int, [_i64, _i64, _i32, _vp, _vp, _vp, _vp, _vp, _i64, _i32, _i32, _i32, _vp, _vp, _vp,
                                    _i64, _vp]),
@@ -300,3 +302,21 @@ def aes_dequantize_features(Xq, scheme: int, granularity: int, scale, zero=None,
     _check(library().aes_dequantize_features(n, F, _ptr(Xq), _ld(Xq), int(scheme), int(granularity), _ptr(scale),
                                              _ptr(zero), _ptr(X), _ld(X), _stream(stream)))
     return X
+
+
+def aes_gcn_layer_f32(plan: Plan, X, Theta, H=None, *, stream=None):
+    """H = (A_s X) Theta in one kernel (aggregation + combination of a layer)."""
+    X = _dev(X, torch.float32, "X", 2)
+    Theta = _dev(Theta, torch.float32, "Theta", 2)
+    F, Fo = X.shape[1], Theta.shape[1]
+    if X.shape[0] != plan.n_cols or Theta.shape[0] != F:
+        raise ValueError("X must be n_cols x F and Theta F x Fo")
+    if H is None:
+        H = torch.empty((plan.n_rows, Fo), dtype=torch.float32, device=X.device)
+    H = _dev(H, torch.float32, "H", 2)
+    if H.shape[0] != plan.n_rows or H.shape[1] != Fo:
+        raise ValueError("H has the wrong shape")
+    _check(library().aes_gcn_layer_f32(plan.n_rows, plan.n_cols, plan.W, _ptr(plan.s_rowptr), _ptr(plan.s_col),
+                                       _ptr(plan.s_val), _ptr(X), _ld(X), F, _ptr(Theta), _ld(Theta), Fo, _ptr(H),
+                                       _ld(H), _stream(stream)))
+    return H

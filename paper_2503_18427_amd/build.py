@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libaes_spmm.so")
-SOURCES = ["aes_common.cpp", "sample_build.hip", "spmm.hip", "quantize.hip"]
+SOURCES = ["aes_common.cpp", "sample_build.hip", "spmm.hip", "quantize.hip", "gcn_layer.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -1,0 +1,259 @@
+// Device-side core of the multiply stage, shared by the SpMM kernels and the fused
+// GCN-layer kernel: slot sources, feature loaders, the tile accumulation loop.
+//
+// Method: AES-SpMM Sec. 3.2 Algorithm 1 (accumulation loop), Sec. 2.3 Eq. 2
+// (dequantisation inside the gather).
+#pragma once
+
+#include "aes_common.hpp"
+#include "aes_sampling.hpp"
+
+namespace aes {
+
+
+constexpr int kTile = 64;          // slots staged in LDS per group per round
+
+enum QMode {
+    kQNone = 0,      // float32 features, or 8-bit features with per-tensor / per-column constants
+    kQRowScale = 1   // 8-bit features with per-row constants: folded into the staged edge value
+};
+
+// Where a row's (col, val) slots come from: a materialised plan (FUSED = false: the
+// three arrays are s_rowptr / s_col / s_val) or the CSR matrix itself, sampled on
+// the fly by Table 1 and Eq. 3 (FUSED = true).
+struct SlotSource {
+    const int64_t *rowptr;
+    const int32_t *col;
+    const float *val;
+    int32_t W;
+    int32_t strategy;
+    uint64_t seed;
+};
+
+struct QParams {
+    const float *scale;   // per-row: indexed by column of A (= row of X)
+    const float *zero;    // may be NULL
+    int granularity;      // aes_q_granularity
+    int affine;           // 1: x_hat = q*scale + zero, q unsigned; 0: x_hat = q*scale, q signed
+};
+
+// ---- feature loaders: VEC consecutive features of one row of X --------------
+// fma(acc, v, x) adds v * (feature + kBias) to acc; the kernel removes
+// kBias * sum(v) in its epilogue.  kBias = 128 lets signed 8-bit codes be
+// converted as unsigned bytes (one conversion instruction per byte, after one
+// XOR per four bytes) instead of sign-extending each byte first.
+template <int VEC_> struct FeatF32;
+template <> struct FeatF32<4> {
+    static constexpr int VEC = 4;
+    static constexpr int kBias = 0;
+    using elem_t = float;
+    using raw_t = float4;
+    static __device__ inline raw_t load(const elem_t *p) { return *reinterpret_cast<const float4 *>(p); }
+    static __device__ inline void fma(float (&acc)[4], float v, const raw_t &x)
+    {
+        acc[0] = __builtin_fmaf(v, x.x, acc[0]);
+        acc[1] = __builtin_fmaf(v, x.y, acc[1]);
+        acc[2] = __builtin_fmaf(v, x.z, acc[2]);
+        acc[3] = __builtin_fmaf(v, x.w, acc[3]);
+    }
+};
+template <> struct FeatF32<1> {
+    static constexpr int VEC = 1;
+    static constexpr int kBias = 0;
+    using elem_t = float;
+    using raw_t = float;
+    static __device__ inline raw_t load(const elem_t *p) { return *p; }
+    static __device__ inline void fma(float (&acc)[1], float v, const raw_t &x) { acc[0] = __builtin_fmaf(v, x, acc[0]); }
+};
+
+// Four packed bytes -> four floats (unsigned; signed codes arrive biased by 128).
+template <bool SIGNED>
+__device__ inline void fma_bytes(float *acc, float v, uint32_t w)
+{
+    if (SIGNED) w ^= 0x80808080u;
+    acc[0] = __builtin_fmaf(v, static_cast<float>(w & 0xffu), acc[0]);
+    acc[1] = __builtin_fmaf(v, static_cast<float>((w >> 8) & 0xffu), acc[1]);
+    acc[2] = __builtin_fmaf(v, static_cast<float>((w >> 16) & 0xffu), acc[2]);
+    acc[3] = __builtin_fmaf(v, static_cast<float>(w >> 24), acc[3]);
+}
+
+template <int VEC_, bool SIGNED> struct FeatQ8;
+template <bool SIGNED> struct FeatQ8<4, SIGNED> {
+    static constexpr int VEC = 4;
+    static constexpr int kBias = SIGNED ? 128 : 0;
+    using elem_t = int8_t;
+    using raw_t = uint32_t;
+    static __device__ inline raw_t load(const elem_t *p) { return *reinterpret_cast<const uint32_t *>(p); }
+    static __device__ inline void fma(float (&acc)[4], float v, const raw_t &x) { fma_bytes<SIGNED>(acc, v, x); }
+};
+template <bool SIGNED> struct FeatQ8<1, SIGNED> {
+    static constexpr int VEC = 1;
+    static constexpr int kBias = 0;
+    using elem_t = int8_t;
+    using raw_t = int8_t;
+    static __device__ inline raw_t load(const elem_t *p) { return *p; }
+    static __device__ inline void fma(float (&acc)[1], float v, const raw_t &x)
+    {
+        float q = SIGNED ? static_cast<float>(x) : static_cast<float>(static_cast<uint8_t>(x));
+        acc[0] = __builtin_fmaf(v, q, acc[0]);
+    }
+};
+
+// Orders this wavefront's LDS traffic: earlier LDS accesses of any lane are
+// complete (and not moved by the compiler) before later ones start.
+__device__ inline void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// ---- the kernel ---------------------------------------------------------------
+// What a lane group needs to know about its row.
+struct RowInfo {
+    int64_t k_begin;     // first slot (plan) or first CSR entry (fused)
+    int64_t n_slots;
+    int64_t row_nnz;     // fused only: entries of the CSR row
+    int32_t samp_n;      // fused, sampled row: N and sample_cnt of Table 1, per-row offset
+    int32_t samp_cnt;
+    uint32_t s_r;
+    bool sampled;
+};
+
+template <bool FUSED>
+__device__ inline RowInfo row_info(const SlotSource &src, int64_t r)
+{
+    RowInfo ri;
+    ri.k_begin = src.rowptr[r];
+    ri.n_slots = src.rowptr[r + 1] - ri.k_begin;
+    ri.row_nnz = ri.n_slots;
+    ri.sampled = false;
+    ri.samp_n = 0;
+    ri.samp_cnt = 1;
+    ri.s_r = 0;
+    if (FUSED && src.W != 0 && ri.row_nnz > src.W) {
+        ri.sampled = true;
+        aes::sample_strategy(ri.row_nnz, src.W, src.strategy, ri.samp_n, ri.samp_cnt);
+        ri.n_slots = static_cast<int64_t>(ri.samp_n) * ri.samp_cnt;
+        ri.s_r = aes::row_offset(src.seed, r);
+    }
+    return ri;
+}
+
+// Adds the row's tiles first_tile, first_tile + tile_step, ... into acc (one chunk of
+// features).  side / vsum collect the sums the 8-bit epilogue needs.
+template <int LPR, int UNROLL, typename Feat, int QMODE, bool QUANT, bool FUSED>
+__device__ __forceinline__ void accumulate_tiles(const SlotSource &src, const RowInfo &ri, int2 *my_stage, int lane,
+                                                 bool lane_on, const typename Feat::elem_t *__restrict__ X,
+                                                 int64_t ldx, int32_t f, const QParams &qp, int64_t first_tile,
+                                                 int64_t tile_step, float (&acc)[Feat::VEC], float &side,
+                                                 float &vsum)
+{
+    for (int64_t t0 = first_tile * kTile; t0 < ri.n_slots; t0 += tile_step * kTile) {
+        const int m = static_cast<int>(ri.n_slots - t0 < kTile ? ri.n_slots - t0 : kTile);
+        wave_lds_sync();                             // previous tile fully consumed
+#pragma unroll
+        for (int s = lane; s < kTile; s += LPR) {
+            if (s < m) {
+                int64_t e = ri.k_begin + t0 + s;
+                if (FUSED && ri.sampled)
+                    e = aes::sampled_entry(ri.k_begin, ri.row_nnz, ri.samp_n, ri.samp_cnt, ri.s_r,
+                                           static_cast<int32_t>(t0) + s);
+                const int32_t c = src.col[e];
+                float v = src.val[e];
+                if (QUANT) {
+                    if (QMODE == kQRowScale) {
+                        if (qp.affine) side = __builtin_fmaf(v, qp.zero[c], side);
+                        v *= qp.scale[c];
+                    } else if (qp.affine) {
+                        side += v;
+                    }
+                }
+                my_stage[s] = make_int2(c, __float_as_int(v));
+            }
+        }
+        wave_lds_sync();                             // tile visible to the whole group
+        if (lane_on) {
+            // UNROLL gathers are issued back to back before the first one is consumed.
+            int k = 0;
+            for (; k + UNROLL <= m; k += UNROLL) {
+                int2 cv[UNROLL];
+                typename Feat::raw_t x[UNROLL];
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) cv[u] = my_stage[k + u];
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) x[u] = Feat::load(X + static_cast<int64_t>(cv[u].x) * ldx + f);
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) {
+                    Feat::fma(acc, __int_as_float(cv[u].y), x[u]);
+                    if (Feat::kBias != 0) vsum += __int_as_float(cv[u].y);
+                }
+            }
+            // Ragged last round: the missing slots are predicated off (value 0, no load), so
+            // short rows and row tails keep their gathers in flight together as well.
+            if (k < m) {
+                int2 cv[UNROLL];
+                typename Feat::raw_t x[UNROLL];
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) cv[u] = (k + u < m) ? my_stage[k + u] : make_int2(-1, 0);
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) {
+                    x[u] = typename Feat::raw_t{};
+                    if (cv[u].x >= 0) x[u] = Feat::load(X + static_cast<int64_t>(cv[u].x) * ldx + f);
+                }
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) {
+                    Feat::fma(acc, __int_as_float(cv[u].y), x[u]);
+                    if (Feat::kBias != 0) vsum += __int_as_float(cv[u].y);
+                }
+            }
+        }
+    }
+}
+
+// Removes the loader's bias, applies the 8-bit group constants and stores one chunk of Y[r, :].
+// `side` must already be summed over the lanes of the group.
+template <typename Feat, int QMODE, bool QUANT>
+__device__ __forceinline__ void finish_chunk(float (&acc)[Feat::VEC], float side, float vsum, bool lane_on, int32_t f,
+                                             const QParams &qp, float *__restrict__ y)
+{
+    constexpr int VEC = Feat::VEC;
+    if (Feat::kBias != 0) {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) acc[i] = __builtin_fmaf(-static_cast<float>(Feat::kBias), vsum, acc[i]);
+    }
+    if (!lane_on) return;
+    if (QUANT) {
+        // x_hat = q*scale_g + zero_g, with the group constants taken out of the sum:
+        //   per tensor / column: Y = scale_c * sum(v*q) + zero_c * sum(v)
+        //   per row            : Y = sum((v*scale_col)*q) + sum(v*zero_col)
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) {
+            if (QMODE == kQRowScale) {
+                if (qp.affine) acc[i] += side;
+            } else {
+                const int g = qp.granularity == AES_Q_PER_COLUMN ? f + i : 0;
+                acc[i] *= qp.scale[g];
+                if (qp.affine) acc[i] = __builtin_fmaf(side, qp.zero[g], acc[i]);
+            }
+        }
+    }
+    if constexpr (VEC % 4 == 0) {
+#pragma unroll
+        for (int i = 0; i < VEC; i += 4)
+            *reinterpret_cast<float4 *>(y + i) = make_float4(acc[i], acc[i + 1], acc[i + 2], acc[i + 3]);
+    } else {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) y[i] = acc[i];
+    }
+}
+
+template <int LPR>
+__device__ __forceinline__ float group_sum(float v)
+{
+#pragma unroll
+    for (int d = LPR / 2; d >= 1; d >>= 1) v += __shfl_xor(v, d, LPR);
+    return v;
+}
+
+}  // namespace aes

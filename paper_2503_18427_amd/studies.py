@@ -3,6 +3,7 @@
     python -m paper_2503_18427_amd.studies width-sweep [workload]
     python -m paper_2503_18427_amd.studies strategies  [workload]
     python -m paper_2503_18427_amd.studies loading     [workload]
+    python -m paper_2503_18427_amd.studies layer       [workload]
 
 They reproduce the *shape* of the paper's evaluation on the synthetic workloads
 (the paper's datasets are not available): kernel time and error against the
@@ -179,14 +180,41 @@ def loading(name: str) -> None:
           f"8-bit {(q[0].numel() + 8 * q[1].numel()) / t_l8 / 1e6:.1f} GB/s\n")
 
 
+def layer(name: str) -> None:
+    """One GNN layer H = (A_s X) Theta: fused kernel vs SpMM followed by a library GEMM."""
+    d = configs.make(name, "cuda")
+    w = d["workload"]
+    n, F, X = d["n"], d["F"], d["X"]
+    g = torch.Generator(device="cuda")
+    g.manual_seed(7)
+    print(f"### fused layer, `{name}` (n = {n}, F = {F}; ms)\n")
+    print("| W | Fo | aes_spmm_f32 | library GEMM (torch.matmul, fp32) | sum | aes_gcn_layer_f32 | saved | "
+          "max abs difference |")
+    print("|---|---|---|---|---|---|---|---|")
+    for W in w.widths:
+        plan = aes.aes_sample_build(d["rowptr"], d["colidx"], d["val"], n, W)
+        for Fo in (64, F):
+            Theta = torch.randn((F, Fo), device="cuda", generator=g) / F ** 0.5
+            Y = torch.empty((n, F), device="cuda")
+            H0 = torch.empty((n, Fo), device="cuda")
+            H1 = torch.empty((n, Fo), device="cuda")
+            t_s = _time_ms(lambda: aes.aes_spmm_f32(plan, X, Y))
+            t_g = _time_ms(lambda: torch.matmul(Y, Theta, out=H0))
+            t_f = _time_ms(lambda: aes.aes_gcn_layer_f32(plan, X, Theta, H1))
+            diff = float((H0 - H1).abs().max())
+            print(f"| {W} | {Fo} | {t_s:.3f} | {t_g:.3f} | {t_s + t_g:.3f} | {t_f:.3f} | "
+                  f"{(1 - t_f / (t_s + t_g)) * 100:.1f} % | {diff:.2e} |")
+    print()
+
+
 def main(argv) -> int:
-    if len(argv) < 2 or argv[1] not in ("width-sweep", "strategies", "loading"):
+    if len(argv) < 2 or argv[1] not in ("width-sweep", "strategies", "loading", "layer"):
         print(__doc__)
         return 2
     assert torch.cuda.is_available(), "the studies need a GPU"
     name = argv[2] if len(argv) > 2 else {"width-sweep": "rmat20", "strategies": "reddit_like",
-                                          "loading": "products_like"}[argv[1]]
-    {"width-sweep": width_sweep, "strategies": strategies, "loading": loading}[argv[1]](name)
+                                          "loading": "products_like", "layer": "products_like"}[argv[1]]
+    {"width-sweep": width_sweep, "strategies": strategies, "loading": loading, "layer": layer}[argv[1]](name)
     return 0
 
 

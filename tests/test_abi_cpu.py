@@ -111,6 +111,15 @@ def test_argument_errors_are_host_side(lib):
     assert dq(4, 8, None, 8, 1, 1, fake, None, fake, 8, None) == -1
     assert dq(0, 8, None, 8, 1, 1, fake, None, None, 8, None) == 0
 
+    gl = lib.aes_gcn_layer_f32
+    assert gl(-1, 4, 0, fake, fake, fake, fake, 8, 8, fake, 8, 8, fake, 8, None) == -1
+    assert gl(4, 4, 0, fake, fake, fake, fake, 8, 8, fake, 4, 8, fake, 8, None) == -1      # ldt < Fo
+    assert gl(4, 4, 0, fake, fake, fake, fake, 8, 8, None, 8, 8, fake, 8, None) == -1      # Theta NULL
+    assert gl(4, 4, 0, fake, fake, fake, fake, 8, 8, fake, 8, 8, None, 8, None) == -1      # H NULL
+    assert gl(4, 4, 0, fake, fake, fake, fake, 512, 512, fake, 8, 8, fake, 8, None) == -2  # F too wide
+    assert gl(4, 4, 0, fake, fake, fake, fake, 10, 10, fake, 8, 8, fake, 8, None) == -2    # F % 4
+    assert gl(0, 4, 0, fake, fake, fake, fake, 8, 8, fake, 8, 8, None, 8, None) == 0
+
     q8 = lib.aes_spmm_q8
     assert q8(4, 4, 0, fake, fake, fake, None, fake, 8, 8, 5, 1, fake, fake, fake, 8, None) == -1
     assert q8(4, 4, 0, fake, fake, fake, None, fake, 8, 8, 1, 5, fake, fake, fake, 8, None) == -1

@@ -279,3 +279,44 @@ def test_long_rows_shared_by_the_workgroup(G, F, W):
         Yqf = aes.aes_spmm_fused_q8(d[0], d[1], d[2], n_cols, W, qd[0], scheme, gran, qd[1], qd[2])
         torch.cuda.synchronize()
         assert torch.equal(Yqf, Yq)
+
+
+@pytest.mark.parametrize("F,Fo", [(128, 128), (256, 256), (64, 32), (32, 200), (100, 48), (8, 1), (256, 64), (128, 33)])
+def test_gcn_layer_fused_with_matrix_cores(G, F, Fo):
+    """Aggregation + combination in one kernel against the oracle (double), with
+    rows that do not fill the last 32-row tile and output widths that do not fill
+    the last 32-column MFMA block."""
+    import oracle as orc
+    import paper_2503_18427_amd as aes
+    rowptr, col, val, _, n_cols = _ragged_case(F + Fo, 64, n=333)
+    rng = np.random.default_rng(F * 1000 + Fo)
+    X = rng.standard_normal((n_cols, F)).astype(np.float32)
+    Theta = (rng.standard_normal((F, Fo)) / np.sqrt(F)).astype(np.float32)
+    for W in (64, 0):
+        plan, ref = G.check_plan(rowptr, col, val, n_cols, W, 0)
+        H = aes.aes_gcn_layer_f32(plan, G.to_dev(X), G.to_dev(Theta))
+        torch.cuda.synchronize()
+        Y, Yabs = orc.spmm_plan(ref[0], ref[1], ref[2], X, want_abs=True)
+        Href = orc.combine(Y, Theta)
+        Habs = orc.combine(Yabs, np.abs(Theta))
+        d = np.abs(H.cpu().numpy().astype(np.float64) - Href)
+        comp = float(np.max(d / np.where(Habs > 0, Habs, 1.0)))
+        assert comp <= 2e-5, comp
+        # strided operands and output
+        Hb = torch.full((rowptr.size - 1, Fo + 3), 5.0, device="cuda")
+        Tb = torch.zeros((F, Fo + 7), device="cuda")
+        Tb[:, 2:Fo + 2] = G.to_dev(Theta)
+        aes.aes_gcn_layer_f32(plan, G.to_dev(X), Tb[:, 2:Fo + 2], Hb[:, 1:Fo + 1])
+        torch.cuda.synchronize()
+        assert torch.equal(Hb[:, 1:Fo + 1], H)
+        assert torch.all(Hb[:, 0] == 5.0) and torch.all(Hb[:, Fo + 1:] == 5.0)
+
+
+def test_gcn_layer_unsupported_shapes(G):
+    import paper_2503_18427_amd as aes
+    rowptr, col, val, _, n_cols = _ragged_case(1, 16, n=40)
+    plan, _ = G.check_plan(rowptr, col, val, n_cols, 16, 0)
+    for F in (260, 6):
+        with pytest.raises(aes.AesError) as e:
+            aes.aes_gcn_layer_f32(plan, torch.zeros((n_cols, F), device="cuda"), torch.zeros((F, 8), device="cuda"))
+        assert e.value.code == -2

@@ -110,3 +110,13 @@ def test_workload_generator_smoke(oracle):
     A = sp.csr_matrix((val.astype(np.float64), col, rowptr), shape=(d["n"], d["n"]))
     short = np.diff(rowptr) <= 32
     assert np.allclose(Y[short], (A @ X.astype(np.float64))[short], atol=1e-12)
+
+
+def test_combination_phase_is_a_matrix_product(oracle):
+    rng = np.random.default_rng(31)
+    Y = rng.standard_normal((37, 20))
+    Theta = rng.standard_normal((20, 13)).astype(np.float32)
+    H = oracle.combine(Y, Theta)
+    assert np.allclose(H, Y @ Theta.astype(np.float64), rtol=0, atol=1e-12)
+    # non-square, so a transposed operand cannot pass; identity weights return Y
+    assert np.array_equal(oracle.combine(Y, np.eye(20, dtype=np.float32)), Y)
