@@ -149,8 +149,9 @@ int aes_sample_build(int64_t n_rows, int64_t n_cols, int64_t nnz,
  *                   slots of any row, or 0 when there is none (unsampled plan,
  *                   plain CSR).  It only selects the kernel variant: with
  *                   W == 0 or W > 2048 rows longer than 2048 slots are shared by
- *                   all wavefronts of a workgroup (partial sums added in a fixed
- *                   order) instead of being left to one lane group.  A row with
+ *                   all wavefronts of a workgroup (partial sums carried in
+ *                   float64 and added in a fixed order) instead of being left
+ *                   to one lane group.  A row with
  *                   more slots than a non-zero W states is still computed
  *                   correctly, only without that sharing.
  *   s_rowptr/s_col/s_val [dev]  a plan from aes_sample_build (or any CSR with

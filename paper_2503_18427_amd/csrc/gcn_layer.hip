@@ -50,7 +50,7 @@ gcn_layer_kernel(int64_t n_rows, SlotSource src, const float *__restrict__ X, in
         float side = 0.0f, vsum = 0.0f;
         if (r < n_rows) {
             const RowInfo ri = row_info<false>(src, r);
-            accumulate_tiles<LPR, 8, FeatF32<4>, kQNone, false, false>(src, ri, stage[wave][group], lane, lane_on, X, ldx,
+            accumulate_tiles<LPR, 8, FeatF32<4>, kQNone, false, false, float>(src, ri, stage[wave][group], lane, lane_on, X, ldx,
                                                                        f, no_q, 0, 1, acc, side, vsum);
         }
         if (lane_on) {

@@ -36,9 +36,10 @@ constexpr int kLongRow = 2048;
 //       fast paths, 1 otherwise)
 // QMODE see above; QUANT: apply the 8-bit epilogue; FUSED: sample from the CSR on the fly
 // LONG  rows above kLongRow slots are processed by the whole workgroup: its lane groups
-//       take the row's tiles round-robin and their partial sums are added in a fixed
-//       order through LDS, so the result stays bit-reproducible.  Without LONG the
-//       kernel has no workgroup barrier at all.
+//       take the row's tiles round-robin and their partial sums (carried in float64,
+//       since such sums run over up to millions of terms) are added in a fixed order
+//       through LDS, so the result stays bit-reproducible.  Without LONG the kernel
+//       has no workgroup barrier at all.
 template <int LPR, int UNROLL, typename Feat, int QMODE, bool QUANT, bool FUSED, bool LONG>
 __global__ void __launch_bounds__(kBlock)
 spmm_rows_kernel(int64_t n_rows, SlotSource src, const int32_t *__restrict__ row_perm,
@@ -75,17 +76,17 @@ spmm_rows_kernel(int64_t n_rows, SlotSource src, const int32_t *__restrict__ row
             for (int i = 0; i < VEC; ++i) acc[i] = 0.0f;
             float side = 0.0f;      // this lane's share of sum(val * zero-point weight)
             float vsum = 0.0f;      // sum of the staged edge values (only when the loader is biased)
-            accumulate_tiles<LPR, UNROLL, Feat, QMODE, QUANT, FUSED>(src, ri, my_stage, lane, lane_on, X, ldx, f, qp, 0,
-                                                                     1, acc, side, vsum);
-            if (QUANT && qp.affine) side = group_sum<LPR>(side);
-            finish_chunk<Feat, QMODE, QUANT>(acc, side, vsum, lane_on, f, qp, Y + r * ldy + f);
+            accumulate_tiles<LPR, UNROLL, Feat, QMODE, QUANT, FUSED, float>(src, ri, my_stage, lane, lane_on, X, ldx, f,
+                                                                            qp, 0, 1, acc, side, vsum);
+            if (QUANT && qp.affine) side = group_sum<LPR, float>(side);
+            finish_chunk<Feat, QMODE, QUANT, float>(acc, side, vsum, lane_on, f, qp, Y + r * ldy + f);
         }
     }
 
     if constexpr (LONG) {
         __shared__ int sh_n_long;
         __shared__ int64_t sh_long_row[kRowsPerBlock];
-        __shared__ float sh_part[kRowsPerBlock][LPR][VEC + 2];
+        __shared__ double sh_part[kRowsPerBlock][LPR][VEC + 2];
         if (threadIdx.x == 0) sh_n_long = 0;
         __syncthreads();
         if (is_long && lane == 0) sh_long_row[atomicAdd(&sh_n_long, 1)] = r;   // order affects no sum
@@ -98,13 +99,14 @@ spmm_rows_kernel(int64_t n_rows, SlotSource src, const int32_t *__restrict__ row
             for (int32_t f0 = 0; f0 < F; f0 += LPR * VEC) {
                 const int32_t f = f0 + lane * VEC;
                 const bool lane_on = f < F;
-                float acc[VEC];
+                double acc[VEC];                         // long sums are carried in float64
 #pragma unroll
-                for (int j = 0; j < VEC; ++j) acc[j] = 0.0f;
-                float side = 0.0f, vsum = 0.0f;
-                accumulate_tiles<LPR, UNROLL, Feat, QMODE, QUANT, FUSED>(src, lri, my_stage, lane, lane_on, X, ldx, f,
-                                                                         qp, gib, kRowsPerBlock, acc, side, vsum);
-                if (QUANT && qp.affine) side = group_sum<LPR>(side);
+                for (int j = 0; j < VEC; ++j) acc[j] = 0.0;
+                double side = 0.0, vsum = 0.0;
+                accumulate_tiles<LPR, UNROLL, Feat, QMODE, QUANT, FUSED, double>(src, lri, my_stage, lane, lane_on, X,
+                                                                                 ldx, f, qp, gib, kRowsPerBlock, acc,
+                                                                                 side, vsum);
+                if (QUANT && qp.affine) side = group_sum<LPR, double>(side);
 #pragma unroll
                 for (int j = 0; j < VEC; ++j) sh_part[gib][lane][j] = acc[j];
                 sh_part[gib][lane][VEC] = side;
@@ -117,7 +119,7 @@ spmm_rows_kernel(int64_t n_rows, SlotSource src, const int32_t *__restrict__ row
                         side += sh_part[g][lane][VEC];
                         vsum += sh_part[g][lane][VEC + 1];
                     }
-                    finish_chunk<Feat, QMODE, QUANT>(acc, side, vsum, lane_on, f, qp, Y + lr * ldy + f);
+                    finish_chunk<Feat, QMODE, QUANT, double>(acc, side, vsum, lane_on, f, qp, Y + lr * ldy + f);
                 }
                 __syncthreads();
             }

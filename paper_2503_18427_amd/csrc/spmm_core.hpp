@@ -37,6 +37,15 @@ struct QParams {
     int affine;           // 1: x_hat = q*scale + zero, q unsigned; 0: x_hat = q*scale, q signed
 };
 
+// acc + a * b in the accumulator's precision: one fused multiply-add in float32 for
+// ordinary rows, in float64 for the long-row variant (whose sums run over up to
+// millions of terms and would otherwise outgrow float32's relative error target).
+__device__ inline float fma_acc(float a, float b, float acc) { return __builtin_fmaf(a, b, acc); }
+__device__ inline double fma_acc(float a, float b, double acc)
+{
+    return __builtin_fma(static_cast<double>(a), static_cast<double>(b), acc);
+}
+
 // ---- feature loaders: VEC consecutive features of one row of X --------------
 // fma(acc, v, x) adds v * (feature + kBias) to acc; the kernel removes
 // kBias * sum(v) in its epilogue.  kBias = 128 lets signed 8-bit codes be
@@ -49,12 +58,13 @@ template <> struct FeatF32<4> {
     using elem_t = float;
     using raw_t = float4;
     static __device__ inline raw_t load(const elem_t *p) { return *reinterpret_cast<const float4 *>(p); }
-    static __device__ inline void fma(float (&acc)[4], float v, const raw_t &x)
+    template <typename AccT>
+    static __device__ inline void fma(AccT (&acc)[4], float v, const raw_t &x)
     {
-        acc[0] = __builtin_fmaf(v, x.x, acc[0]);
-        acc[1] = __builtin_fmaf(v, x.y, acc[1]);
-        acc[2] = __builtin_fmaf(v, x.z, acc[2]);
-        acc[3] = __builtin_fmaf(v, x.w, acc[3]);
+        acc[0] = fma_acc(v, x.x, acc[0]);
+        acc[1] = fma_acc(v, x.y, acc[1]);
+        acc[2] = fma_acc(v, x.z, acc[2]);
+        acc[3] = fma_acc(v, x.w, acc[3]);
     }
 };
 template <> struct FeatF32<1> {
@@ -63,18 +73,19 @@ template <> struct FeatF32<1> {
     using elem_t = float;
     using raw_t = float;
     static __device__ inline raw_t load(const elem_t *p) { return *p; }
-    static __device__ inline void fma(float (&acc)[1], float v, const raw_t &x) { acc[0] = __builtin_fmaf(v, x, acc[0]); }
+    template <typename AccT>
+    static __device__ inline void fma(AccT (&acc)[1], float v, const raw_t &x) { acc[0] = fma_acc(v, x, acc[0]); }
 };
 
 // Four packed bytes -> four floats (unsigned; signed codes arrive biased by 128).
-template <bool SIGNED>
-__device__ inline void fma_bytes(float *acc, float v, uint32_t w)
+template <bool SIGNED, typename AccT>
+__device__ inline void fma_bytes(AccT *acc, float v, uint32_t w)
 {
     if (SIGNED) w ^= 0x80808080u;
-    acc[0] = __builtin_fmaf(v, static_cast<float>(w & 0xffu), acc[0]);
-    acc[1] = __builtin_fmaf(v, static_cast<float>((w >> 8) & 0xffu), acc[1]);
-    acc[2] = __builtin_fmaf(v, static_cast<float>((w >> 16) & 0xffu), acc[2]);
-    acc[3] = __builtin_fmaf(v, static_cast<float>(w >> 24), acc[3]);
+    acc[0] = fma_acc(v, static_cast<float>(w & 0xffu), acc[0]);
+    acc[1] = fma_acc(v, static_cast<float>((w >> 8) & 0xffu), acc[1]);
+    acc[2] = fma_acc(v, static_cast<float>((w >> 16) & 0xffu), acc[2]);
+    acc[3] = fma_acc(v, static_cast<float>(w >> 24), acc[3]);
 }
 
 template <int VEC_, bool SIGNED> struct FeatQ8;
@@ -84,7 +95,8 @@ template <bool SIGNED> struct FeatQ8<4, SIGNED> {
     using elem_t = int8_t;
     using raw_t = uint32_t;
     static __device__ inline raw_t load(const elem_t *p) { return *reinterpret_cast<const uint32_t *>(p); }
-    static __device__ inline void fma(float (&acc)[4], float v, const raw_t &x) { fma_bytes<SIGNED>(acc, v, x); }
+    template <typename AccT>
+    static __device__ inline void fma(AccT (&acc)[4], float v, const raw_t &x) { fma_bytes<SIGNED>(acc, v, x); }
 };
 template <bool SIGNED> struct FeatQ8<1, SIGNED> {
     static constexpr int VEC = 1;
@@ -92,10 +104,11 @@ template <bool SIGNED> struct FeatQ8<1, SIGNED> {
     using elem_t = int8_t;
     using raw_t = int8_t;
     static __device__ inline raw_t load(const elem_t *p) { return *p; }
-    static __device__ inline void fma(float (&acc)[1], float v, const raw_t &x)
+    template <typename AccT>
+    static __device__ inline void fma(AccT (&acc)[1], float v, const raw_t &x)
     {
         float q = SIGNED ? static_cast<float>(x) : static_cast<float>(static_cast<uint8_t>(x));
-        acc[0] = __builtin_fmaf(v, q, acc[0]);
+        acc[0] = fma_acc(v, q, acc[0]);
     }
 };
 
@@ -142,12 +155,12 @@ __device__ inline RowInfo row_info(const SlotSource &src, int64_t r)
 
 // Adds the row's tiles first_tile, first_tile + tile_step, ... into acc (one chunk of
 // features).  side / vsum collect the sums the 8-bit epilogue needs.
-template <int LPR, int UNROLL, typename Feat, int QMODE, bool QUANT, bool FUSED>
+template <int LPR, int UNROLL, typename Feat, int QMODE, bool QUANT, bool FUSED, typename AccT>
 __device__ __forceinline__ void accumulate_tiles(const SlotSource &src, const RowInfo &ri, int2 *my_stage, int lane,
                                                  bool lane_on, const typename Feat::elem_t *__restrict__ X,
                                                  int64_t ldx, int32_t f, const QParams &qp, int64_t first_tile,
-                                                 int64_t tile_step, float (&acc)[Feat::VEC], float &side,
-                                                 float &vsum)
+                                                 int64_t tile_step, AccT (&acc)[Feat::VEC], AccT &side,
+                                                 AccT &vsum)
 {
     for (int64_t t0 = first_tile * kTile; t0 < ri.n_slots; t0 += tile_step * kTile) {
         const int m = static_cast<int>(ri.n_slots - t0 < kTile ? ri.n_slots - t0 : kTile);
@@ -163,7 +176,7 @@ __device__ __forceinline__ void accumulate_tiles(const SlotSource &src, const Ro
                 float v = src.val[e];
                 if (QUANT) {
                     if (QMODE == kQRowScale) {
-                        if (qp.affine) side = __builtin_fmaf(v, qp.zero[c], side);
+                        if (qp.affine) side = fma_acc(v, qp.zero[c], side);
                         v *= qp.scale[c];
                     } else if (qp.affine) {
                         side += v;
@@ -213,15 +226,19 @@ __device__ __forceinline__ void accumulate_tiles(const SlotSource &src, const Ro
 
 // Removes the loader's bias, applies the 8-bit group constants and stores one chunk of Y[r, :].
 // `side` must already be summed over the lanes of the group.
-template <typename Feat, int QMODE, bool QUANT>
-__device__ __forceinline__ void finish_chunk(float (&acc)[Feat::VEC], float side, float vsum, bool lane_on, int32_t f,
-                                             const QParams &qp, float *__restrict__ y)
+template <typename Feat, int QMODE, bool QUANT, typename AccT>
+__device__ __forceinline__ void finish_chunk(const AccT (&acc_in)[Feat::VEC], AccT side_in, AccT vsum, bool lane_on,
+                                             int32_t f, const QParams &qp, float *__restrict__ y)
 {
     constexpr int VEC = Feat::VEC;
-    if (Feat::kBias != 0) {
+    float acc[VEC];
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) acc[i] = __builtin_fmaf(-static_cast<float>(Feat::kBias), vsum, acc[i]);
+    for (int i = 0; i < VEC; ++i) {
+        AccT a = acc_in[i];
+        if (Feat::kBias != 0) a = a - static_cast<AccT>(Feat::kBias) * vsum;   // exact product, one rounding
+        acc[i] = static_cast<float>(a);
     }
+    const float side = static_cast<float>(side_in);
     if (!lane_on) return;
     if (QUANT) {
         // x_hat = q*scale_g + zero_g, with the group constants taken out of the sum:
@@ -248,8 +265,8 @@ __device__ __forceinline__ void finish_chunk(float (&acc)[Feat::VEC], float side
     }
 }
 
-template <int LPR>
-__device__ __forceinline__ float group_sum(float v)
+template <int LPR, typename AccT>
+__device__ __forceinline__ AccT group_sum(AccT v)
 {
 #pragma unroll
     for (int d = LPR / 2; d >= 1; d >>= 1) v += __shfl_xor(v, d, LPR);

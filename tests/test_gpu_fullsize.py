@@ -57,3 +57,34 @@ def test_reddit_like(G):
 
 def test_rmat20(G):
     _run(G, "rmat20", (16, 32, 64, 128, 256), schemes=(SYM,))
+
+
+def test_entry_indices_beyond_2_31(G):
+    """A matrix with 2.6 billion stored entries (48 rows of 54 M): every sampled
+    entry index needs 64 bits.  Plan (with source indices) bit-exact against the
+    oracle, plan and fused multiplies against the oracle's product."""
+    import oracle as orc
+    import paper_2503_18427_amd as aes
+    n_rows, per_row, n_cols, F, W = 48, 54_000_000, 100_000, 64, 64
+    nnz = n_rows * per_row
+    assert nnz > 2 ** 31
+    g = torch.Generator(device="cuda")
+    g.manual_seed(5)
+    col = torch.randint(0, n_cols, (nnz,), dtype=torch.int32, device="cuda", generator=g)
+    val = torch.rand(nnz, device="cuda", generator=g)
+    rowptr = torch.arange(0, nnz + 1, per_row, dtype=torch.int64, device="cuda")
+    X = torch.randn((n_cols, F), device="cuda", generator=g)
+    print(f"[huge] nnz={nnz}", flush=True)
+    plan = aes.aes_sample_build(rowptr, col, val, n_cols, W, 3, want_eid=True)
+    Y = aes.aes_spmm_f32(plan, X)
+    Yf = aes.aes_spmm_fused_f32(rowptr, col, val, n_cols, W, X, 3)
+    torch.cuda.synchronize()
+    assert torch.equal(Y, Yf)
+    ref = orc.sample_build(rowptr.cpu().numpy(), col.cpu().numpy(), val.cpu().numpy(), W, seed=3)
+    S = int(ref[0][-1])
+    assert S == n_rows * W and int(ref[3].max()) > 2 ** 31
+    assert np.array_equal(plan.s_rowptr.cpu().numpy(), ref[0])
+    assert np.array_equal(plan.s_eid[:S].cpu().numpy(), ref[3])
+    assert np.array_equal(plan.s_col[:S].cpu().numpy(), ref[1])
+    assert np.array_equal(plan.s_val[:S].cpu().numpy().view(np.uint32), ref[2].view(np.uint32))
+    G.check_f32(plan, ref, X)

@@ -164,7 +164,7 @@ def test_empty_and_degenerate(G):
     torch.cuda.synchronize()
     assert torch.all(Y == 0)
     # one very long row and the all-starts-coincide row (modulus 1429)
-    for nnz, W in [(100000, 64), (1436, 64), (1 << 17, 1024)]:
+    for nnz, W in [(100000, 64), (1436, 64), (1 << 17, 1024), (3_000_000, 65536), (2_000_000, 1 << 20)]:
         rp = np.array([0, nnz], dtype=np.int64)
         rng = np.random.default_rng(nnz)
         col = rng.integers(0, 300, size=nnz).astype(np.int32)
