@@ -166,6 +166,9 @@ def main() -> int:
         "unit": "GB/s",
         "frac": leg_gbps["spmm_f32"] / HBM_PEAK_GBPS,
         "traffic": traffic,
+        "traffic_GBps": (traffic / (leg_ms["spmm_f32"] * 1e-3) / 1e9) if traffic else None,
+        "traffic_note": "FETCH_SIZE + WRITE_SIZE per launch from rocprofv3 --pmc, scaled by a known-size copy "
+                        "(profiles/); counted between L2 and the fabric, so reads served by the Infinity Cache are included",
         "algorithmic_bytes": leg_bytes["spmm_f32"],
         "avg_ms": leg_ms["spmm_f32"],
         "perfect_cache_model": {"distinct_feature_rows": distinct_cols, "compulsory_bytes": compulsory,

@@ -10,7 +10,6 @@
 
 namespace aes {
 
-
 constexpr int kTile = 64;          // slots staged in LDS per group per round
 
 enum QMode {
