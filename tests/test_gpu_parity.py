@@ -320,3 +320,31 @@ def test_gcn_layer_unsupported_shapes(G):
         with pytest.raises(aes.AesError) as e:
             aes.aes_gcn_layer_f32(plan, torch.zeros((n_cols, F), device="cuda"), torch.zeros((F, 8), device="cuda"))
         assert e.value.code == -2
+
+
+def test_unsorted_rows_and_special_values(G):
+    """Within-row order is the caller's (the sampler takes runs as stored), and
+    non-finite features propagate exactly where the oracle says: only to rows
+    that actually sample the poisoned feature row."""
+    import oracle as orc
+    import paper_2503_18427_amd as aes
+    rng = np.random.default_rng(77)
+    deg = rng.integers(0, 300, size=400)
+    rowptr, col, val = random_csr(400, 700, deg, rng, sort_cols=False)
+    X = rng.standard_normal((700, 64)).astype(np.float32)
+    for W in (16, 64):
+        plan, ref = G.check_plan(rowptr, col, val, 700, W, 0)
+        G.check_f32(plan, ref, X, use_perm=False)
+    Xp = X.copy()
+    Xp[13, :] = np.nan
+    Xp[500, 7] = np.inf
+    Xp[600, 9] = -np.inf
+    plan, ref = G.check_plan(rowptr, col, val, 700, 16, 0)
+    Y = aes.aes_spmm_f32(plan, G.to_dev(Xp), use_perm=False).cpu().numpy()
+    with np.errstate(invalid="ignore"):
+        Yref = orc.spmm_plan(ref[0], ref[1], ref[2], Xp)
+    assert np.array_equal(np.isnan(Y), np.isnan(Yref))
+    assert np.array_equal(np.isposinf(Y), np.isposinf(Yref)) and np.array_equal(np.isneginf(Y), np.isneginf(Yref))
+    ok = np.isfinite(Yref)
+    assert np.isnan(Yref).any() and ok.any()
+    assert np.max(np.abs(Y[ok] - Yref[ok])) < 1e-4
