@@ -30,16 +30,29 @@ def _run(G, name, widths, exact=False, schemes=(SYM,)):
     rows = np.sort(np.random.default_rng(1).choice(d["n"], size=min(N_ROWS_CHECKED, d["n"]), replace=False))
     # the sample always holds the longest rows too
     rows = np.unique(np.concatenate([rows, np.argsort(np.diff(rowptr))[-8:]])).astype(np.int64)
+    import paper_2503_18427_amd as aes
     q = {s: G.check_quantize(X, s, w.q_granularity) for s in schemes}
-    for W in tuple(widths) + ((0,) if exact else ()):
+    deg = d["rowptr"][1:] - d["rowptr"][:-1]
+    Y_exact = None
+    for W in ((0,) if exact else ()) + tuple(widths):
         plan, ref = G.check_plan(d["rowptr"], d["colidx"], d["val"], d["n"], W, 0)
-        _, c, g = G.check_f32(plan, ref, X, rows=rows)
+        Y, c, g = G.check_f32(plan, ref, X, rows=rows, use_perm=False)        # bench.py's launch configuration
         print(f"[{name}] W={W} slots={int(ref[0][-1])} fp32 err comp={c:.2e} glob={g:.2e}", flush=True)
+        # properties that hold at any size, checked on EVERY row: the single-kernel form is
+        # bit-identical, and rows that fit (row_nnz <= W) are bit-identical to the unsampled product
+        Yf = aes.aes_spmm_fused_f32(d["rowptr"], d["colidx"], d["val"], d["n"], W, X)
+        torch.cuda.synchronize()
+        assert torch.equal(Yf, Y)
+        del Yf
+        if W == 0:
+            Y_exact = Y
+        elif Y_exact is not None:
+            short = deg <= W
+            assert torch.equal(Y[short], Y_exact[short])
         for s in schemes:
-            _, c, g = G.check_q8(plan, ref, q[s][0], q[s][1], s, w.q_granularity, rows=rows)
+            _, c, g = G.check_q8(plan, ref, q[s][0], q[s][1], s, w.q_granularity, rows=rows, use_perm=False)
             print(f"[{name}] W={W} int8 scheme={s} err comp={c:.2e} glob={g:.2e}", flush=True)
         del plan, ref
-    # a short-row property that holds at any size: rows with nnz <= W are exact SpMM rows
     return d
 
 
