@@ -457,6 +457,8 @@ extern "C" int aes_quantize_features(int64_t n, int32_t F, const float *X, int64
     float *group_lo = partial + static_cast<size_t>(n_slabs) * 2 * F;
     float *group_d = group_lo + F;
     const unsigned col_blocks = static_cast<unsigned>(aes::ceil_div(F, kColsPerBlock));
+    if (col_blocks > 65535u)
+        return aes::fail(AES_ERR_UNSUPPORTED, "%s: F=%d too wide for per-column / per-tensor groups", what, (int)F);
     if (n > 0) {
         column_partials_kernel<<<dim3(n_slabs, col_blocks), dim3(kBlock), 0, stream>>>(n, F, X, ldx, affine, partial);
         if (int rc = aes::check_launch("aes_quantize_features/partials")) return rc;
