@@ -4,6 +4,8 @@
     python -m paper_2503_18427_amd.studies strategies  [workload]
     python -m paper_2503_18427_amd.studies loading     [workload]
     python -m paper_2503_18427_amd.studies layer       [workload]
+    python -m paper_2503_18427_amd.studies graph       [workload]
+    python -m paper_2503_18427_amd.studies sampling-rate [workload]
 
 They reproduce the *shape* of the paper's evaluation on the synthetic workloads
 (the paper's datasets are not available): kernel time and error against the
@@ -207,14 +209,68 @@ def layer(name: str) -> None:
     print()
 
 
+def sampling_rate(name: str) -> None:
+    """Distribution of the per-row sampling rate slots / row_nnz (the quantity of the paper's Fig. 5)."""
+    d = configs.make(name, "cuda")
+    n = d["n"]
+    deg = (d["rowptr"][1:] - d["rowptr"][:-1]).double()
+    print(f"### per-row sampling rate, `{name}` (n = {n}, nnz = {d['nnz']}): share of rows whose rate is at most x\n")
+    xs = (0.05, 0.1, 0.2, 0.4, 0.6, 0.8, 0.99)
+    print("| W | " + " | ".join(f"x = {x}" for x in xs) + " | mean rate | edges kept |")
+    print("|---|" + "---|" * (len(xs) + 2))
+    for W in (16, 32, 64, 128, 256, 512, 1024):
+        plan = aes.aes_sample_build(d["rowptr"], d["colidx"], d["val"], n, W)
+        slots = (plan.s_rowptr[1:] - plan.s_rowptr[:-1]).double()
+        rate = torch.where(deg > 0, slots / deg.clamp(min=1), torch.ones_like(deg))
+        cdf = " | ".join(f"{float((rate <= x).double().mean()) * 100:.1f} %" for x in xs)
+        print(f"| {W} | {cdf} | {float(rate.mean()):.3f} | {float(slots.sum() / deg.sum()) * 100:.1f} % |")
+    print()
+
+
+def graph(name: str) -> None:
+    """One whole step launched eagerly vs replayed from a captured HIP graph (small, launch-bound workloads)."""
+    d = configs.make(name, "cuda")
+    w = d["workload"]
+    n, F, X = d["n"], d["F"], d["X"]
+    scheme, gran = w.q_scheme, w.q_granularity
+    W = w.widths[0]
+    csr = (d["rowptr"], d["colidx"], d["val"])
+    plan = aes.aes_sample_build(*csr, n, W)
+    ws_b = torch.empty(max(aes.aes_sample_workspace_bytes(n), 8), dtype=torch.uint8, device="cuda")
+    ws_q = torch.empty(max(aes.aes_quantize_workspace_bytes(n, F, gran), 8), dtype=torch.uint8, device="cuda")
+    q = aes.aes_quantize_features(X, scheme, gran)
+    Y = torch.empty((n, F), device="cuda")
+    Yq = torch.empty((n, F), device="cuda")
+
+    def step():
+        aes.aes_sample_build(*csr, n, W, out=plan, workspace=ws_b)
+        aes.aes_spmm_f32(plan, X, Y)
+        aes.aes_quantize_features(X, scheme, gran, out=q, workspace=ws_q)
+        aes.aes_spmm_q8(plan, q[0], scheme, gran, q[1], q[2], Yq)
+
+    t_eager = _time_ms(step, iters=50, warmup=5)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step()
+    t_graph = _time_ms(g.replay, iters=50, warmup=5)
+    print(f"### whole step, eager launches vs HIP-graph replay, `{name}` (W = {W}): "
+          f"{t_eager:.3f} ms vs {t_graph:.3f} ms\n")
+
+
 def main(argv) -> int:
-    if len(argv) < 2 or argv[1] not in ("width-sweep", "strategies", "loading", "layer"):
+    if len(argv) < 2 or argv[1] not in ("width-sweep", "strategies", "loading", "layer", "graph", "sampling-rate"):
         print(__doc__)
         return 2
     assert torch.cuda.is_available(), "the studies need a GPU"
     name = argv[2] if len(argv) > 2 else {"width-sweep": "rmat20", "strategies": "reddit_like",
-                                          "loading": "products_like", "layer": "products_like"}[argv[1]]
-    {"width-sweep": width_sweep, "strategies": strategies, "loading": loading, "layer": layer}[argv[1]](name)
+                                          "loading": "products_like", "layer": "products_like", "graph": "arxiv_like", "sampling-rate": "reddit_like"}[argv[1]]
+    {"width-sweep": width_sweep, "strategies": strategies, "loading": loading, "layer": layer,
+     "graph": graph, "sampling-rate": sampling_rate}[argv[1]](name)
     return 0
 
 
