@@ -134,3 +134,25 @@ def test_binding_rejects_host_tensors():
     with pytest.raises(TypeError):
         aes.aes_sample_build(torch.zeros(3, dtype=torch.int64), torch.zeros(2, dtype=torch.int32),
                              torch.zeros(2), 2, 4)
+
+
+def test_last_error_is_per_thread(lib):
+    """The message buffer is thread-local: a failure in one thread does not
+    overwrite what another thread reads."""
+    import threading
+    import paper_2503_18427_amd as aes
+    fake = 0x1000
+    assert lib.aes_spmm_f32(-1, 4, 0, fake, fake, fake, None, fake, 8, 8, fake, 8, None) == -1
+    mine = aes.aes_last_error()
+    seen = {}
+
+    def other():
+        seen["before"] = aes.aes_last_error()
+        lib.aes_quantize_features(-5, 8, fake, 8, 1, 1, fake, 8, fake, fake, fake, 1 << 20, None)
+        seen["after"] = aes.aes_last_error()
+
+    t = threading.Thread(target=other)
+    t.start()
+    t.join()
+    assert seen["before"] == "" and "aes_quantize_features" in seen["after"]
+    assert aes.aes_last_error() == mine and "aes_spmm_f32" in mine
