@@ -139,8 +139,9 @@ int aes_sample_build(int64_t n_rows, int64_t n_cols, int64_t nnz,
 
 /*
  * Y[r, c] = sum_k s_val[k] * X[s_col[k], c] over the slots k of row r, for
- * 0 <= c < F.  float32 accumulation (fused multiply-add); the summation order
- * within a row is fixed, so results are bit-reproducible from run to run.
+ * 0 <= c < F.  float32 accumulation by fused multiply-add in slot order (float64
+ * for the long rows described under W); the summation order within a row is
+ * fixed, so results are bit-reproducible from run to run.
  * Rows without slots give zero rows.  Every element of Y[0..n_rows, 0..F) is
  * written; padding columns F..ldy are not touched.
  *
@@ -151,9 +152,9 @@ int aes_sample_build(int64_t n_rows, int64_t n_cols, int64_t nnz,
  *                   W == 0 or W > 2048 rows longer than 2048 slots are shared by
  *                   all wavefronts of a workgroup (partial sums carried in
  *                   float64 and added in a fixed order) instead of being left
- *                   to one lane group.  A row with
- *                   more slots than a non-zero W states is still computed
- *                   correctly, only without that sharing.
+ *                   to one lane group.  A row with more slots than a non-zero
+ *                   W states is still computed correctly, only without that
+ *                   sharing.
  *   s_rowptr/s_col/s_val [dev]  a plan from aes_sample_build (or any CSR with
  *                   int64 rowptr, int32 colidx, float32 val); s_col / s_val may
  *                   be NULL only when the plan has no slots at all
