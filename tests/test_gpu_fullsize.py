@@ -101,3 +101,62 @@ def test_entry_indices_beyond_2_31(G):
     assert np.array_equal(plan.s_col[:S].cpu().numpy(), ref[1])
     assert np.array_equal(plan.s_val[:S].cpu().numpy().view(np.uint32), ref[2].view(np.uint32))
     G.check_f32(plan, ref, X)
+
+
+def test_papers_like_scale(G):
+    """111 M nodes, 1.66 G entries, 53 GB of float32 features on one GPU: every
+    index path beyond 2^31 (entries, slots, feature elements).  The oracle runs on
+    the sub-matrix of a seeded row sample (its CSR segments and the feature rows
+    they touch are copied to the host), which is Algorithm 1 row by row."""
+    import oracle as orc
+    import paper_2503_18427_amd as aes
+    from workloads import configs
+    torch.cuda.empty_cache()
+    free, _ = torch.cuda.mem_get_info()
+    if free < 230 * 2 ** 30:
+        pytest.skip("needs about 200 GiB of free GPU memory")
+    d = configs.make("papers_like", "cuda")
+    w = d["workload"]
+    n, F, W = d["n"], d["F"], w.widths[0]
+    rowptr, colidx, val, X = d["rowptr"], d["colidx"], d["val"], d["X"]
+    print(f"[papers_like] n={n} nnz={d['nnz']}", flush=True)
+    assert d["nnz"] > 2 ** 30 and n * F > 2 ** 33
+    plan = aes.aes_sample_build(rowptr, colidx, val, n, W, 0)
+    Y = aes.aes_spmm_f32(plan, X)
+    q = aes.aes_quantize_features(X, SYM, w.q_granularity)
+    Yq = aes.aes_spmm_q8(plan, q[0], SYM, w.q_granularity, q[1], q[2])
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(0)
+    deg = rowptr[1:] - rowptr[:-1]
+    rows = np.unique(np.concatenate([rng.choice(n, 3000, replace=False), [0, n - 1, int(torch.argmax(deg))]]))
+    rt = torch.from_numpy(rows).cuda()
+    b, e = rowptr[rt], rowptr[rt + 1]
+    seg = torch.cat([torch.arange(int(bb), int(ee), device="cuda") for bb, ee in zip(b.tolist(), e.tolist())])
+    sub_rowptr = np.concatenate([[0], np.cumsum((e - b).cpu().numpy())]).astype(np.int64)
+    sub_col, sub_val = colidx[seg].cpu().numpy(), val[seg].cpu().numpy()
+    cols = np.unique(sub_col)                       # the feature rows the sampled rows can touch
+    remap = np.full(n, -1, dtype=np.int64)
+    remap[cols] = np.arange(cols.size)
+    sub_col = remap[sub_col].astype(np.int32)
+    ct = torch.from_numpy(cols).cuda()
+    # plan rows: slot counts and sampled columns, bit for bit
+    ref = orc.sample_build(sub_rowptr, sub_col, sub_val, W, 0)
+    got_counts = (plan.s_rowptr[rt + 1] - plan.s_rowptr[rt]).cpu().numpy()
+    assert np.array_equal(got_counts, np.diff(ref[0]))
+    pseg = torch.cat([torch.arange(int(bb), int(ee), device="cuda")
+                      for bb, ee in zip(plan.s_rowptr[rt].tolist(), plan.s_rowptr[rt + 1].tolist())])
+    assert np.array_equal(remap[plan.s_col[pseg].cpu().numpy()], ref[1])
+    assert np.array_equal(plan.s_val[pseg].cpu().numpy().view(np.uint32), ref[2].view(np.uint32))
+    # products
+    from helpers import rel_err
+    Yref, Yabs = orc.spmm_plan(ref[0], ref[1], ref[2], X[ct].cpu().numpy(), want_abs=True)
+    comp, glob = rel_err(Y[rt].cpu().numpy(), Yref, Yabs)
+    print(f"[papers_like] fp32 err comp={comp:.2e} glob={glob:.2e}", flush=True)
+    assert comp <= G.F32_TOL and glob <= G.F32_TOL
+    rq, rs = q[0][ct].cpu().numpy(), q[1][ct].cpu().numpy()
+    oq, os_, oz = orc.quantize(X[ct].cpu().numpy(), SYM, w.q_granularity)
+    assert np.array_equal(rq, oq) and np.array_equal(rs.view(np.uint32), os_.view(np.uint32))
+    Yqref, Yqabs = orc.spmm_q8(ref[0], ref[1], ref[2], oq, SYM, w.q_granularity, os_, oz, want_abs=True)
+    comp, glob = rel_err(Yq[rt].cpu().numpy(), Yqref, Yqabs)
+    print(f"[papers_like] int8 err comp={comp:.2e} glob={glob:.2e}", flush=True)
+    assert comp <= G.Q8_TOL and glob <= G.Q8_TOL

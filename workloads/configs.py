@@ -55,6 +55,10 @@ WORKLOADS = {w.name: w for w in [
     Workload("rmat20", "rmat", 1 << 20, 64.0, rmat_scale=20, rmat_edges=1 << 26, norm="row",
              F=256, x_dist="uniform", widths=(16, 32, 64, 128, 256),
              q_granularity=Q_PER_COLUMN, seed=4),
+    # beyond the five benchmark configurations: a citation-graph shape two orders of magnitude larger
+    # (111 M nodes, ~1.66 G stored entries), to exercise 64-bit indexing and the 288 GB of one MI355X
+    Workload("papers_like", "powerlaw", 111_000_000, 14.0, gamma=2.2, norm="row", F=128,
+             widths=(32,), q_granularity=Q_PER_ROW, seed=9),
     # shrunk recipes for CPU-only tests and quick GPU parity
     Workload("arxiv_small", "powerlaw", 6_000, 7.0, gamma=2.2, norm="sym", F=128,
              widths=(32, 64), q_granularity=Q_PER_COLUMN, seed=11),
