@@ -180,3 +180,28 @@ def test_accuracy_first_invariants(oracle):
                 assert e.tolist() == list(range(nnz))
             else:
                 assert e.tolist() == [(i * 1429) % nnz for i in range(W)]
+
+
+def test_sampler_properties_hypothesis(oracle):
+    """Property test over (W, row_nnz, seed, mode): slot count, index range, runs of
+    N consecutive entries, and agreement of every start with exact-integer Eq. 3."""
+    from hypothesis import given, settings, strategies as st
+
+    @settings(max_examples=300, deadline=None)
+    @given(W=st.integers(1, 300), nnz=st.integers(0, 40000), seed=st.integers(0, 2 ** 64 - 1),
+           mode=st.sampled_from([0, 1, 2]), rid=st.integers(0, 2 ** 31 - 2))
+    def check(W, nnz, seed, mode, rid):
+        N, cnt = oracle.strategy(nnz, W, mode)
+        assert N * cnt == oracle.row_slots(nnz, W, mode)
+        if nnz <= W:
+            assert (N, cnt) == (nnz, 1)
+            return
+        assert 1 <= N <= W and 1 <= cnt <= W and N * cnt <= W
+        s_r = oracle.row_offset(seed, rid)
+        assert s_r == (seed * (2 * rid + 1) * 2654435761) & 0xFFFFFFFF
+        for i in (0, cnt // 2, cnt - 1):
+            st_i = oracle.hash_start(i + s_r, nnz, N)
+            assert st_i == ((i + s_r) * 1429) % (nnz - N + 1)
+            assert 0 <= st_i and st_i + N - 1 <= nnz - 1
+
+    check()

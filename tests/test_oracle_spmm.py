@@ -29,13 +29,14 @@ def _dense_from_elements(rowptr, eids, s_rowptr, col, val, n_cols):
 
 @pytest.mark.parametrize("W", [4, 16, 32, 48, 64])
 @pytest.mark.parametrize("seed", [0, 99])
-def test_brute_force_dense(oracle, W, seed):
+@pytest.mark.parametrize("mode", [0, 1, 2])
+def test_brute_force_dense(oracle, W, seed, mode):
     rowptr, col, val, X = _case(W)
-    s_rowptr, s_col, s_val, s_eid = oracle.sample_build(rowptr, col, val, W, seed=seed)
+    s_rowptr, s_col, s_val, s_eid = oracle.sample_build(rowptr, col, val, W, seed=seed, mode=mode)
     A = _dense_from_elements(rowptr, s_eid, s_rowptr, col, val, X.shape[0])
     Yd = A @ X.astype(np.float64)
     Y1, Yabs = oracle.spmm_plan(s_rowptr, s_col, s_val, X, want_abs=True)
-    Y2 = oracle.aes_spmm(rowptr, col, val, W, X, seed=seed)
+    Y2 = oracle.aes_spmm(rowptr, col, val, W, X, seed=seed, mode=mode)
     tol = 1e-12 * np.maximum(Yabs, 1.0)
     assert np.all(np.abs(Y1 - Yd) <= tol)
     assert np.all(np.abs(Y2 - Yd) <= tol)
