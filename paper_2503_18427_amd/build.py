@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libaes_spmm.so")
-SOURCES = ["aes_common.cpp", "sample_build.hip", "spmm.hip", "quantize.hip", "gcn_layer.hip"]
+SOURCES = ["aes_common.cpp", "sample_build.hip", "spmm_f32.hip", "spmm_q8.hip", "quantize.hip", "gcn_layer.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -26,16 +26,28 @@ def lib_path() -> str:
     return LIB
 
 
-def build(verbose: bool = False) -> str:
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + ["-I", os.path.join(ROOT, "include"), "-I", CSRC]
-    for s in SOURCES:
-        path = os.path.join(CSRC, s)
-        cmd += (["-x", "hip", path] if s.endswith(".cpp") else [path])
-    cmd += ["-o", LIB]
+def _compile(hipcc: str, src: str, obj: str, verbose: bool) -> None:
+    flags = [f for f in HIPCC_FLAGS if f != "-shared"]
+    cmd = [hipcc] + flags + ["-I", os.path.join(ROOT, "include"), "-I", CSRC, "-x", "hip", "-c", src, "-o", obj]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
+
+
+def build(verbose: bool = False) -> str:
+    """Compile every source to an object (in parallel) under _build/, then link the shared library."""
+    from concurrent.futures import ThreadPoolExecutor
+
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    objdir = os.path.join(HERE, "_build")
+    os.makedirs(objdir, exist_ok=True)
+    jobs = [(os.path.join(CSRC, s), os.path.join(objdir, os.path.splitext(s)[0] + ".o")) for s in SOURCES]
+    with ThreadPoolExecutor(max_workers=min(len(jobs), 8)) as pool:
+        list(pool.map(lambda j: _compile(hipcc, j[0], j[1], verbose), jobs))
+    link = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-fno-gpu-rdc"] + [o for _, o in jobs] + ["-o", LIB]
+    if verbose:
+        print(" ".join(link), flush=True)
+    subprocess.run(link, check=True)
     return LIB
 
 

@@ -1,0 +1,49 @@
+// aes_spmm_f32 / aes_spmm_fused_f32: float32 features through the SpMM kernel
+// (Sec. 3.2 Algorithm 1, accumulation loop; the fused form samples on the fly).
+#include "spmm_kernel.hpp"
+
+namespace {
+
+using namespace aes;
+
+template <bool FUSED>
+int run_f32(const char *what, int64_t n_rows, const SlotSource &src, const int32_t *row_perm, const float *X,
+            int64_t ldx, int32_t F, float *Y, int64_t ldy, hipStream_t stream)
+{
+    const bool fast = aes::aligned(X, 16) && aes::aligned(Y, 16) && F % 4 == 0 && ldx % 4 == 0 && ldy % 4 == 0;
+    const bool lr = long_rows_possible(src.W);
+    QParams qp = {nullptr, nullptr, 0, 0};
+    if (fast) return dispatch_lanes<FeatF32<4>, kQNone, false, FUSED>(lr, n_rows, src, row_perm, X, ldx, F, qp, Y, ldy, stream, what);
+    return launch_rows<64, 4, FeatF32<1>, kQNone, false, FUSED>(lr, n_rows, src, row_perm, X, ldx, F, qp, Y, ldy, stream, what);
+}
+
+}  // namespace
+
+extern "C" int aes_spmm_f32(int64_t n_rows, int64_t n_cols, int32_t W,
+                            const int64_t *s_rowptr, const int32_t *s_col, const float *s_val,
+                            const int32_t *row_perm,
+                            const float *X, int64_t ldx, int32_t F,
+                            float *Y, int64_t ldy, void *stream)
+{
+    const char *what = "aes_spmm_f32";
+    if (int rc = check_common(what, n_rows, n_cols, s_rowptr, s_col, s_val, X, ldx, F, Y, ldy)) return rc;
+    if (int rc = check_sampling(what, W, AES_STRATEGY_ADAPTIVE)) return rc;
+    if (n_rows == 0) return AES_OK;
+    const SlotSource src = {s_rowptr, s_col, s_val, W, 0, 0};   // W: only the bound on slots per row
+    return run_f32<false>(what, n_rows, src, row_perm, X, ldx, F, Y, ldy, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int aes_spmm_fused_f32(int64_t n_rows, int64_t n_cols,
+                                  const int64_t *rowptr, const int32_t *colidx, const float *val,
+                                  int32_t W, uint64_t seed, int32_t strategy,
+                                  const float *X, int64_t ldx, int32_t F,
+                                  float *Y, int64_t ldy, void *stream)
+{
+    const char *what = "aes_spmm_fused_f32";
+    if (int rc = check_common(what, n_rows, n_cols, rowptr, colidx, val, X, ldx, F, Y, ldy)) return rc;
+    if (int rc = check_sampling(what, W, strategy)) return rc;
+    if (n_rows == 0) return AES_OK;
+    const SlotSource src = {rowptr, colidx, val, W, strategy, seed};
+    return run_f32<true>(what, n_rows, src, nullptr, X, ldx, F, Y, ldy, static_cast<hipStream_t>(stream));
+}
+

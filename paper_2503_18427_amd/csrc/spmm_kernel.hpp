@@ -1,4 +1,5 @@
-// aes_spmm_f32 / aes_spmm_q8: the multiply stage of AES-SpMM on gfx950.
+// The SpMM kernel of the multiply stage (aes_spmm_f32 / aes_spmm_q8 and their single-kernel
+// forms) on gfx950, with its launch helpers; instantiated by spmm_f32.hip and spmm_q8.hip.
 //
 // Method: Sec. 3.2 Algorithm 1, accumulation loop: result += sh_val[k] *
 // B[sh_col[k], cid] over the row's sampled slots; the quantised variant applies
@@ -21,11 +22,11 @@
 //
 // The kernel is bound by the gather traffic (about 2 flop per 4 bytes), not by
 // arithmetic, so there is no MFMA here.
+#pragma once
+
 #include "spmm_core.hpp"
 
-namespace {
-
-using namespace aes;
+namespace aes {
 
 // Rows with more slots than this are not left to one lane group: all groups of the
 // workgroup share such a row (LONG variant, used when the caller's width allows them).
@@ -128,7 +129,7 @@ spmm_rows_kernel(int64_t n_rows, SlotSource src, const int32_t *__restrict__ row
 }
 
 template <int LPR, int UNROLL, typename Feat, int QMODE, bool QUANT, bool FUSED>
-int launch_rows(bool long_rows, int64_t n_rows, const SlotSource &src,
+inline int launch_rows(bool long_rows, int64_t n_rows, const SlotSource &src,
                 const int32_t *row_perm, const typename Feat::elem_t *X, int64_t ldx, int32_t F, QParams qp,
                 float *Y, int64_t ldy, hipStream_t stream, const char *what)
 {
@@ -146,14 +147,14 @@ int launch_rows(bool long_rows, int64_t n_rows, const SlotSource &src,
 }
 
 // Lanes per row when every lane owns `vec` consecutive features.
-int lanes_per_row(int32_t F, int vec)
+inline int lanes_per_row(int32_t F, int vec)
 {
     int l = aes::pow2_ceil(aes::ceil_div(F, vec));
     return l < 8 ? 8 : l > 64 ? 64 : l;
 }
 
 // Rows can exceed kLongRow slots only without sampling (W == 0) or with a very wide W.
-bool long_rows_possible(int32_t W) { return W == 0 || W > kLongRow; }
+inline bool long_rows_possible(int32_t W) { return W == 0 || W > kLongRow; }
 
 // Vector path: pick the lane-group width from F.
 template <typename Feat, int QMODE, bool QUANT, bool FUSED>
@@ -169,53 +170,7 @@ int dispatch_lanes(bool lr, int64_t n_rows, const SlotSource &src, const int32_t
     }
 }
 
-template <bool FUSED>
-int run_f32(const char *what, int64_t n_rows, const SlotSource &src, const int32_t *row_perm, const float *X,
-            int64_t ldx, int32_t F, float *Y, int64_t ldy, hipStream_t stream)
-{
-    const bool fast = aes::aligned(X, 16) && aes::aligned(Y, 16) && F % 4 == 0 && ldx % 4 == 0 && ldy % 4 == 0;
-    const bool lr = long_rows_possible(src.W);
-    QParams qp = {nullptr, nullptr, 0, 0};
-    if (fast) return dispatch_lanes<FeatF32<4>, kQNone, false, FUSED>(lr, n_rows, src, row_perm, X, ldx, F, qp, Y, ldy, stream, what);
-    return launch_rows<64, 4, FeatF32<1>, kQNone, false, FUSED>(lr, n_rows, src, row_perm, X, ldx, F, qp, Y, ldy, stream, what);
-}
-
-// 8-bit features: 4 codes per lane when rows are 4-byte aligned, else element-wise.
-template <bool SIGNED, int QMODE, bool FUSED>
-int dispatch_q8(bool fast, int64_t n_rows, const SlotSource &src, const int32_t *row_perm, const int8_t *Xq,
-                int64_t ldq, int32_t F, QParams qp, float *Y, int64_t ldy, hipStream_t stream, const char *what)
-{
-    const bool lr = long_rows_possible(src.W);
-    if (fast)
-        return dispatch_lanes<FeatQ8<4, SIGNED>, QMODE, true, FUSED>(lr, n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
-    return launch_rows<64, 4, FeatQ8<1, SIGNED>, QMODE, true, FUSED>(lr, n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
-}
-
-template <bool FUSED>
-int run_q8(const char *what, int64_t n_rows, const SlotSource &src, const int32_t *row_perm, const int8_t *Xq,
-           int64_t ldq, int32_t F, int32_t scheme, int32_t granularity, const float *scale, const float *zero,
-           float *Y, int64_t ldy, hipStream_t stream)
-{
-    if (scheme != AES_Q_AFFINE_FLOOR_U8 && scheme != AES_Q_SYMMETRIC_RNE_I8)
-        return aes::fail(AES_ERR_INVALID_ARG, "%s: unknown scheme %d", what, (int)scheme);
-    if (granularity < AES_Q_PER_TENSOR || granularity > AES_Q_PER_ROW)
-        return aes::fail(AES_ERR_INVALID_ARG, "%s: unknown granularity %d", what, (int)granularity);
-    if (scale == nullptr) return aes::fail(AES_ERR_INVALID_ARG, "%s: scale is NULL", what);
-    const bool affine = scheme == AES_Q_AFFINE_FLOOR_U8;
-    if (affine && zero == nullptr) return aes::fail(AES_ERR_INVALID_ARG, "%s: zero is NULL for the affine scheme", what);
-    if (n_rows == 0) return AES_OK;
-    const bool fast = aes::aligned(Y, 16) && ldy % 4 == 0 && aes::aligned(Xq, 4) && F % 4 == 0 && ldq % 4 == 0;
-    QParams qp = {scale, zero, granularity, affine ? 1 : 0};
-    const bool per_row = granularity == AES_Q_PER_ROW;
-    if (affine) {
-        if (per_row) return dispatch_q8<false, kQRowScale, FUSED>(fast, n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
-        return dispatch_q8<false, kQNone, FUSED>(fast, n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
-    }
-    if (per_row) return dispatch_q8<true, kQRowScale, FUSED>(fast, n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
-    return dispatch_q8<true, kQNone, FUSED>(fast, n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
-}
-
-int check_sampling(const char *what, int32_t W, int32_t strategy)
+inline int check_sampling(const char *what, int32_t W, int32_t strategy)
 {
     if (W < 0 || W > AES_MAX_W) return aes::fail(AES_ERR_INVALID_ARG, "%s: W=%d outside 0..%d", what, (int)W, (int)AES_MAX_W);
     if (strategy < AES_STRATEGY_ADAPTIVE || strategy > AES_STRATEGY_SFS)
@@ -223,7 +178,7 @@ int check_sampling(const char *what, int32_t W, int32_t strategy)
     return AES_OK;
 }
 
-int check_common(const char *what, int64_t n_rows, int64_t n_cols, const int64_t *s_rowptr, const int32_t *s_col,
+inline int check_common(const char *what, int64_t n_rows, int64_t n_cols, const int64_t *s_rowptr, const int32_t *s_col,
                  const float *s_val, const void *X, int64_t ldx, int32_t F, const float *Y, int64_t ldy)
 {
     if (n_rows < 0 || n_cols < 0)
@@ -241,64 +196,4 @@ int check_common(const char *what, int64_t n_rows, int64_t n_cols, const int64_t
     return AES_OK;
 }
 
-}  // namespace
-
-extern "C" int aes_spmm_f32(int64_t n_rows, int64_t n_cols, int32_t W,
-                            const int64_t *s_rowptr, const int32_t *s_col, const float *s_val,
-                            const int32_t *row_perm,
-                            const float *X, int64_t ldx, int32_t F,
-                            float *Y, int64_t ldy, void *stream)
-{
-    const char *what = "aes_spmm_f32";
-    if (int rc = check_common(what, n_rows, n_cols, s_rowptr, s_col, s_val, X, ldx, F, Y, ldy)) return rc;
-    if (int rc = check_sampling(what, W, AES_STRATEGY_ADAPTIVE)) return rc;
-    if (n_rows == 0) return AES_OK;
-    const SlotSource src = {s_rowptr, s_col, s_val, W, 0, 0};   // W: only the bound on slots per row
-    return run_f32<false>(what, n_rows, src, row_perm, X, ldx, F, Y, ldy, static_cast<hipStream_t>(stream));
-}
-
-extern "C" int aes_spmm_q8(int64_t n_rows, int64_t n_cols, int32_t W,
-                           const int64_t *s_rowptr, const int32_t *s_col, const float *s_val,
-                           const int32_t *row_perm,
-                           const int8_t *Xq, int64_t ldq, int32_t F,
-                           int32_t scheme, int32_t granularity,
-                           const float *scale, const float *zero,
-                           float *Y, int64_t ldy, void *stream)
-{
-    const char *what = "aes_spmm_q8";
-    if (int rc = check_common(what, n_rows, n_cols, s_rowptr, s_col, s_val, Xq, ldq, F, Y, ldy)) return rc;
-    if (int rc = check_sampling(what, W, AES_STRATEGY_ADAPTIVE)) return rc;
-    const SlotSource src = {s_rowptr, s_col, s_val, W, 0, 0};   // W: only the bound on slots per row
-    return run_q8<false>(what, n_rows, src, row_perm, Xq, ldq, F, scheme, granularity, scale, zero, Y, ldy,
-                         static_cast<hipStream_t>(stream));
-}
-
-extern "C" int aes_spmm_fused_f32(int64_t n_rows, int64_t n_cols,
-                                  const int64_t *rowptr, const int32_t *colidx, const float *val,
-                                  int32_t W, uint64_t seed, int32_t strategy,
-                                  const float *X, int64_t ldx, int32_t F,
-                                  float *Y, int64_t ldy, void *stream)
-{
-    const char *what = "aes_spmm_fused_f32";
-    if (int rc = check_common(what, n_rows, n_cols, rowptr, colidx, val, X, ldx, F, Y, ldy)) return rc;
-    if (int rc = check_sampling(what, W, strategy)) return rc;
-    if (n_rows == 0) return AES_OK;
-    const SlotSource src = {rowptr, colidx, val, W, strategy, seed};
-    return run_f32<true>(what, n_rows, src, nullptr, X, ldx, F, Y, ldy, static_cast<hipStream_t>(stream));
-}
-
-extern "C" int aes_spmm_fused_q8(int64_t n_rows, int64_t n_cols,
-                                 const int64_t *rowptr, const int32_t *colidx, const float *val,
-                                 int32_t W, uint64_t seed, int32_t strategy,
-                                 const int8_t *Xq, int64_t ldq, int32_t F,
-                                 int32_t scheme, int32_t granularity,
-                                 const float *scale, const float *zero,
-                                 float *Y, int64_t ldy, void *stream)
-{
-    const char *what = "aes_spmm_fused_q8";
-    if (int rc = check_common(what, n_rows, n_cols, rowptr, colidx, val, Xq, ldq, F, Y, ldy)) return rc;
-    if (int rc = check_sampling(what, W, strategy)) return rc;
-    const SlotSource src = {rowptr, colidx, val, W, strategy, seed};
-    return run_q8<true>(what, n_rows, src, nullptr, Xq, ldq, F, scheme, granularity, scale, zero, Y, ldy,
-                        static_cast<hipStream_t>(stream));
-}
+}  // namespace aes
