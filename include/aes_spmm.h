@@ -51,7 +51,10 @@ typedef enum aes_status {
 typedef enum aes_q_granularity {
     AES_Q_PER_TENSOR = 0,      /* 1 group                                        */
     AES_Q_PER_COLUMN = 1,      /* F groups, one per feature column               */
-    AES_Q_PER_ROW = 2          /* n groups, one per node                         */
+    AES_Q_PER_ROW = 2,         /* n groups, one per node                         */
+    AES_Q_PER_ROW_FOLDED = 3   /* aes_spmm_q8 only: per-node constants already    */
+                               /* folded into the plan's values, see              */
+                               /* aes_plan_fold_row_constants                     */
 } aes_q_granularity;
 
 typedef enum aes_q_scheme {
@@ -229,7 +232,8 @@ int aes_dequantize_features(int64_t n, int32_t F, const int8_t *Xq, int64_t ldq,
  *
  *   Xq    [dev]  n_cols x F bytes, leading dimension ldq
  *   scale, zero [dev]  as written by aes_quantize_features; zero may be NULL
- *                for SYMMETRIC_RNE_I8
+ *                for SYMMETRIC_RNE_I8 (for AES_Q_PER_ROW_FOLDED see
+ *                aes_plan_fold_row_constants)
  * Other arguments as aes_spmm_f32.  The fast path needs Xq 4-byte aligned,
  * F and ldq multiples of 4, Y 16-byte aligned and ldy a multiple of 4;
  * anything else runs the element-wise kernel.
@@ -241,6 +245,32 @@ int aes_spmm_q8(int64_t n_rows, int64_t n_cols, int32_t W,
                 int32_t scheme, int32_t granularity,
                 const float *scale, const float *zero,
                 float *Y, int64_t ldy, void *stream);
+
+/*
+ * Folds per-node (AES_Q_PER_ROW) dequantisation constants into a plan, for a
+ * plan that multiplies the same quantised feature matrix more than once.  With
+ * per-node scales aes_spmm_q8 gathers scale[s_col[k]] for every slot, and that
+ * 4-byte gather costs a whole 128-byte memory line, as much as a 128-feature
+ * row of codes.  After
+ *     s_val_folded[k] = s_val[k] * scale[s_col[k]]
+ *     row_bias[r]     = sum over the slots k of row r of s_val[k] * zero[s_col[k]]
+ * (the second only for AES_Q_AFFINE_FLOOR_U8), calling aes_spmm_q8 with
+ * s_val = s_val_folded, granularity = AES_Q_PER_ROW_FOLDED, scale ignored (may be
+ * NULL) and zero = row_bias (NULL for the symmetric scheme) computes the same
+ * Y = sum_k s_val[k] * (q * scale + zero) without touching scale or zero again.
+ *
+ *   s_rowptr/s_col/s_val [dev]  the plan; n_rows rows
+ *   scale, zero [dev]           per-node constants (n_cols entries); zero may be
+ *                               NULL for AES_Q_SYMMETRIC_RNE_I8
+ *   s_val_folded [dev]          out, as many floats as the plan has slots; may
+ *                               alias s_val
+ *   row_bias     [dev]          out, n_rows floats; required for the affine
+ *                               scheme, ignored (may be NULL) otherwise
+ */
+int aes_plan_fold_row_constants(int64_t n_rows,
+                                const int64_t *s_rowptr, const int32_t *s_col, const float *s_val,
+                                int32_t scheme, const float *scale, const float *zero,
+                                float *s_val_folded, float *row_bias, void *stream);
 
 /* ------------------------------------------------------------------------- */
 /* Algorithm 1 as one kernel: sample each row on the fly, then multiply        */

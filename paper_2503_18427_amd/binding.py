@@ -10,7 +10,7 @@ import torch
 from . import build as _build
 
 AES_OK, AES_ERR_INVALID_ARG, AES_ERR_UNSUPPORTED, AES_ERR_WORKSPACE, AES_ERR_HIP = 0, -1, -2, -3, -4
-AES_Q_PER_TENSOR, AES_Q_PER_COLUMN, AES_Q_PER_ROW = 0, 1, 2
+AES_Q_PER_TENSOR, AES_Q_PER_COLUMN, AES_Q_PER_ROW, AES_Q_PER_ROW_FOLDED = 0, 1, 2, 3
 AES_Q_AFFINE_FLOOR_U8, AES_Q_SYMMETRIC_RNE_I8 = 0, 1
 AES_STRATEGY_ADAPTIVE, AES_STRATEGY_AFS, AES_STRATEGY_SFS = 0, 1, 2
 
@@ -30,6 +30,7 @@ SIGNATURES = {
     "aes_spmm_f32": (ctypes.c_int, [_i64, _i64, _i32, _vp, _vp, _vp, _vp, _vp, _i64, _i32, _vp, _i64, _vp]),
     "aes_quantize_workspace_bytes": (_sz, [_i64, _i32, _i32]),
     "aes_quantize_features": (ctypes.c_int, [_i64, _i32, _vp, _i64, _i32, _i32, _vp, _i64, _vp, _vp, _vp, _sz, _vp]),
+    "aes_plan_fold_row_constants": (ctypes.c_int, [_i64, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp]),
     "aes_gcn_layer_f32": (ctypes.c_int, [_i64, _i64, _i32, _vp, _vp, _vp, _vp, _i64, _i32, _vp, _i64, _i32, _vp, _i64,
                                          _vp]),
     "aes_dequantize_features": (ctypes.c_int, [_i64, _i32, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _i64, _vp]),
@@ -205,14 +206,19 @@ def aes_spmm_q8(plan: Plan, Xq, scheme: int, granularity: int, scale, zero=None,
     if not isinstance(Xq, torch.Tensor) or Xq.dtype not in (torch.int8, torch.uint8):
         raise TypeError("Xq: int8 / uint8 tensor required")
     Xq = _dev(Xq, Xq.dtype, "Xq", 2)
-    scale = _dev(scale, torch.float32, "scale")
+    if scale is not None:
+        scale = _dev(scale, torch.float32, "scale")
     if zero is not None:
         zero = _dev(zero, torch.float32, "zero")
     F = Xq.shape[1]
     if Xq.shape[0] != plan.n_cols:
         raise ValueError("Xq must have n_cols rows")
     groups = {AES_Q_PER_TENSOR: 1, AES_Q_PER_COLUMN: F, AES_Q_PER_ROW: plan.n_cols}.get(granularity)
-    if groups is not None and (scale.numel() < groups or (zero is not None and zero.numel() < groups)):
+    if granularity == AES_Q_PER_ROW_FOLDED:
+        if zero is not None and zero.numel() < plan.n_rows:
+            raise ValueError("zero must hold the n_rows row biases for folded constants")
+    elif groups is not None and (scale is None or scale.numel() < groups
+                                 or (zero is not None and zero.numel() < groups)):
         raise ValueError("scale / zero too short for this granularity")
     if Y is None:
         Y = torch.empty((plan.n_rows, F), dtype=torch.float32, device=Xq.device)
@@ -320,3 +326,23 @@ def aes_gcn_layer_f32(plan: Plan, X, Theta, H=None, *, stream=None):
                                        _ptr(plan.s_val), _ptr(X), _ld(X), F, _ptr(Theta), _ld(Theta), Fo, _ptr(H),
                                        _ld(H), _stream(stream)))
     return H
+
+
+def aes_plan_fold_row_constants(plan: Plan, scheme: int, scale, zero=None, *, s_val_folded=None, row_bias=None,
+                                stream=None):
+    """Fold per-node dequantisation constants into a plan.  Returns (folded plan, row_bias or None);
+    use them with aes_spmm_q8(..., granularity=AES_Q_PER_ROW_FOLDED, scale=None, zero=row_bias)."""
+    scale = _dev(scale, torch.float32, "scale")
+    if zero is not None:
+        zero = _dev(zero, torch.float32, "zero")
+    if scale.numel() < plan.n_cols or (zero is not None and zero.numel() < plan.n_cols):
+        raise ValueError("scale / zero must have one entry per column of the plan")
+    if s_val_folded is None:
+        s_val_folded = torch.empty_like(plan.s_val)
+    affine = scheme == AES_Q_AFFINE_FLOOR_U8
+    if affine and row_bias is None:
+        row_bias = torch.empty(plan.n_rows, dtype=torch.float32, device=plan.s_val.device)
+    _check(library().aes_plan_fold_row_constants(plan.n_rows, _ptr(plan.s_rowptr), _ptr(plan.s_col), _ptr(plan.s_val),
+                                                 int(scheme), _ptr(scale), _ptr(zero), _ptr(s_val_folded),
+                                                 _ptr(row_bias) if affine else None, _stream(stream)))
+    return plan._replace(s_val=s_val_folded), (row_bias if affine else None)

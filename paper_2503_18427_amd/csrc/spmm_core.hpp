@@ -227,7 +227,7 @@ __device__ __forceinline__ void accumulate_tiles(const SlotSource &src, const Ro
 // `side` must already be summed over the lanes of the group.
 template <typename Feat, int QMODE, bool QUANT, typename AccT>
 __device__ __forceinline__ void finish_chunk(const AccT (&acc_in)[Feat::VEC], AccT side_in, AccT vsum, bool lane_on,
-                                             int32_t f, const QParams &qp, float *__restrict__ y)
+                                             int32_t f, const QParams &qp, int64_t r, float *__restrict__ y)
 {
     constexpr int VEC = Feat::VEC;
     float acc[VEC];
@@ -247,6 +247,8 @@ __device__ __forceinline__ void finish_chunk(const AccT (&acc_in)[Feat::VEC], Ac
         for (int i = 0; i < VEC; ++i) {
             if (QMODE == kQRowScale) {
                 if (qp.affine) acc[i] += side;
+            } else if (qp.granularity == AES_Q_PER_ROW_FOLDED) {
+                if (qp.zero) acc[i] += qp.zero[r];   // constants live in the plan's values; zero = row bias
             } else {
                 const int g = qp.granularity == AES_Q_PER_COLUMN ? f + i : 0;
                 acc[i] *= qp.scale[g];

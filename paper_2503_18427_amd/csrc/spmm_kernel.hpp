@@ -80,7 +80,7 @@ spmm_rows_kernel(int64_t n_rows, SlotSource src, const int32_t *__restrict__ row
             accumulate_tiles<LPR, UNROLL, Feat, QMODE, QUANT, FUSED, float>(src, ri, my_stage, lane, lane_on, X, ldx, f,
                                                                             qp, 0, 1, acc, side, vsum);
             if (QUANT && qp.affine) side = group_sum<LPR, float>(side);
-            finish_chunk<Feat, QMODE, QUANT, float>(acc, side, vsum, lane_on, f, qp, Y + r * ldy + f);
+            finish_chunk<Feat, QMODE, QUANT, float>(acc, side, vsum, lane_on, f, qp, r, Y + r * ldy + f);
         }
     }
 
@@ -120,7 +120,7 @@ spmm_rows_kernel(int64_t n_rows, SlotSource src, const int32_t *__restrict__ row
                         side += sh_part[g][lane][VEC];
                         vsum += sh_part[g][lane][VEC + 1];
                     }
-                    finish_chunk<Feat, QMODE, QUANT, double>(acc, side, vsum, lane_on, f, qp, Y + lr * ldy + f);
+                    finish_chunk<Feat, QMODE, QUANT, double>(acc, side, vsum, lane_on, f, qp, lr, Y + lr * ldy + f);
                 }
                 __syncthreads();
             }

@@ -24,14 +24,24 @@ int run_q8(const char *what, int64_t n_rows, const SlotSource &src, const int32_
 {
     if (scheme != AES_Q_AFFINE_FLOOR_U8 && scheme != AES_Q_SYMMETRIC_RNE_I8)
         return aes::fail(AES_ERR_INVALID_ARG, "%s: unknown scheme %d", what, (int)scheme);
-    if (granularity < AES_Q_PER_TENSOR || granularity > AES_Q_PER_ROW)
+    if (granularity < AES_Q_PER_TENSOR || granularity > AES_Q_PER_ROW_FOLDED)
         return aes::fail(AES_ERR_INVALID_ARG, "%s: unknown granularity %d", what, (int)granularity);
-    if (scale == nullptr) return aes::fail(AES_ERR_INVALID_ARG, "%s: scale is NULL", what);
+    const bool folded = granularity == AES_Q_PER_ROW_FOLDED;
+    if (FUSED && folded)
+        return aes::fail(AES_ERR_INVALID_ARG, "%s: folded constants need a materialised plan", what);
+    if (!folded && scale == nullptr) return aes::fail(AES_ERR_INVALID_ARG, "%s: scale is NULL", what);
     const bool affine = scheme == AES_Q_AFFINE_FLOOR_U8;
-    if (affine && zero == nullptr) return aes::fail(AES_ERR_INVALID_ARG, "%s: zero is NULL for the affine scheme", what);
+    if (affine && zero == nullptr)
+        return aes::fail(AES_ERR_INVALID_ARG, "%s: zero (the row bias, for folded constants) is NULL for the affine scheme", what);
     if (n_rows == 0) return AES_OK;
     const bool fast = aes::aligned(Y, 16) && ldy % 4 == 0 && aes::aligned(Xq, 4) && F % 4 == 0 && ldq % 4 == 0;
-    QParams qp = {scale, zero, granularity, affine ? 1 : 0};
+    // folded: the kernel only adds zero[r] (the row bias) at the end; the affine flag of QParams,
+    // which drives the per-slot zero-point sums, stays off, the unsigned decoding is in the loader
+    QParams qp = {scale, folded && !affine ? nullptr : zero, granularity, (affine && !folded) ? 1 : 0};
+    if (folded) {
+        if (affine) return dispatch_q8<false, kQNone, FUSED>(fast, n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
+        return dispatch_q8<true, kQNone, FUSED>(fast, n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
+    }
     const bool per_row = granularity == AES_Q_PER_ROW;
     if (affine) {
         if (per_row) return dispatch_q8<false, kQRowScale, FUSED>(fast, n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
@@ -41,7 +51,52 @@ int run_q8(const char *what, int64_t n_rows, const SlotSource &src, const int32_
     return dispatch_q8<true, kQNone, FUSED>(fast, n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
 }
 
+// One group of 16 lanes per row: s_val_folded = s_val * scale[col], row_bias = sum s_val * zero[col].
+__global__ void __launch_bounds__(kBlock)
+fold_row_constants_kernel(int64_t n_rows, const int64_t *__restrict__ s_rowptr, const int32_t *__restrict__ s_col,
+                          const float *s_val, const float *__restrict__ scale, const float *__restrict__ zero,
+                          float *s_val_folded, float *__restrict__ row_bias)
+{
+    constexpr int kLanes = 16;
+    const int lane = threadIdx.x % kLanes;
+    const int64_t r = static_cast<int64_t>(blockIdx.x) * (kBlock / kLanes) + threadIdx.x / kLanes;
+    if (r >= n_rows) return;
+    const int64_t k_end = s_rowptr[r + 1];
+    float bias = 0.0f;
+    for (int64_t k = s_rowptr[r] + lane; k < k_end; k += kLanes) {
+        const int32_t c = s_col[k];
+        const float v = s_val[k];
+        if (zero) bias = __builtin_fmaf(v, zero[c], bias);
+        s_val_folded[k] = v * scale[c];
+    }
+    if (row_bias) {
+        bias = group_sum<kLanes, float>(bias);
+        if (lane == 0) row_bias[r] = bias;
+    }
+}
+
 }  // namespace
+
+extern "C" int aes_plan_fold_row_constants(int64_t n_rows,
+                                           const int64_t *s_rowptr, const int32_t *s_col, const float *s_val,
+                                           int32_t scheme, const float *scale, const float *zero,
+                                           float *s_val_folded, float *row_bias, void *stream)
+{
+    const char *what = "aes_plan_fold_row_constants";
+    if (n_rows < 0) return aes::fail(AES_ERR_INVALID_ARG, "%s: n_rows=%lld is negative", what, (long long)n_rows);
+    if (scheme != AES_Q_AFFINE_FLOOR_U8 && scheme != AES_Q_SYMMETRIC_RNE_I8)
+        return aes::fail(AES_ERR_INVALID_ARG, "%s: unknown scheme %d", what, (int)scheme);
+    const bool affine = scheme == AES_Q_AFFINE_FLOOR_U8;
+    if (s_rowptr == nullptr || scale == nullptr) return aes::fail(AES_ERR_INVALID_ARG, "%s: s_rowptr / scale is NULL", what);
+    if (affine && (zero == nullptr || row_bias == nullptr))
+        return aes::fail(AES_ERR_INVALID_ARG, "%s: zero / row_bias is NULL for the affine scheme", what);
+    if (n_rows == 0) return AES_OK;
+    const int64_t grid = aes::ceil_div(n_rows, kBlock / 16);
+    if (grid > INT32_MAX) return aes::fail(AES_ERR_UNSUPPORTED, "%s: n_rows=%lld too large", what, (long long)n_rows);
+    fold_row_constants_kernel<<<dim3(static_cast<unsigned>(grid)), dim3(kBlock), 0, static_cast<hipStream_t>(stream)>>>(
+        n_rows, s_rowptr, s_col, s_val, scale, affine ? zero : nullptr, s_val_folded, affine ? row_bias : nullptr);
+    return aes::check_launch(what);
+}
 
 extern "C" int aes_spmm_q8(int64_t n_rows, int64_t n_cols, int32_t W,
                            const int64_t *s_rowptr, const int32_t *s_col, const float *s_val,

@@ -6,6 +6,7 @@
     python -m paper_2503_18427_amd.studies layer       [workload]
     python -m paper_2503_18427_amd.studies graph       [workload]
     python -m paper_2503_18427_amd.studies sampling-rate [workload]
+    python -m paper_2503_18427_amd.studies folded      [workload]
 
 They reproduce the *shape* of the paper's evaluation on the synthetic workloads
 (the paper's datasets are not available): kernel time and error against the
@@ -209,6 +210,35 @@ def layer(name: str) -> None:
     print()
 
 
+def folded(name: str) -> None:
+    """8-bit SpMM with per-node scales: gathered per slot vs folded into the plan once."""
+    d = configs.make(name, "cuda")
+    w = d["workload"]
+    n, F, X = d["n"], d["F"], d["X"]
+    W = w.widths[0]
+    plan = aes.aes_sample_build(d["rowptr"], d["colidx"], d["val"], n, W)
+    S = int(plan.s_rowptr[-1])
+    Y = torch.empty((n, F), device="cuda")
+    t32 = _time_ms(lambda: aes.aes_spmm_f32(plan, X, Y), iters=5)
+    print(f"### per-node scales gathered vs folded, `{name}` (n = {n}, S = {S}, F = {F}, W = {W}; ms; fp32 SpMM {t32:.3f})\n")
+    print("| scheme | aes_spmm_q8 per row | fold pass | aes_spmm_q8 folded | speedup of the multiply | vs fp32 SpMM | "
+          "max abs difference |")
+    print("|---|---|---|---|---|---|---|")
+    for scheme, label in ((aes.AES_Q_SYMMETRIC_RNE_I8, "symmetric int8"), (aes.AES_Q_AFFINE_FLOOR_U8, "affine uint8")):
+        q = aes.aes_quantize_features(X, scheme, aes.AES_Q_PER_ROW)
+        t_row = _time_ms(lambda: aes.aes_spmm_q8(plan, q[0], scheme, aes.AES_Q_PER_ROW, q[1], q[2], Y), iters=5)
+        big = n * F > 2 ** 31                      # no second copy of Y for the very large workloads
+        Y0 = None if big else Y.clone()
+        fplan, bias = aes.aes_plan_fold_row_constants(plan, scheme, q[1], q[2])
+        t_fold = _time_ms(lambda: aes.aes_plan_fold_row_constants(plan, scheme, q[1], q[2], s_val_folded=fplan.s_val,
+                                                                  row_bias=bias), iters=5)
+        t_f = _time_ms(lambda: aes.aes_spmm_q8(fplan, q[0], scheme, aes.AES_Q_PER_ROW_FOLDED, None, bias, Y), iters=5)
+        diff = "-" if big else f"{float((Y - Y0).abs().max()):.1e}"
+        print(f"| {label} | {t_row:.3f} | {t_fold:.3f} | {t_f:.3f} | {t_row / t_f:.2f}x | {t32 / t_f:.2f}x | {diff} |")
+        del q, fplan, Y0
+    print()
+
+
 def sampling_rate(name: str) -> None:
     """Distribution of the per-row sampling rate slots / row_nnz (the quantity of the paper's Fig. 5)."""
     d = configs.make(name, "cuda")
@@ -263,14 +293,14 @@ def graph(name: str) -> None:
 
 
 def main(argv) -> int:
-    if len(argv) < 2 or argv[1] not in ("width-sweep", "strategies", "loading", "layer", "graph", "sampling-rate"):
+    if len(argv) < 2 or argv[1] not in ("width-sweep", "strategies", "loading", "layer", "graph", "sampling-rate", "folded"):
         print(__doc__)
         return 2
     assert torch.cuda.is_available(), "the studies need a GPU"
     name = argv[2] if len(argv) > 2 else {"width-sweep": "rmat20", "strategies": "reddit_like",
-                                          "loading": "products_like", "layer": "products_like", "graph": "arxiv_like", "sampling-rate": "reddit_like"}[argv[1]]
+                                          "loading": "products_like", "layer": "products_like", "graph": "arxiv_like", "sampling-rate": "reddit_like", "folded": "products_like"}[argv[1]]
     {"width-sweep": width_sweep, "strategies": strategies, "loading": loading, "layer": layer,
-     "graph": graph, "sampling-rate": sampling_rate}[argv[1]](name)
+     "graph": graph, "sampling-rate": sampling_rate, "folded": folded}[argv[1]](name)
     return 0
 
 

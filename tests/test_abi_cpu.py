@@ -111,6 +111,17 @@ def test_argument_errors_are_host_side(lib):
     assert dq(4, 8, None, 8, 1, 1, fake, None, fake, 8, None) == -1
     assert dq(0, 8, None, 8, 1, 1, fake, None, None, 8, None) == 0
 
+    fold = lib.aes_plan_fold_row_constants
+    assert fold(-1, fake, fake, fake, 1, fake, None, fake, None, None) == -1
+    assert fold(4, fake, fake, fake, 7, fake, None, fake, None, None) == -1
+    assert fold(4, None, fake, fake, 1, fake, None, fake, None, None) == -1
+    assert fold(4, fake, fake, fake, 1, None, None, fake, None, None) == -1
+    assert fold(4, fake, fake, fake, 0, fake, None, fake, fake, None) == -1      # affine needs zero
+    assert fold(4, fake, fake, fake, 0, fake, fake, fake, None, None) == -1      # affine needs row_bias
+    assert fold(0, fake, fake, fake, 1, fake, None, fake, None, None) == 0
+    assert lib.aes_spmm_fused_q8(4, 4, fake, fake, fake, 16, 0, 0, fake, 8, 8, 1, 3, fake, None, fake, 8, None) == -1
+    assert lib.aes_quantize_features(4, 8, fake, 8, 1, 3, fake, 8, fake, fake, fake, 1 << 20, None) == -1
+
     gl = lib.aes_gcn_layer_f32
     assert gl(-1, 4, 0, fake, fake, fake, fake, 8, 8, fake, 8, 8, fake, 8, None) == -1
     assert gl(4, 4, 0, fake, fake, fake, fake, 8, 8, fake, 4, 8, fake, 8, None) == -1      # ldt < Fo

@@ -375,3 +375,42 @@ def test_two_streams_run_different_entry_points_concurrently(G):
     s2.synchronize()
     for p1, y1, q2, y2 in outs:
         assert torch.equal(y1, Ya) and torch.equal(y2, Yqa) and torch.equal(q2[0], qa[0])
+
+
+@pytest.mark.parametrize("scheme", [SYM, AFF])
+@pytest.mark.parametrize("F", [128, 50])
+def test_folded_row_constants(G, scheme, F):
+    """Per-node dequantisation constants folded into the plan's values once: the
+    8-bit product must still match the oracle's dequantise-then-multiply (and the
+    unfolded kernel closely), on short, long and empty rows."""
+    import paper_2503_18427_amd as aes
+    rng = np.random.default_rng(F + scheme)
+    deg = np.concatenate([rng.integers(0, 200, size=500), [0, 5000, 2049, 1, 64]])
+    n_cols = 800
+    rowptr, col, val = random_csr(deg.size, n_cols, deg, rng)
+    X = (rng.standard_normal((n_cols, F)) * rng.uniform(0.1, 10.0, size=(n_cols, 1))).astype(np.float32)
+    qd, qr = G.check_quantize(X, scheme, ROW)
+    for W in (64, 0):
+        plan, ref = G.check_plan(rowptr, col, val, n_cols, W, 0)
+        Y0, _, _ = G.check_q8(plan, ref, qd, qr, scheme, ROW, use_perm=False)
+        folded, bias = aes.aes_plan_fold_row_constants(plan, scheme, qd[1], qd[2])
+        assert (bias is None) == (scheme == SYM)
+        Yf = aes.aes_spmm_q8(folded, qd[0], scheme, aes.AES_Q_PER_ROW_FOLDED, None, bias, use_perm=False)
+        torch.cuda.synchronize()
+        # same check as the unfolded path: against the oracle's own dequantised product
+        import oracle as orc
+        from helpers import rel_err
+        Yref, Yabs = orc.spmm_q8(ref[0], ref[1], ref[2], qr[0], scheme, ROW, qr[1], qr[2], want_abs=True)
+        if scheme == AFF:
+            mag = (np.abs(qr[0].astype(np.float32) * qr[1][:, None]) + np.abs(qr[2][:, None])).astype(np.float32)
+            Yabs = orc.spmm_plan(ref[0], ref[1], np.abs(ref[2]), np.ascontiguousarray(mag))
+        comp, glob = rel_err(Yf.cpu().numpy(), Yref, Yabs)
+        assert comp <= G.Q8_TOL and glob <= G.Q8_TOL, (comp, glob)
+        assert float((Yf - Y0).abs().max()) <= 1e-3 * max(1.0, float(Y0.abs().max()))
+        # in place: the folded values may overwrite the plan's own
+        S = int(plan.s_rowptr[-1])
+        keep = plan.s_val.clone()
+        aes.aes_plan_fold_row_constants(plan, scheme, qd[1], qd[2], s_val_folded=plan.s_val, row_bias=bias)
+        torch.cuda.synchronize()
+        assert torch.equal(plan.s_val[:S], folded.s_val[:S])
+        plan.s_val.copy_(keep)

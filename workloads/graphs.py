@@ -81,14 +81,22 @@ def chung_lu(weights: torch.Tensor, seed: int, self_loops: bool, relabel: bool):
     device = weights.device
     n = weights.numel()
     m = int(round(float(weights.sum()) / 2.0))
-    cdf = torch.cumsum(weights, 0)
-    cdf = cdf / cdf[-1]
+    # Integer cumulative weights: a floating-point prefix sum on the GPU is not reproducible
+    # from run to run (its partial sums combine in timing-dependent order); an int64 one is exact.
+    wq = torch.clamp((weights * (2.0 ** 40 / float(weights.max()))).to(torch.int64), min=1)
+    cdf = torch.cumsum(wq, 0)
+    total = int(cdf[-1])
     chunks = []
     step = 1 << 24
+
+    def draw(stream, k, s):
+        u = (rng.uniform(seed, stream, k, device, start=s) * float(total)).to(torch.int64).clamp_(max=total - 1)
+        return torch.searchsorted(cdf, u, right=True).clamp_(max=n - 1)
+
     for s in range(0, m, step):
         k = min(step, m - s)
-        src = torch.searchsorted(cdf, rng.uniform(seed, 1, k, device, start=s)).clamp_(max=n - 1)
-        dst = torch.searchsorted(cdf, rng.uniform(seed, 2, k, device, start=s)).clamp_(max=n - 1)
+        src = draw(1, k, s)
+        dst = draw(2, k, s)
         chunks.append(src * n + dst)
         chunks.append(dst * n + src)
     keys = torch.cat(chunks) if chunks else torch.empty(0, dtype=torch.int64, device=device)
