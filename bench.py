@@ -258,15 +258,16 @@ def cpu_baseline(d, plan, Y, Yq, qbuf, W, scheme, gran, n_rows_sample, leg_bytes
     Yref, Yabs = orc.spmm_plan(ref[0], ref[1], ref[2], X, rows=rows, want_abs=True)
     t_f32 = time.perf_counter() - t
 
-    nq = min(n, n_rows_sample)
+    # The oracle quantises X itself; nothing it consumes comes from the GPU path.
+    nq = n
     t = time.perf_counter()
-    orc.quantize(X[:nq], scheme, gran)
+    oq, osc, ozr = orc.quantize(X, scheme, gran)
     t_quant = time.perf_counter() - t
+    codes_ok = bool(np.array_equal(qbuf[0].cpu().numpy(), oq)
+                    and np.array_equal(qbuf[1].cpu().numpy().view(np.uint32), osc.view(np.uint32)))
 
-    Xq_h = qbuf[0].cpu().numpy()
-    sc_h, zr_h = qbuf[1].cpu().numpy(), qbuf[2].cpu().numpy()
     t = time.perf_counter()
-    Yqref, Yqabs = orc.spmm_q8(ref[0], ref[1], ref[2], Xq_h, scheme, gran, sc_h, zr_h, rows=rows, want_abs=True)
+    Yqref, Yqabs = orc.spmm_q8(ref[0], ref[1], ref[2], oq, scheme, gran, osc, ozr, rows=rows, want_abs=True)
     t_q8 = time.perf_counter() - t
 
     groups_q = {0: 1, 1: F, 2: nq}[gran]
@@ -293,11 +294,12 @@ def cpu_baseline(d, plan, Y, Yq, qbuf, W, scheme, gran, n_rows_sample, leg_bytes
         "kind": "oracle",
         "sample": f"sample build on all rows; fp32 and int8 SpMM on {n_rows_sample} of {n} rows "
                   f"({slots_rows} slots; the int8 leg dequantises all of X first, as the oracle defines it); "
-                  f"quantise on the first {nq} rows; each leg's rate scaled to the full step's bytes",
+                  f"quantise on all {nq} feature rows; each leg's rate scaled to the full step's bytes",
         "seconds": {"sample_build": t_build, "spmm_f32": t_f32, "quantize": t_quant, "spmm_q8": t_q8},
         "leg_GBps": {k: v / 1e9 for k, v in rate.items()},
     }
     errs = {"fp32_vs_oracle": e32, "int8_vs_oracle_dequantised": e8, "plan_bit_exact": plan_ok,
+            "int8_codes_and_scales_bit_exact": codes_ok,
             "rows_checked": n_rows_sample}
     return base, errs
 
