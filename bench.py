@@ -270,6 +270,17 @@ def cpu_baseline(d, plan, Y, Yq, qbuf, W, scheme, gran, n_rows_sample, leg_bytes
     Yqref, Yqabs = orc.spmm_q8(ref[0], ref[1], ref[2], oq, scheme, gran, osc, ozr, rows=rows, want_abs=True)
     t_q8 = time.perf_counter() - t
 
+    # one host core, on a bounded row sample (the full workload would take ~16 x longer)
+    n_st = min(100_000, rows.size)
+    rows_st = rows[:: max(1, rows.size // n_st)][:n_st]
+    slots_st = int((ref[0][rows_st + 1] - ref[0][rows_st]).sum())
+    threads = orc.num_threads()
+    orc.set_num_threads(1)
+    t = time.perf_counter()
+    orc.spmm_plan(ref[0], ref[1], ref[2], X, rows=rows_st)
+    t_st = time.perf_counter() - t
+    orc.set_num_threads(threads)
+
     groups_q = {0: 1, 1: F, 2: nq}[gran]
     rate = {
         "sample_build": leg_bytes["sample_build"] / t_build,
@@ -297,6 +308,8 @@ def cpu_baseline(d, plan, Y, Yq, qbuf, W, scheme, gran, n_rows_sample, leg_bytes
                   f"quantise on all {nq} feature rows; each leg's rate scaled to the full step's bytes",
         "seconds": {"sample_build": t_build, "spmm_f32": t_f32, "quantize": t_quant, "spmm_q8": t_q8},
         "leg_GBps": {k: v / 1e9 for k, v in rate.items()},
+        "single_thread": {"spmm_f32_GBps": algorithmic_bytes(rows_st.size, slots_st, F, 4, False) / t_st / 1e9,
+                          "rows": int(rows_st.size), "seconds": t_st},
     }
     errs = {"fp32_vs_oracle": e32, "int8_vs_oracle_dequantised": e8, "plan_bit_exact": plan_ok,
             "int8_codes_and_scales_bit_exact": codes_ok,
