@@ -321,6 +321,19 @@ int aes_gcn_layer_f32(int64_t n_rows, int64_t n_cols, int32_t W,
                       const float *Theta, int64_t ldt, int32_t Fo,
                       float *H, int64_t ldh, void *stream);
 
+/*
+ * The same layer on 8-bit features: H = (A_s x_hat) Theta with the dequantisation of Sec. 2.3
+ * Eq. 2 fused into the gather exactly as in aes_spmm_q8 (same scheme / granularity / scale /
+ * zero arguments, AES_Q_PER_ROW_FOLDED included), the aggregated tile multiplied by Theta on
+ * the matrix cores.  Xq needs 4-byte aligned rows with F and ldq multiples of 4, F <= 256.
+ */
+int aes_gcn_layer_q8(int64_t n_rows, int64_t n_cols, int32_t W,
+                     const int64_t *s_rowptr, const int32_t *s_col, const float *s_val,
+                     const int8_t *Xq, int64_t ldq, int32_t F,
+                     int32_t scheme, int32_t granularity, const float *scale, const float *zero,
+                     const float *Theta, int64_t ldt, int32_t Fo,
+                     float *H, int64_t ldh, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -20,6 +20,7 @@ from .binding import (  # noqa: F401
     Plan,
     aes_dequantize_features,
     aes_gcn_layer_f32,
+    aes_gcn_layer_q8,
     aes_last_error,
     aes_plan_fold_row_constants,
     aes_quantize_features,

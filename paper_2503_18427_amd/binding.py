@@ -33,6 +33,8 @@ SIGNATURES = {
     "aes_plan_fold_row_constants": (ctypes.c_int, [_i64, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp]),
     "aes_gcn_layer_f32": (ctypes.c_int, [_i64, _i64, _i32, _vp, _vp, _vp, _vp, _i64, _i32, _vp, _i64, _i32, _vp, _i64,
                                          _vp]),
+    "aes_gcn_layer_q8": (ctypes.c_int, [_i64, _i64, _i32, _vp, _vp, _vp, _vp, _i64, _i32, _i32, _i32, _vp, _vp, _vp,
+                                        _i64, _i32, _vp, _i64, _vp]),
     "aes_dequantize_features": (ctypes.c_int, [_i64, _i32, _vp, _i64, _i32, _i32, _vp, _vp, _vp, _i64, _vp]),
     "aes_spmm_q8": (ctypes.c_int, [_i64, _i64, _i32, _vp, _vp, _vp, _vp, _vp, _i64, _i32, _i32, _i32, _vp, _vp, _vp,
                                    _i64, _vp]),
@@ -346,3 +348,31 @@ def aes_plan_fold_row_constants(plan: Plan, scheme: int, scale, zero=None, *, s_
                                                  int(scheme), _ptr(scale), _ptr(zero), _ptr(s_val_folded),
                                                  _ptr(row_bias) if affine else None, _stream(stream)))
     return plan._replace(s_val=s_val_folded), (row_bias if affine else None)
+
+
+def aes_gcn_layer_q8(plan: Plan, Xq, scheme: int, granularity: int, scale, zero, Theta, H=None, *, stream=None):
+    """H = (A_s x_hat) Theta with 8-bit features dequantised inside the gather."""
+    if not isinstance(Xq, torch.Tensor) or Xq.dtype not in (torch.int8, torch.uint8):
+        raise TypeError("Xq: int8 / uint8 tensor required")
+    Xq = _dev(Xq, Xq.dtype, "Xq", 2)
+    Theta = _dev(Theta, torch.float32, "Theta", 2)
+    if scale is not None:
+        scale = _dev(scale, torch.float32, "scale")
+    if zero is not None:
+        zero = _dev(zero, torch.float32, "zero")
+    F, Fo = Xq.shape[1], Theta.shape[1]
+    if Xq.shape[0] != plan.n_cols or Theta.shape[0] != F:
+        raise ValueError("Xq must be n_cols x F and Theta F x Fo")
+    groups = {AES_Q_PER_TENSOR: 1, AES_Q_PER_COLUMN: F, AES_Q_PER_ROW: plan.n_cols}.get(granularity)
+    if groups is not None and (scale is None or scale.numel() < groups or (zero is not None and zero.numel() < groups)):
+        raise ValueError("scale / zero too short for this granularity")
+    if H is None:
+        H = torch.empty((plan.n_rows, Fo), dtype=torch.float32, device=Xq.device)
+    H = _dev(H, torch.float32, "H", 2)
+    if H.shape[0] != plan.n_rows or H.shape[1] != Fo:
+        raise ValueError("H has the wrong shape")
+    _check(library().aes_gcn_layer_q8(plan.n_rows, plan.n_cols, plan.W, _ptr(plan.s_rowptr), _ptr(plan.s_col),
+                                      _ptr(plan.s_val), _ptr(Xq), _ld(Xq), F, int(scheme), int(granularity),
+                                      _ptr(scale), _ptr(zero), _ptr(Theta), _ld(Theta), Fo, _ptr(H), _ld(H),
+                                      _stream(stream)))
+    return H

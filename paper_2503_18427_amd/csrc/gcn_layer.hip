@@ -1,6 +1,5 @@
-// aes_gcn_layer_f32: aggregation and combination of one GNN layer in one kernel,
-//     H = (A_s X) Theta
-// on gfx950.
+// aes_gcn_layer_f32 / aes_gcn_layer_q8: aggregation and combination of one GNN layer in one
+// kernel, H = (A_s X) Theta (X float32, or 8-bit codes dequantised inside the gather), on gfx950.
 //
 // Method: Sec. 2.1 of the AES-SpMM paper splits a layer into the aggregation
 // phase (the sampled SpMM of Sec. 3.2 Algorithm 1) and the combination phase (a
@@ -22,10 +21,14 @@ constexpr int kMaxFeatures = 256;    // one chunk of four features per lane, at 
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-template <int LPR>
-__global__ void __launch_bounds__(kBlock)
-gcn_layer_kernel(int64_t n_rows, SlotSource src, const float *__restrict__ X, int64_t ldx, int32_t F,
-                 const float *__restrict__ Theta, int64_t ldt, int32_t Fo, float *__restrict__ H, int64_t ldh)
+// Feat / QMODE / QUANT as in the SpMM kernel: float32 features, or 8-bit codes dequantised in the gather.
+// At least four waves per SIMD: the gather phase needs the occupancy, and the register allocator
+// would otherwise spend the whole file on the unrolled MFMA phase.
+template <int LPR, typename Feat, int QMODE, bool QUANT>
+__global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(4)))
+gcn_layer_kernel(int64_t n_rows, SlotSource src, const typename Feat::elem_t *__restrict__ X, int64_t ldx, int32_t F,
+                 QParams qp, const float *__restrict__ Theta, int64_t ldt, int32_t Fo, float *__restrict__ H,
+                 int64_t ldh)
 {
     constexpr int kGroups = kWave / LPR;
     constexpr int kGroupsPerBlock = kGroups * kWavesPerBlock;
@@ -43,78 +46,162 @@ gcn_layer_kernel(int64_t n_rows, SlotSource src, const float *__restrict__ X, in
     // ---- aggregation: Algorithm 1's accumulation loop, one lane group per row ----
     const int32_t f = lane * 4;
     const bool lane_on = f < F;
-    const QParams no_q = {nullptr, nullptr, 0, 0};
     for (int rr = wave * kGroups + group; rr < kTileRows; rr += kGroupsPerBlock) {
         const int64_t r = row0 + rr;
         float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
         float side = 0.0f, vsum = 0.0f;
         if (r < n_rows) {
             const RowInfo ri = row_info<false>(src, r);
-            accumulate_tiles<LPR, 8, FeatF32<4>, kQNone, false, false, float>(src, ri, stage[wave][group], lane, lane_on, X, ldx,
-                                                                       f, no_q, 0, 1, acc, side, vsum);
+            accumulate_tiles<LPR, 8, Feat, QMODE, QUANT, false, float>(src, ri, stage[wave][group], lane, lane_on, X, ldx, f,
+                                                                       qp, 0, 1, acc, side, vsum);
         }
+        if (QUANT && qp.affine) side = group_sum<LPR, float>(side);
         if (lane_on) {
+            float y[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+            if (r < n_rows) finish_values<Feat, QMODE, QUANT, float>(acc, side, vsum, f, qp, r, y);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) ys[rr * y_stride + f + i] = acc[i];
+            for (int i = 0; i < 4; ++i) ys[rr * y_stride + f + i] = y[i];
         }
     }
-    __syncthreads();
-
     // ---- combination: H_tile (32 x Fo) = ys (32 x F) * Theta (F x Fo) on the matrix cores ----
     // v_mfma_f32_32x32x2_f32: lane l supplies A[l % 32][l / 32] and B[l / 32][l % 32];
     // it receives D[8 * (v / 4) + 4 * (l / 32) + v % 4][l % 32] in result register v.
+    //
+    // A wave owns the 32-column blocks nb = wave, wave + 4, ...  Its Theta operands are held in
+    // registers in chunks of kChunk MFMAs (64 rows of Theta): the first two chunks are requested
+    // BEFORE the workgroup barrier, right after the wave's last gather, so their latency - long,
+    // because the vector memory path is saturated by the gathers of the other workgroups - passes
+    // while the wave waits for the rest of the tile; a chunk's registers are refilled as soon as it
+    // has been consumed.  The gather loop's registers are dead by then, so this costs no occupancy.
+    constexpr int kChunk = 32;
     const int i = wl % 32, h = wl / 32;
-    for (int nb = wave; nb * 32 < Fo; nb += kWavesPerBlock) {
+    const int n_chunks = (F + 2 * kChunk - 1) / (2 * kChunk);
+    float b0[kChunk], b1[kChunk];
+    // Address = wave-uniform row base (scalar registers) + one 32-bit per-lane offset, so the
+    // 32 loads of a chunk share a single address register.
+    auto load_b = [&](int nb, int chunk, float (&b)[kChunk]) {
         const int col = nb * 32 + i;
         const bool col_on = col < Fo;
-        const float *theta_col = Theta + (col_on ? col : 0);
-        floatx16 c;
+        const uint32_t lane_off = static_cast<uint32_t>(h) * static_cast<uint32_t>(ldt) + (col_on ? col : 0);
 #pragma unroll
-        for (int v = 0; v < 16; ++v) c[v] = 0.0f;
-        // Operands are fetched kBatch MFMAs ahead: the loads of the next batch are issued
-        // before the current batch's MFMA chain, so Theta's L2 latency hides behind it.
-        constexpr int kBatch = 8;
-        float a_cur[kBatch], b_cur[kBatch], a_nxt[kBatch], b_nxt[kBatch];
-        auto fetch = [&](int k_base, float (&a)[kBatch], float (&b)[kBatch]) {
+        for (int u = 0; u < kChunk; ++u) {
+            const int k_even = chunk * 2 * kChunk + 2 * u;              // uniform; this lane reads row k_even + h
+            const float *row_base = Theta + static_cast<int64_t>(k_even) * ldt;
+            b[u] = (k_even + h < F && col_on) ? row_base[lane_off] : 0.0f;
+        }
+    };
+    if (wave * 32 < Fo) {
+        load_b(wave, 0, b0);
+        if (n_chunks > 1) load_b(wave, 1, b1);
+    }
+    __syncthreads();
+
+    floatx16 c;
+    auto run_chunk = [&](int chunk, const float (&b)[kChunk]) {
+        constexpr int kBatch = 8;                    // A operands come from LDS, eight reads ahead
+        float a_cur[kBatch], a_nxt[kBatch];
+        auto load_a = [&](int u0, float (&a)[kBatch]) {
 #pragma unroll
             for (int u = 0; u < kBatch; ++u) {
-                const int k = k_base + 2 * u + h;
-                const bool on = k < F;
-                a[u] = on ? ys[i * y_stride + k] : 0.0f;
-                b[u] = (on && col_on) ? theta_col[static_cast<int64_t>(k) * ldt] : 0.0f;
+                const int k = chunk * 2 * kChunk + 2 * (u0 + u) + h;
+                a[u] = k < F ? ys[i * y_stride + k] : 0.0f;
             }
         };
-        fetch(0, a_cur, b_cur);
-        for (int k0 = 0; k0 < F; k0 += 2 * kBatch) {
-            if (k0 + 2 * kBatch < F) fetch(k0 + 2 * kBatch, a_nxt, b_nxt);
+        load_a(0, a_cur);
 #pragma unroll
-            for (int u = 0; u < kBatch; ++u) c = __builtin_amdgcn_mfma_f32_32x32x2f32(a_cur[u], b_cur[u], c, 0, 0, 0);
+        for (int u0 = 0; u0 < kChunk; u0 += kBatch) {
+            if (u0 + kBatch < kChunk) load_a(u0 + kBatch, a_nxt);
+            __builtin_amdgcn_sched_barrier(0);       // keep the read-ahead at one batch: registers
 #pragma unroll
-            for (int u = 0; u < kBatch; ++u) {
-                a_cur[u] = a_nxt[u];
-                b_cur[u] = b_nxt[u];
+            for (int u = 0; u < kBatch; ++u) c = __builtin_amdgcn_mfma_f32_32x32x2f32(a_cur[u], b[u0 + u], c, 0, 0, 0);
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u) a_cur[u] = a_nxt[u];
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    for (int nb = wave; nb * 32 < Fo; nb += kWavesPerBlock) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) c[v] = 0.0f;
+        for (int chunk = 0; chunk < n_chunks; chunk += 2) {
+            run_chunk(chunk, b0);
+            if (chunk + 2 < n_chunks) load_b(nb, chunk + 2, b0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (chunk + 1 < n_chunks) {
+                run_chunk(chunk + 1, b1);
+                if (chunk + 3 < n_chunks) load_b(nb, chunk + 3, b1);
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
-        if (col_on) {
+        const int col = nb * 32 + i;
+        if (col < Fo) {
+            const uint32_t out_off = static_cast<uint32_t>(4 * h) * static_cast<uint32_t>(ldh) + col;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int64_t r = row0 + 8 * (v / 4) + 4 * h + (v % 4);
-                if (r < n_rows) H[r * ldh + col] = c[v];
+                const int64_t r_base = row0 + 8 * (v / 4) + (v % 4);     // uniform; this lane's row is r_base + 4h
+                if (r_base + 4 * h < n_rows) (H + r_base * ldh)[out_off] = c[v];
             }
+        }
+        const int next = nb + kWavesPerBlock;        // a further column block of this wave: its first chunks
+        if (next * 32 < Fo) {
+            load_b(next, 0, b0);
+            if (n_chunks > 1) load_b(next, 1, b1);
         }
     }
 }
 
-template <int LPR>
-int launch_gcn(int64_t n_rows, const SlotSource &src, const float *X, int64_t ldx, int32_t F, const float *Theta,
-               int64_t ldt, int32_t Fo, float *H, int64_t ldh, hipStream_t stream)
+template <int LPR, typename Feat, int QMODE, bool QUANT>
+int launch_gcn(const char *what, int64_t n_rows, const SlotSource &src, const typename Feat::elem_t *X, int64_t ldx,
+               int32_t F, QParams qp, const float *Theta, int64_t ldt, int32_t Fo, float *H, int64_t ldh,
+               hipStream_t stream)
 {
     const int64_t grid = ceil_div(n_rows, kTileRows);
-    if (grid > INT32_MAX) return fail(AES_ERR_UNSUPPORTED, "aes_gcn_layer_f32: n_rows=%lld too large", (long long)n_rows);
+    if (grid > INT32_MAX) return fail(AES_ERR_UNSUPPORTED, "%s: n_rows=%lld too large", what, (long long)n_rows);
     const size_t shmem = static_cast<size_t>(kTileRows) * (F + 1) * sizeof(float);
-    gcn_layer_kernel<LPR><<<dim3(static_cast<unsigned>(grid)), dim3(kBlock), shmem, stream>>>(n_rows, src, X, ldx, F, Theta,
-                                                                                             ldt, Fo, H, ldh);
-    return check_launch("aes_gcn_layer_f32");
+    gcn_layer_kernel<LPR, Feat, QMODE, QUANT><<<dim3(static_cast<unsigned>(grid)), dim3(kBlock), shmem, stream>>>(
+        n_rows, src, X, ldx, F, qp, Theta, ldt, Fo, H, ldh);
+    return check_launch(what);
+}
+
+template <typename Feat, int QMODE, bool QUANT>
+int dispatch_gcn(const char *what, int64_t n_rows, const SlotSource &src, const typename Feat::elem_t *X, int64_t ldx,
+                 int32_t F, QParams qp, const float *Theta, int64_t ldt, int32_t Fo, float *H, int64_t ldh,
+                 hipStream_t stream)
+{
+    int l = pow2_ceil(ceil_div(F, 4));
+    l = l < 8 ? 8 : l;
+    switch (l) {
+        case 8: return launch_gcn<8, Feat, QMODE, QUANT>(what, n_rows, src, X, ldx, F, qp, Theta, ldt, Fo, H, ldh, stream);
+        case 16: return launch_gcn<16, Feat, QMODE, QUANT>(what, n_rows, src, X, ldx, F, qp, Theta, ldt, Fo, H, ldh, stream);
+        case 32: return launch_gcn<32, Feat, QMODE, QUANT>(what, n_rows, src, X, ldx, F, qp, Theta, ldt, Fo, H, ldh, stream);
+        default: return launch_gcn<64, Feat, QMODE, QUANT>(what, n_rows, src, X, ldx, F, qp, Theta, ldt, Fo, H, ldh, stream);
+    }
+}
+
+// Argument checks shared by the float32 and the 8-bit entry point (elem_bytes = bytes per feature).
+int check_layer(const char *what, int64_t n_rows, int64_t n_cols, int32_t W, const int64_t *s_rowptr, const void *X,
+                int64_t ldx, int32_t F, int elem_bytes, const float *Theta, int64_t ldt, int32_t Fo, const float *H,
+                int64_t ldh)
+{
+    if (n_rows < 0 || n_cols < 0)
+        return fail(AES_ERR_INVALID_ARG, "%s: negative size (n_rows=%lld n_cols=%lld)", what, (long long)n_rows,
+                    (long long)n_cols);
+    if (n_cols > INT32_MAX) return fail(AES_ERR_UNSUPPORTED, "%s: n_cols=%lld does not fit int32", what, (long long)n_cols);
+    if (W < 0 || W > AES_MAX_W) return fail(AES_ERR_INVALID_ARG, "%s: W=%d outside 0..%d", what, (int)W, (int)AES_MAX_W);
+    if (F < 1 || Fo < 1 || Fo >= (1 << 24)) return fail(AES_ERR_INVALID_ARG, "%s: F=%d / Fo=%d out of range", what, (int)F, (int)Fo);
+    if (ldx < F || ldt < Fo || ldh < Fo)
+        return fail(AES_ERR_INVALID_ARG, "%s: leading dimension too small (ldx=%lld ldt=%lld ldh=%lld)", what,
+                    (long long)ldx, (long long)ldt, (long long)ldh);
+    if (s_rowptr == nullptr || Theta == nullptr) return fail(AES_ERR_INVALID_ARG, "%s: s_rowptr / Theta is NULL", what);
+    if (n_rows > 0 && H == nullptr) return fail(AES_ERR_INVALID_ARG, "%s: H is NULL", what);
+    if (n_rows > 0 && n_cols > 0 && X == nullptr) return fail(AES_ERR_INVALID_ARG, "%s: X is NULL", what);
+    if (ldt >= (1 << 28) || ldh >= (1 << 28))
+        return fail(AES_ERR_UNSUPPORTED, "%s: ldt / ldh must stay below 2^28 (32-bit lane offsets)", what);
+    if (F > kMaxFeatures || F % 4 != 0 || ldx % 4 != 0 || !aligned(X, 4 * elem_bytes))
+        return fail(AES_ERR_UNSUPPORTED,
+                    "%s: needs F <= %d, F and the feature leading dimension multiples of 4 and aligned feature rows "
+                    "(F=%d ld=%lld); use the SpMM entry point and a GEMM instead", what, kMaxFeatures, (int)F,
+                    (long long)ldx);
+    return AES_OK;
 }
 
 }  // namespace
@@ -126,32 +213,42 @@ extern "C" int aes_gcn_layer_f32(int64_t n_rows, int64_t n_cols, int32_t W,
                                  float *H, int64_t ldh, void *stream)
 {
     const char *what = "aes_gcn_layer_f32";
-    if (n_rows < 0 || n_cols < 0)
-        return aes::fail(AES_ERR_INVALID_ARG, "%s: negative size (n_rows=%lld n_cols=%lld)", what, (long long)n_rows,
-                         (long long)n_cols);
-    if (n_cols > INT32_MAX) return aes::fail(AES_ERR_UNSUPPORTED, "%s: n_cols=%lld does not fit int32", what, (long long)n_cols);
-    if (W < 0 || W > AES_MAX_W) return aes::fail(AES_ERR_INVALID_ARG, "%s: W=%d outside 0..%d", what, (int)W, (int)AES_MAX_W);
-    if (F < 1 || Fo < 1 || Fo >= (1 << 24))
-        return aes::fail(AES_ERR_INVALID_ARG, "%s: F=%d / Fo=%d out of range", what, (int)F, (int)Fo);
-    if (ldx < F || ldt < Fo || ldh < Fo)
-        return aes::fail(AES_ERR_INVALID_ARG, "%s: leading dimension too small (ldx=%lld ldt=%lld ldh=%lld)", what,
-                         (long long)ldx, (long long)ldt, (long long)ldh);
-    if (s_rowptr == nullptr || Theta == nullptr) return aes::fail(AES_ERR_INVALID_ARG, "%s: s_rowptr / Theta is NULL", what);
-    if (n_rows > 0 && H == nullptr) return aes::fail(AES_ERR_INVALID_ARG, "%s: H is NULL", what);
-    if (n_rows > 0 && n_cols > 0 && X == nullptr) return aes::fail(AES_ERR_INVALID_ARG, "%s: X is NULL", what);
-    if (F > kMaxFeatures || F % 4 != 0 || ldx % 4 != 0 || !aes::aligned(X, 16))
-        return aes::fail(AES_ERR_UNSUPPORTED,
-                         "%s: needs F <= %d, F and ldx multiples of 4 and X 16-byte aligned (F=%d ldx=%lld); "
-                         "use aes_spmm_f32 and a GEMM instead", what, kMaxFeatures, (int)F, (long long)ldx);
+    if (int rc = check_layer(what, n_rows, n_cols, W, s_rowptr, X, ldx, F, 4, Theta, ldt, Fo, H, ldh)) return rc;
     if (n_rows == 0) return AES_OK;
-    hipStream_t stream_ = static_cast<hipStream_t>(stream);
     const SlotSource src = {s_rowptr, s_col, s_val, W, 0, 0};
-    int l = aes::pow2_ceil(aes::ceil_div(F, 4));
-    l = l < 8 ? 8 : l;
-    switch (l) {
-        case 8: return launch_gcn<8>(n_rows, src, X, ldx, F, Theta, ldt, Fo, H, ldh, stream_);
-        case 16: return launch_gcn<16>(n_rows, src, X, ldx, F, Theta, ldt, Fo, H, ldh, stream_);
-        case 32: return launch_gcn<32>(n_rows, src, X, ldx, F, Theta, ldt, Fo, H, ldh, stream_);
-        default: return launch_gcn<64>(n_rows, src, X, ldx, F, Theta, ldt, Fo, H, ldh, stream_);
+    const QParams qp = {nullptr, nullptr, 0, 0};
+    return dispatch_gcn<FeatF32<4>, kQNone, false>(what, n_rows, src, X, ldx, F, qp, Theta, ldt, Fo, H, ldh,
+                                                   static_cast<hipStream_t>(stream));
+}
+
+extern "C" int aes_gcn_layer_q8(int64_t n_rows, int64_t n_cols, int32_t W,
+                                const int64_t *s_rowptr, const int32_t *s_col, const float *s_val,
+                                const int8_t *Xq, int64_t ldq, int32_t F,
+                                int32_t scheme, int32_t granularity, const float *scale, const float *zero,
+                                const float *Theta, int64_t ldt, int32_t Fo,
+                                float *H, int64_t ldh, void *stream_)
+{
+    const char *what = "aes_gcn_layer_q8";
+    if (int rc = check_layer(what, n_rows, n_cols, W, s_rowptr, Xq, ldq, F, 1, Theta, ldt, Fo, H, ldh)) return rc;
+    if (scheme != AES_Q_AFFINE_FLOOR_U8 && scheme != AES_Q_SYMMETRIC_RNE_I8)
+        return fail(AES_ERR_INVALID_ARG, "%s: unknown scheme %d", what, (int)scheme);
+    if (granularity < AES_Q_PER_TENSOR || granularity > AES_Q_PER_ROW_FOLDED)
+        return fail(AES_ERR_INVALID_ARG, "%s: unknown granularity %d", what, (int)granularity);
+    const bool folded = granularity == AES_Q_PER_ROW_FOLDED;
+    const bool affine = scheme == AES_Q_AFFINE_FLOOR_U8;
+    if (!folded && scale == nullptr) return fail(AES_ERR_INVALID_ARG, "%s: scale is NULL", what);
+    if (affine && zero == nullptr) return fail(AES_ERR_INVALID_ARG, "%s: zero is NULL for the affine scheme", what);
+    if (n_rows == 0) return AES_OK;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    const SlotSource src = {s_rowptr, s_col, s_val, W, 0, 0};
+    const QParams qp = {scale, folded && !affine ? nullptr : zero, granularity, (affine && !folded) ? 1 : 0};
+    const bool row_scale = granularity == AES_Q_PER_ROW;
+    if (affine) {
+        if (row_scale)
+            return dispatch_gcn<FeatQ8<4, false>, kQRowScale, true>(what, n_rows, src, Xq, ldq, F, qp, Theta, ldt, Fo, H, ldh, stream);
+        return dispatch_gcn<FeatQ8<4, false>, kQNone, true>(what, n_rows, src, Xq, ldq, F, qp, Theta, ldt, Fo, H, ldh, stream);
     }
+    if (row_scale)
+        return dispatch_gcn<FeatQ8<4, true>, kQRowScale, true>(what, n_rows, src, Xq, ldq, F, qp, Theta, ldt, Fo, H, ldh, stream);
+    return dispatch_gcn<FeatQ8<4, true>, kQNone, true>(what, n_rows, src, Xq, ldq, F, qp, Theta, ldt, Fo, H, ldh, stream);
 }

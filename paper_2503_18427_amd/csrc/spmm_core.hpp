@@ -223,22 +223,21 @@ __device__ __forceinline__ void accumulate_tiles(const SlotSource &src, const Ro
     }
 }
 
-// Removes the loader's bias, applies the 8-bit group constants and stores one chunk of Y[r, :].
+// Removes the loader's bias and applies the 8-bit group constants to one chunk of a row:
+// out[] holds the finished float32 values of features f .. f + VEC - 1 of row r.
 // `side` must already be summed over the lanes of the group.
 template <typename Feat, int QMODE, bool QUANT, typename AccT>
-__device__ __forceinline__ void finish_chunk(const AccT (&acc_in)[Feat::VEC], AccT side_in, AccT vsum, bool lane_on,
-                                             int32_t f, const QParams &qp, int64_t r, float *__restrict__ y)
+__device__ __forceinline__ void finish_values(const AccT (&acc_in)[Feat::VEC], AccT side_in, AccT vsum, int32_t f,
+                                              const QParams &qp, int64_t r, float (&out)[Feat::VEC])
 {
     constexpr int VEC = Feat::VEC;
-    float acc[VEC];
 #pragma unroll
     for (int i = 0; i < VEC; ++i) {
         AccT a = acc_in[i];
         if (Feat::kBias != 0) a = a - static_cast<AccT>(Feat::kBias) * vsum;   // exact product, one rounding
-        acc[i] = static_cast<float>(a);
+        out[i] = static_cast<float>(a);
     }
     const float side = static_cast<float>(side_in);
-    if (!lane_on) return;
     if (QUANT) {
         // x_hat = q*scale_g + zero_g, with the group constants taken out of the sum:
         //   per tensor / column: Y = scale_c * sum(v*q) + zero_c * sum(v)
@@ -246,16 +245,27 @@ __device__ __forceinline__ void finish_chunk(const AccT (&acc_in)[Feat::VEC], Ac
 #pragma unroll
         for (int i = 0; i < VEC; ++i) {
             if (QMODE == kQRowScale) {
-                if (qp.affine) acc[i] += side;
+                if (qp.affine) out[i] += side;
             } else if (qp.granularity == AES_Q_PER_ROW_FOLDED) {
-                if (qp.zero) acc[i] += qp.zero[r];   // constants live in the plan's values; zero = row bias
+                if (qp.zero) out[i] += qp.zero[r];   // constants live in the plan's values; zero = row bias
             } else {
                 const int g = qp.granularity == AES_Q_PER_COLUMN ? f + i : 0;
-                acc[i] *= qp.scale[g];
-                if (qp.affine) acc[i] = __builtin_fmaf(side, qp.zero[g], acc[i]);
+                out[i] *= qp.scale[g];
+                if (qp.affine) out[i] = __builtin_fmaf(side, qp.zero[g], out[i]);
             }
         }
     }
+}
+
+// finish_values, then the store of the chunk to Y[r, f ...] (16-byte stores on the vector paths).
+template <typename Feat, int QMODE, bool QUANT, typename AccT>
+__device__ __forceinline__ void finish_chunk(const AccT (&acc_in)[Feat::VEC], AccT side_in, AccT vsum, bool lane_on,
+                                             int32_t f, const QParams &qp, int64_t r, float *__restrict__ y)
+{
+    constexpr int VEC = Feat::VEC;
+    if (!lane_on) return;
+    float acc[VEC];
+    finish_values<Feat, QMODE, QUANT, AccT>(acc_in, side_in, vsum, f, qp, r, acc);
     if constexpr (VEC % 4 == 0) {
 #pragma unroll
         for (int i = 0; i < VEC; i += 4)

@@ -131,6 +131,14 @@ def test_argument_errors_are_host_side(lib):
     assert gl(4, 4, 0, fake, fake, fake, fake, 10, 10, fake, 8, 8, fake, 8, None) == -2    # F % 4
     assert gl(0, 4, 0, fake, fake, fake, fake, 8, 8, fake, 8, 8, None, 8, None) == 0
 
+    glq = lib.aes_gcn_layer_q8
+    assert glq(4, 4, 0, fake, fake, fake, fake, 8, 8, 9, 1, fake, None, fake, 8, 8, fake, 8, None) == -1   # scheme
+    assert glq(4, 4, 0, fake, fake, fake, fake, 8, 8, 1, 7, fake, None, fake, 8, 8, fake, 8, None) == -1   # granularity
+    assert glq(4, 4, 0, fake, fake, fake, fake, 8, 8, 1, 1, None, None, fake, 8, 8, fake, 8, None) == -1   # scale NULL
+    assert glq(4, 4, 0, fake, fake, fake, fake, 8, 8, 0, 1, fake, None, fake, 8, 8, fake, 8, None) == -1   # affine, zero NULL
+    assert glq(4, 4, 0, fake, fake, fake, fake, 300, 300, 1, 1, fake, None, fake, 8, 8, fake, 8, None) == -2
+    assert glq(0, 4, 0, fake, fake, fake, fake, 8, 8, 1, 1, fake, None, fake, 8, 8, None, 8, None) == 0
+
     q8 = lib.aes_spmm_q8
     assert q8(4, 4, 0, fake, fake, fake, None, fake, 8, 8, 5, 1, fake, fake, fake, 8, None) == -1
     assert q8(4, 4, 0, fake, fake, fake, None, fake, 8, 8, 1, 5, fake, fake, fake, 8, None) == -1

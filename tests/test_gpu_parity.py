@@ -414,3 +414,38 @@ def test_folded_row_constants(G, scheme, F):
         torch.cuda.synchronize()
         assert torch.equal(plan.s_val[:S], folded.s_val[:S])
         plan.s_val.copy_(keep)
+
+
+@pytest.mark.parametrize("scheme,gran", [(SYM, ROW), (SYM, COLUMN), (AFF, ROW), (AFF, COLUMN), (AFF, TENSOR), (SYM, TENSOR)])
+@pytest.mark.parametrize("F,Fo", [(128, 64), (64, 100)])
+def test_gcn_layer_on_8bit_features(G, scheme, gran, F, Fo):
+    """The fused layer with the dequantisation inside the gather: against the oracle's
+    dequantise -> aggregate -> combine in double, and with folded per-node constants."""
+    import oracle as orc
+    import paper_2503_18427_amd as aes
+    rowptr, col, val, _, n_cols = _ragged_case(F + Fo + scheme + gran, 32, n=200)
+    rng = np.random.default_rng(F + 7 * gran)
+    X = (rng.standard_normal((n_cols, F)) * rng.uniform(0.2, 5.0, size=(n_cols, 1))).astype(np.float32)
+    Theta = (rng.standard_normal((F, Fo)) / np.sqrt(F)).astype(np.float32)
+    qd, qr = G.check_quantize(X, scheme, gran)
+    plan, ref = G.check_plan(rowptr, col, val, n_cols, 32, 0)
+    H = aes.aes_gcn_layer_q8(plan, qd[0], scheme, gran, qd[1], qd[2], G.to_dev(Theta))
+    torch.cuda.synchronize()
+    Y, Yabs = orc.spmm_q8(ref[0], ref[1], ref[2], qr[0], scheme, gran, qr[1], qr[2], want_abs=True)
+    if scheme == AFF:
+        sc = {0: qr[1][0], 1: qr[1][None, :], 2: qr[1][:, None]}[gran]
+        zr = {0: qr[2][0], 1: qr[2][None, :], 2: qr[2][:, None]}[gran]
+        mag = (np.abs(qr[0].astype(np.float32) * sc) + np.abs(zr)).astype(np.float32)
+        Yabs = orc.spmm_plan(ref[0], ref[1], np.abs(ref[2]), np.ascontiguousarray(np.broadcast_to(mag, X.shape)))
+    Href = orc.combine(Y, Theta)
+    Habs = orc.combine(Yabs, np.abs(Theta))
+    comp = float(np.max(np.abs(H.cpu().numpy() - Href) / np.where(Habs > 0, Habs, 1.0)))
+    assert comp <= G.Q8_TOL, comp
+    # the fused layer equals the 8-bit SpMM followed by a float64 product with Theta, closely
+    Yg = aes.aes_spmm_q8(plan, qd[0], scheme, gran, qd[1], qd[2], use_perm=False)
+    assert float((H.double() - Yg.double() @ G.to_dev(Theta).double()).abs().max()) < 1e-4
+    if gran == ROW:
+        fplan, bias = aes.aes_plan_fold_row_constants(plan, scheme, qd[1], qd[2])
+        Hf = aes.aes_gcn_layer_q8(fplan, qd[0], scheme, aes.AES_Q_PER_ROW_FOLDED, None, bias, G.to_dev(Theta))
+        torch.cuda.synchronize()
+        assert float((Hf - H).abs().max()) < 1e-4
