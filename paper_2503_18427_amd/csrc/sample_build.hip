@@ -192,13 +192,22 @@ offsets_kernel(int64_t n_rows, const int64_t *__restrict__ rowptr, int32_t W, in
 }
 
 // ---- kernel 4 ---------------------------------------------------------------
-// One thread per OUTPUT SLOT.  A workgroup owns kSampleRows consecutive rows:
-// their rowptr / s_rowptr segments sit in LDS, every thread finds the row of its
-// slot by binary search there, then copies (row fits) or samples: slot k of a
-// sampled row is entry j = k / sample_cnt of run i = k % sample_cnt, the run
-// starting at Eq. 3's start_i.  Writes are perfectly coalesced and the work per
-// thread does not depend on the degree distribution.
+// One thread per OUTPUT SLOT.  A workgroup owns kSampleRows consecutive rows, whose
+// rowptr / s_rowptr segments sit in LDS, and walks its slots in chunks of kChunkSlots:
+//   1 every non-empty row that starts inside the chunk writes its index at its first slot
+//   2 an inclusive prefix maximum over the chunk turns these head marks into the row of
+//     every slot (slots before the first mark belong to the row carried over from the
+//     previous chunk)
+//   3 thread t takes slots t, t + 256, ... of the chunk: entry k of a row that fits, or
+//     entry j = k / sample_cnt of run i = k % sample_cnt (the run starting at Eq. 3's
+//     start_i) of a sampled row; the loads of all its slots are issued before the first
+//     store.
+// Reads of whole rows and all writes are coalesced, and the work per slot does not depend
+// on the degree distribution: a hub row of millions of entries (W = 0) costs what the same
+// number of short rows costs.
 constexpr int kSampleRows = 256;
+constexpr int kSlotsPerThread = 8;
+constexpr int kChunkSlots = kBlock * kSlotsPerThread;
 
 __global__ void __launch_bounds__(kBlock)
 sample_slots_kernel(int64_t n_rows, const int64_t *__restrict__ rowptr, const int32_t *__restrict__ colidx,
@@ -206,39 +215,104 @@ sample_slots_kernel(int64_t n_rows, const int64_t *__restrict__ rowptr, const in
                     const int64_t *__restrict__ s_rowptr, int32_t *__restrict__ s_col,
                     float *__restrict__ s_val, int64_t *__restrict__ s_eid)
 {
+    static_assert(kSampleRows == kBlock, "one thread marks one row");
     __shared__ int64_t sh_out[kSampleRows + 1];
     __shared__ int64_t sh_in[kSampleRows + 1];
+    __shared__ __attribute__((aligned(16))) int32_t sh_row[kChunkSlots];   // head marks, then the row of every slot
+    __shared__ int32_t sh_wave_max[aes::kWavesPerBlock];
+    const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
     const int64_t r_lo = static_cast<int64_t>(blockIdx.x) * kSampleRows;
     const int nr = static_cast<int>(n_rows - r_lo < kSampleRows ? n_rows - r_lo : kSampleRows);
-    for (int i = threadIdx.x; i <= nr; i += kBlock) {
+    for (int i = tid; i <= nr; i += kBlock) {
         sh_out[i] = s_rowptr[r_lo + i];
         sh_in[i] = rowptr[r_lo + i];
     }
+#pragma unroll
+    for (int u = 0; u < kSlotsPerThread; ++u) sh_row[u * kBlock + tid] = -1;
     __syncthreads();
     const int64_t base = sh_out[0];
     const int64_t total = sh_out[nr] - base;
-    for (int64_t t = threadIdx.x; t < total; t += kBlock) {
-        // largest q in [0, nr) with sh_out[q] - base <= t (empty rows are skipped by construction)
-        int lo = 0, hi = nr;
-        while (hi - lo > 1) {
-            const int mid = (lo + hi) >> 1;
-            if (sh_out[mid] - base <= t) lo = mid; else hi = mid;
+    if (total == 0) return;                                   // uniform
+    const int64_t e_any = sh_in[0];                           // a valid entry index: some row here is non-empty
+    int64_t my_head = -1;                                     // first slot of this thread's row, block-relative
+    if (tid < nr && sh_out[tid + 1] > sh_out[tid]) my_head = sh_out[tid] - base;
+    int carry = 0;
+    for (int64_t c0 = 0; c0 < total; c0 += kChunkSlots) {
+        if (my_head >= c0 && my_head < c0 + kChunkSlots) sh_row[my_head - c0] = tid;
+        __syncthreads();
+        // inclusive prefix maximum: 8 consecutive marks per thread, then across the wave, then across waves
+        int m[kSlotsPerThread];
+        {
+            const int4 a = reinterpret_cast<const int4 *>(sh_row)[2 * tid];
+            const int4 b = reinterpret_cast<const int4 *>(sh_row)[2 * tid + 1];
+            m[0] = a.x; m[1] = a.y; m[2] = a.z; m[3] = a.w; m[4] = b.x; m[5] = b.y; m[6] = b.z; m[7] = b.w;
         }
-        const int64_t r = r_lo + lo;
-        const int64_t k = t - (sh_out[lo] - base);
-        const int64_t row_begin = sh_in[lo];
-        const int64_t row_nnz = sh_in[lo + 1] - row_begin;
-        int64_t e;
-        if (W == 0 || row_nnz <= W) {
-            e = row_begin + k;
-        } else {
-            int32_t N, cnt;
-            aes::sample_strategy(row_nnz, W, strategy, N, cnt);
-            e = aes::sampled_entry(row_begin, row_nnz, N, cnt, aes::row_offset(seed, r), static_cast<int32_t>(k));
+#pragma unroll
+        for (int u = 1; u < kSlotsPerThread; ++u) m[u] = m[u] > m[u - 1] ? m[u] : m[u - 1];
+        int incl = m[kSlotsPerThread - 1];
+#pragma unroll
+        for (int d = 1; d < kWave; d <<= 1) {
+            const int o = __shfl_up(incl, d, kWave);
+            if (lane >= d && o > incl) incl = o;
         }
-        s_col[base + t] = colidx[e];
-        s_val[base + t] = val[e];
-        if (s_eid) s_eid[base + t] = e;
+        int before = __shfl_up(incl, 1, kWave);               // maximum over the earlier lanes of this wave
+        if (lane == 0) before = -1;
+        if (lane == kWave - 1) sh_wave_max[wave] = incl;
+        __syncthreads();
+        int next_carry = carry;
+        if (carry > before) before = carry;
+#pragma unroll
+        for (int w = 0; w < aes::kWavesPerBlock; ++w) {
+            const int wm = sh_wave_max[w];
+            if (w < wave && wm > before) before = wm;
+            if (wm > next_carry) next_carry = wm;
+        }
+        carry = next_carry;
+#pragma unroll
+        for (int u = 0; u < kSlotsPerThread; ++u) m[u] = m[u] > before ? m[u] : before;
+        reinterpret_cast<int4 *>(sh_row)[2 * tid] = make_int4(m[0], m[1], m[2], m[3]);
+        reinterpret_cast<int4 *>(sh_row)[2 * tid + 1] = make_int4(m[4], m[5], m[6], m[7]);
+        __syncthreads();
+
+        int64_t e[kSlotsPerThread];
+#pragma unroll
+        for (int u = 0; u < kSlotsPerThread; ++u) {
+            const int idx = u * kBlock + tid;
+            const int64_t t = c0 + idx;
+            const int q = sh_row[idx];
+            sh_row[idx] = -1;                                 // this thread's own entries: ready for the next chunk
+            e[u] = e_any;                                     // slots past the end read a valid entry and store nothing
+            if (t < total) {
+                const int64_t k = t - (sh_out[q] - base);
+                const int64_t row_begin = sh_in[q];
+                const int64_t row_nnz = sh_in[q + 1] - row_begin;
+                if (W == 0 || row_nnz <= W) {
+                    e[u] = row_begin + k;
+                } else {
+                    int32_t N, cnt;
+                    aes::sample_strategy(row_nnz, W, strategy, N, cnt);
+                    e[u] = aes::sampled_entry(row_begin, row_nnz, N, cnt, aes::row_offset(seed, r_lo + q),
+                                              static_cast<int32_t>(k));
+                }
+            }
+        }
+        int32_t c[kSlotsPerThread];
+        float v[kSlotsPerThread];
+#pragma unroll
+        for (int u = 0; u < kSlotsPerThread; ++u) {
+            c[u] = colidx[e[u]];
+            v[u] = val[e[u]];
+        }
+#pragma unroll
+        for (int u = 0; u < kSlotsPerThread; ++u) {
+            const int64_t t = c0 + u * kBlock + tid;
+            if (t < total) {
+                s_col[base + t] = c[u];
+                s_val[base + t] = v[u];
+                if (s_eid) s_eid[base + t] = e[u];
+            }
+        }
+        __syncthreads();                                      // marks reset before the next chunk's heads are written
     }
 }
 
