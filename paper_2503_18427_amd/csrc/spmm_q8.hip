@@ -75,6 +75,32 @@ fold_row_constants_kernel(int64_t n_rows, const int64_t *__restrict__ s_rowptr, 
     }
 }
 
+// Symmetric scheme: no row sums are needed, so the fold is element-wise over the S = s_rowptr[n_rows]
+// slots (read on the device); four slots per thread and round, their scale gathers in flight together.
+__global__ void __launch_bounds__(kBlock)
+fold_scales_flat_kernel(int64_t n_rows, const int64_t *__restrict__ s_rowptr, const int32_t *__restrict__ s_col,
+                        const float *s_val, const float *__restrict__ scale, float *s_val_folded)
+{
+    constexpr int kPerThread = 4;
+    const int64_t S = s_rowptr[n_rows];
+    const int64_t step = static_cast<int64_t>(gridDim.x) * kBlock * kPerThread;
+    for (int64_t k0 = static_cast<int64_t>(blockIdx.x) * kBlock * kPerThread + threadIdx.x; k0 < S; k0 += step) {
+        float v[kPerThread], sc[kPerThread];
+#pragma unroll
+        for (int u = 0; u < kPerThread; ++u) {
+            const int64_t k = k0 + u * kBlock;
+            const int64_t kc = k < S ? k : S - 1;      // clamped: a valid slot, read twice, stored once
+            v[u] = s_val[kc];
+            sc[u] = scale[s_col[kc]];
+        }
+#pragma unroll
+        for (int u = 0; u < kPerThread; ++u) {
+            const int64_t k = k0 + u * kBlock;
+            if (k < S) s_val_folded[k] = v[u] * sc[u];
+        }
+    }
+}
+
 }  // namespace
 
 extern "C" int aes_plan_fold_row_constants(int64_t n_rows,
@@ -91,6 +117,11 @@ extern "C" int aes_plan_fold_row_constants(int64_t n_rows,
     if (affine && (zero == nullptr || row_bias == nullptr))
         return aes::fail(AES_ERR_INVALID_ARG, "%s: zero / row_bias is NULL for the affine scheme", what);
     if (n_rows == 0) return AES_OK;
+    if (!affine) {
+        fold_scales_flat_kernel<<<dim3(256 * 16), dim3(kBlock), 0, static_cast<hipStream_t>(stream)>>>(
+            n_rows, s_rowptr, s_col, s_val, scale, s_val_folded);
+        return aes::check_launch(what);
+    }
     const int64_t grid = aes::ceil_div(n_rows, kBlock / 16);
     if (grid > INT32_MAX) return aes::fail(AES_ERR_UNSUPPORTED, "%s: n_rows=%lld too large", what, (long long)n_rows);
     fold_row_constants_kernel<<<dim3(static_cast<unsigned>(grid)), dim3(kBlock), 0, static_cast<hipStream_t>(stream)>>>(
