@@ -194,6 +194,8 @@ int check_layer(const char *what, int64_t n_rows, int64_t n_cols, int32_t W, con
     if (s_rowptr == nullptr || Theta == nullptr) return fail(AES_ERR_INVALID_ARG, "%s: s_rowptr / Theta is NULL", what);
     if (n_rows > 0 && H == nullptr) return fail(AES_ERR_INVALID_ARG, "%s: H is NULL", what);
     if (n_rows > 0 && n_cols > 0 && X == nullptr) return fail(AES_ERR_INVALID_ARG, "%s: X is NULL", what);
+    if (ldx > UINT32_MAX)
+        return fail(AES_ERR_UNSUPPORTED, "%s: feature leading dimension %lld does not fit 32 bits", what, (long long)ldx);
     if (ldt >= (1 << 28) || ldh >= (1 << 28))
         return fail(AES_ERR_UNSUPPORTED, "%s: ldt / ldh must stay below 2^28 (32-bit lane offsets)", what);
     if (F > kMaxFeatures || F % 4 != 0 || ldx % 4 != 0 || !aligned(X, 4 * elem_bytes))

@@ -161,6 +161,11 @@ __device__ __forceinline__ void accumulate_tiles(const SlotSource &src, const Ro
                                                  int64_t tile_step, AccT (&acc)[Feat::VEC], AccT &side,
                                                  AccT &vsum)
 {
+    // Column indices are non-negative and the host has checked ldx < 2^32: the row offset is one
+    // 32 x 32 -> 64-bit multiply-add per gather instead of a sign-extended 64 x 64-bit product.
+    const uint32_t ld = static_cast<uint32_t>(ldx);
+    const typename Feat::elem_t *const x_lane = X + f;
+    auto row_of = [&](int32_t c) { return x_lane + static_cast<uint64_t>(static_cast<uint32_t>(c)) * ld; };
     for (int64_t t0 = first_tile * kTile; t0 < ri.n_slots; t0 += tile_step * kTile) {
         const int m = static_cast<int>(ri.n_slots - t0 < kTile ? ri.n_slots - t0 : kTile);
         wave_lds_sync();                             // previous tile fully consumed
@@ -194,7 +199,7 @@ __device__ __forceinline__ void accumulate_tiles(const SlotSource &src, const Ro
 #pragma unroll
                 for (int u = 0; u < UNROLL; ++u) cv[u] = my_stage[k + u];
 #pragma unroll
-                for (int u = 0; u < UNROLL; ++u) x[u] = Feat::load(X + static_cast<int64_t>(cv[u].x) * ldx + f);
+                for (int u = 0; u < UNROLL; ++u) x[u] = Feat::load(row_of(cv[u].x));
 #pragma unroll
                 for (int u = 0; u < UNROLL; ++u) {
                     Feat::fma(acc, __int_as_float(cv[u].y), x[u]);
@@ -211,7 +216,7 @@ __device__ __forceinline__ void accumulate_tiles(const SlotSource &src, const Ro
 #pragma unroll
                 for (int u = 0; u < UNROLL; ++u) {
                     x[u] = typename Feat::raw_t{};
-                    if (cv[u].x >= 0) x[u] = Feat::load(X + static_cast<int64_t>(cv[u].x) * ldx + f);
+                    if (cv[u].x >= 0) x[u] = Feat::load(row_of(cv[u].x));
                 }
 #pragma unroll
                 for (int u = 0; u < UNROLL; ++u) {

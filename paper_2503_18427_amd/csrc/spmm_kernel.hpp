@@ -189,6 +189,8 @@ inline int check_common(const char *what, int64_t n_rows, int64_t n_cols, const 
     if (ldx < F || ldy < F)
         return aes::fail(AES_ERR_INVALID_ARG, "%s: leading dimension smaller than F (ldx=%lld ldy=%lld F=%d)", what,
                          (long long)ldx, (long long)ldy, (int)F);
+    if (ldx > UINT32_MAX)
+        return aes::fail(AES_ERR_UNSUPPORTED, "%s: feature leading dimension %lld does not fit 32 bits", what, (long long)ldx);
     if (s_rowptr == nullptr) return aes::fail(AES_ERR_INVALID_ARG, "%s: s_rowptr is NULL", what);
     if (n_rows > 0 && Y == nullptr) return aes::fail(AES_ERR_INVALID_ARG, "%s: Y is NULL", what);
     // s_col / s_val may be NULL only for a plan without slots; that cannot be seen from the host
