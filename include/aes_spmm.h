@@ -25,7 +25,8 @@
  *   - aes_last_error() returns a static, thread-local, human-readable message
  *     for the last failing call of the calling thread.
  *   - Matrices are row-major.  Leading dimensions (ldx, ldq, ldy) are counted
- *     in elements and must be >= the row length.
+ *     in elements and must be >= the row length; the leading dimension of a
+ *     gathered feature matrix (X, Xq) must be below 2^32 (AES_ERR_UNSUPPORTED).
  *   - Within-row order of CSR entries is the caller's; the sampling takes runs
  *     of consecutive entries, so results depend on it.  Nothing is sorted.
  */

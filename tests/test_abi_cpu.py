@@ -93,6 +93,8 @@ def test_argument_errors_are_host_side(lib):
     assert f32(4, 4, 0, fake, fake, fake, None, fake, 8, 8, None, 8, None) == -1
     assert f32(0, 4, 0, fake, fake, fake, None, fake, 8, 8, None, 8, None) == 0       # nothing to do
     assert f32(4, 4, -1, fake, fake, fake, None, fake, 8, 8, fake, 8, None) == -1     # bad W
+    assert f32(4, 4, 0, fake, fake, fake, None, fake, 1 << 32, 8, fake, 8, None) == -2  # ldx beyond 32 bits
+    assert "32 bits" in aes.aes_last_error()
 
     q = lib.aes_quantize_features
     assert q(-1, 8, fake, 8, 1, 1, fake, 8, fake, fake, fake, 1 << 20, None) == -1
@@ -129,6 +131,8 @@ def test_argument_errors_are_host_side(lib):
     assert gl(4, 4, 0, fake, fake, fake, fake, 8, 8, fake, 8, 8, None, 8, None) == -1      # H NULL
     assert gl(4, 4, 0, fake, fake, fake, fake, 512, 512, fake, 8, 8, fake, 8, None) == -2  # F too wide
     assert gl(4, 4, 0, fake, fake, fake, fake, 10, 10, fake, 8, 8, fake, 8, None) == -2    # F % 4
+    assert gl(4, 4, 0, fake, fake, fake, fake, 1 << 32, 8, fake, 8, 8, fake, 8, None) == -2  # ldx beyond 32 bits
+    assert gl(4, 4, 0, fake, fake, fake, fake, 8, 8, fake, 1 << 28, 8, fake, 8, None) == -2  # ldt beyond the lane offsets
     assert gl(0, 4, 0, fake, fake, fake, fake, 8, 8, fake, 8, 8, None, 8, None) == 0
 
     glq = lib.aes_gcn_layer_q8
