@@ -225,33 +225,50 @@ column_partials_kernel(int64_t n, int32_t F, const float *__restrict__ X, int64_
     }
 }
 
-// Folds the slab partials of 64 columns per workgroup (4 lanes per column).
+// Folds the slab partials of kFoldCols columns per workgroup (kFoldLanes lanes per column, four
+// independent loads in flight per lane).
 // Per column: writes (scale, zero) and keeps x_min and d = x_max - x_min for the
 // encode kernel, which must divide by exactly the d that Eq. 1 names (scale * 255
 // would have been rounded twice).  Per tensor: leaves the column's (min, max) in
 // lo_out / d_out for tensor_fold_kernel.
+constexpr int kFoldCols = 16;
+constexpr int kFoldLanes = kBlock / kFoldCols;
+
 __global__ void __launch_bounds__(kBlock)
 finalise_kernel(int32_t F, int n_slabs, int empty, const float *__restrict__ partial, int affine_, int per_tensor,
                 float *__restrict__ scale_out, float *__restrict__ zero_out, float *__restrict__ lo_out,
                 float *__restrict__ d_out)
 {
-    __shared__ float sh_lo[kRowLanes][kColsPerBlock];
-    __shared__ float sh_hi[kRowLanes][kColsPerBlock];
+    __shared__ float sh_lo[kFoldLanes][kFoldCols];
+    __shared__ float sh_hi[kFoldLanes][kFoldCols];
     const bool affine = affine_ != 0;
-    const int tx = threadIdx.x % kColsPerBlock, ty = threadIdx.x / kColsPerBlock;
-    const int32_t c = blockIdx.x * kColsPerBlock + tx;
+    const int tx = threadIdx.x % kFoldCols, ty = threadIdx.x / kFoldCols;
+    const int32_t c = blockIdx.x * kFoldCols + tx;
     float lo = INFINITY, hi = -INFINITY;
     if (c < F) {
-        for (int s = ty; s < n_slabs; s += kRowLanes) {
-            lo = fminf(lo, partial[(static_cast<int64_t>(s) * 2 + 0) * F + c]);
-            hi = fmaxf(hi, partial[(static_cast<int64_t>(s) * 2 + 1) * F + c]);
+        const float *p = partial + c;
+        const int64_t slab_stride = 2 * static_cast<int64_t>(F);
+        int s = ty;
+        for (; s + 3 * kFoldLanes < n_slabs; s += 4 * kFoldLanes) {
+            float l[4], h[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                l[u] = p[(s + u * kFoldLanes) * slab_stride];
+                h[u] = p[(s + u * kFoldLanes) * slab_stride + F];
+            }
+            lo = fminf(fminf(lo, l[0]), fminf(l[1], fminf(l[2], l[3])));
+            hi = fmaxf(fmaxf(hi, h[0]), fmaxf(h[1], fmaxf(h[2], h[3])));
+        }
+        for (; s < n_slabs; s += kFoldLanes) {
+            lo = fminf(lo, p[s * slab_stride]);
+            hi = fmaxf(hi, p[s * slab_stride + F]);
         }
     }
     sh_lo[ty][tx] = lo;
     sh_hi[ty][tx] = hi;
     __syncthreads();
     if (ty != 0 || c >= F) return;
-    for (int j = 1; j < kRowLanes; ++j) {
+    for (int j = 1; j < kFoldLanes; ++j) {
         lo = fminf(lo, sh_lo[j][tx]);
         hi = fmaxf(hi, sh_hi[j][tx]);
     }
@@ -302,71 +319,130 @@ tensor_fold_kernel(int32_t F, int affine_, float *__restrict__ lo_io, float *__r
     }
 }
 
-// Element-wise encode with the finished group constants.
-template <int VEC>
+// Position of a grid-stride walk over the n x per_row items of a matrix (an item = VEC consecutive
+// features of one row): one 64-bit division per thread, then an add-with-carry per step.
+struct ItemWalk {
+    int64_t r, dr;
+    int32_t i, di, per_row;      // item within the row, its step, items per row
+    __device__ ItemWalk(int32_t per_row_) : per_row(per_row_)
+    {
+        const int64_t first = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+        const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
+        r = first / per_row;
+        i = static_cast<int32_t>(first - r * per_row);
+        dr = stride / per_row;
+        di = static_cast<int32_t>(stride - dr * per_row);
+    }
+    __device__ void next()
+    {
+        r += dr;
+        i += di;
+        if (i >= per_row) { i -= per_row; ++r; }
+    }
+};
+
+// Element-wise encode with the finished group constants.  The vector form walks over groups of
+// kEncodeRows consecutive rows: a thread encodes the same four columns of each of them, so their
+// loads are in flight together and the columns' constants are fetched once per group.
+constexpr int kEncodeRows = 4;
+
 __global__ void __launch_bounds__(kBlock)
-encode_kernel(int64_t n, int32_t F, const float *__restrict__ X, int64_t ldx, int affine_, int per_tensor,
-              const float *__restrict__ scale_in, const float *__restrict__ lo_in, const float *__restrict__ d_in,
-              int8_t *__restrict__ Xq, int64_t ldq)
+encode_vec_kernel(int64_t n, int32_t F, const float *__restrict__ X, int64_t ldx, int affine_, int per_tensor,
+                  const float *__restrict__ scale_in, const float *__restrict__ lo_in, const float *__restrict__ d_in,
+                  int8_t *__restrict__ Xq, int64_t ldq)
 {
     const bool affine = affine_ != 0;
-    const int64_t per_row = F / VEC;
-    const int64_t items = n * per_row;
-    for (int64_t it = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; it < items;
-         it += static_cast<int64_t>(gridDim.x) * kBlock) {
-        const int64_t r = it / per_row;
-        const int32_t f = static_cast<int32_t>(it - r * per_row) * VEC;
-        if constexpr (VEC == 4) {
-            const float4 v = *reinterpret_cast<const float4 *>(X + r * ldx + f);
-            const float x[4] = {v.x, v.y, v.z, v.w};
-            uint32_t w = 0;
+    const int64_t n_groups = (n + kEncodeRows - 1) / kEncodeRows;
+    for (ItemWalk w(F / 4); w.r < n_groups; w.next()) {
+        const int64_t r0 = w.r * kEncodeRows;
+        const int32_t f = w.i * 4;
+        float4 v[kEncodeRows];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int g = per_tensor ? 0 : f + i;
-                w |= encode(x[i], affine ? lo_in[g] : 0.0f, affine ? d_in[g] : 0.0f, scale_in[g], affine) << (8 * i);
-            }
-            *reinterpret_cast<uint32_t *>(Xq + r * ldq + f) = w;
-        } else {
-            const int g = per_tensor ? 0 : f;
-            Xq[r * ldq + f] = static_cast<int8_t>(
-                encode(X[r * ldx + f], affine ? lo_in[g] : 0.0f, affine ? d_in[g] : 0.0f, scale_in[g], affine));
+        for (int b = 0; b < kEncodeRows; ++b)
+            if (r0 + b < n) v[b] = *reinterpret_cast<const float4 *>(X + (r0 + b) * ldx + f);
+        float sc[4], lo[4], d[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int g = per_tensor ? 0 : f + i;
+            sc[i] = scale_in[g];
+            lo[i] = affine ? lo_in[g] : 0.0f;
+            d[i] = affine ? d_in[g] : 0.0f;
         }
+#pragma unroll
+        for (int b = 0; b < kEncodeRows; ++b) {
+            if (r0 + b >= n) break;
+            const float x[4] = {v[b].x, v[b].y, v[b].z, v[b].w};
+            uint32_t q = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) q |= encode(x[i], lo[i], d[i], sc[i], affine) << (8 * i);
+            *reinterpret_cast<uint32_t *>(Xq + (r0 + b) * ldq + f) = q;
+        }
+    }
+}
+
+__global__ void __launch_bounds__(kBlock)
+encode_scalar_kernel(int64_t n, int32_t F, const float *__restrict__ X, int64_t ldx, int affine_, int per_tensor,
+                     const float *__restrict__ scale_in, const float *__restrict__ lo_in,
+                     const float *__restrict__ d_in, int8_t *__restrict__ Xq, int64_t ldq)
+{
+    const bool affine = affine_ != 0;
+    for (ItemWalk w(F); w.r < n; w.next()) {
+        const int g = per_tensor ? 0 : w.i;
+        Xq[w.r * ldq + w.i] = static_cast<int8_t>(
+            encode(X[w.r * ldx + w.i], affine ? lo_in[g] : 0.0f, affine ? d_in[g] : 0.0f, scale_in[g], affine));
     }
 }
 
 // Eq. 2 as a stand-alone pass (the paper's placement: dequantise after loading,
 // before the SpMM): x_hat = q * scale_g + zero_g, multiply then add, binary32.
-template <int VEC>
+__device__ inline float dequantize_one(uint32_t byte, bool affine, float scale, float zero)
+{
+    const float q = affine ? static_cast<float>(byte) : static_cast<float>(static_cast<int8_t>(byte));
+    float t = q * scale;
+    if (affine) t = t + zero;
+    return t;
+}
+
+// Vector form: groups of kEncodeRows consecutive rows per thread, as in encode_vec_kernel.
 __global__ void __launch_bounds__(kBlock)
-dequantize_kernel(int64_t n, int32_t F, const int8_t *__restrict__ Xq, int64_t ldq, int affine_, int granularity,
-                  const float *__restrict__ scale, const float *__restrict__ zero, float *__restrict__ X, int64_t ldx)
+dequantize_vec_kernel(int64_t n, int32_t F, const int8_t *__restrict__ Xq, int64_t ldq, int affine_, int granularity,
+                      const float *__restrict__ scale, const float *__restrict__ zero, float *__restrict__ X,
+                      int64_t ldx)
 {
     const bool affine = affine_ != 0;
-    const int64_t per_row = F / VEC;
-    const int64_t items = n * per_row;
-    for (int64_t it = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; it < items;
-         it += static_cast<int64_t>(gridDim.x) * kBlock) {
-        const int64_t r = it / per_row;
-        const int32_t f = static_cast<int32_t>(it - r * per_row) * VEC;
-        uint32_t w;
-        if constexpr (VEC == 4)
-            w = *reinterpret_cast<const uint32_t *>(Xq + r * ldq + f);
-        else
-            w = static_cast<uint8_t>(Xq[r * ldq + f]);
-        float out[VEC];
+    const int64_t n_groups = (n + kEncodeRows - 1) / kEncodeRows;
+    for (ItemWalk w(F / 4); w.r < n_groups; w.next()) {
+        const int64_t r0 = w.r * kEncodeRows;
+        const int32_t f = w.i * 4;
+        uint32_t word[kEncodeRows];
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) {
-            const uint32_t byte = (w >> (8 * i)) & 0xffu;
-            const float q = affine ? static_cast<float>(byte) : static_cast<float>(static_cast<int8_t>(byte));
-            const int64_t g = granularity == AES_Q_PER_TENSOR ? 0 : granularity == AES_Q_PER_COLUMN ? f + i : r;
-            float t = q * scale[g];
-            if (affine) t = t + zero[g];
-            out[i] = t;
-        }
-        if constexpr (VEC == 4)
+        for (int b = 0; b < kEncodeRows; ++b)
+            if (r0 + b < n) word[b] = *reinterpret_cast<const uint32_t *>(Xq + (r0 + b) * ldq + f);
+#pragma unroll
+        for (int b = 0; b < kEncodeRows; ++b) {
+            const int64_t r = r0 + b;
+            if (r >= n) break;
+            float out[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int64_t g = granularity == AES_Q_PER_TENSOR ? 0 : granularity == AES_Q_PER_COLUMN ? f + i : r;
+                out[i] = dequantize_one((word[b] >> (8 * i)) & 0xffu, affine, scale[g], affine ? zero[g] : 0.0f);
+            }
             *reinterpret_cast<float4 *>(X + r * ldx + f) = make_float4(out[0], out[1], out[2], out[3]);
-        else
-            X[r * ldx + f] = out[0];
+        }
+    }
+}
+
+__global__ void __launch_bounds__(kBlock)
+dequantize_scalar_kernel(int64_t n, int32_t F, const int8_t *__restrict__ Xq, int64_t ldq, int affine_,
+                         int granularity, const float *__restrict__ scale, const float *__restrict__ zero,
+                         float *__restrict__ X, int64_t ldx)
+{
+    const bool affine = affine_ != 0;
+    for (ItemWalk w(F); w.r < n; w.next()) {
+        const int64_t g = granularity == AES_Q_PER_TENSOR ? 0 : granularity == AES_Q_PER_COLUMN ? w.i : w.r;
+        X[w.r * ldx + w.i] = dequantize_one(static_cast<uint8_t>(Xq[w.r * ldq + w.i]), affine, scale[g],
+                                            affine ? zero[g] : 0.0f);
     }
 }
 
@@ -377,6 +453,7 @@ int slabs_for(int64_t n)
 }
 
 constexpr int kRowsPerGroup = 4;
+constexpr int64_t kMaxElementwiseBlocks = 256 * 64;   // grid-stride beyond: measured faster than one item per thread
 
 template <int LPR, int VEC>
 void launch_rows(int64_t n, int32_t F, const float *X, int64_t ldx, int affine, int8_t *Xq, int64_t ldq,
@@ -464,7 +541,7 @@ extern "C" int aes_quantize_features(int64_t n, int32_t F, const float *X, int64
         if (int rc = aes::check_launch("aes_quantize_features/partials")) return rc;
     }
     const int empty = n == 0 ? 1 : 0;
-    finalise_kernel<<<dim3(col_blocks), dim3(kBlock), 0, stream>>>(F, empty ? 0 : n_slabs, empty, partial, affine,
+    finalise_kernel<<<dim3(static_cast<unsigned>(aes::ceil_div(F, kFoldCols))), dim3(kBlock), 0, stream>>>(F, empty ? 0 : n_slabs, empty, partial, affine,
                                                                    per_tensor, scale, zero, group_lo, group_d);
     if (int rc = aes::check_launch("aes_quantize_features/finalise")) return rc;
     if (per_tensor) {
@@ -472,14 +549,14 @@ extern "C" int aes_quantize_features(int64_t n, int32_t F, const float *X, int64
         if (int rc = aes::check_launch("aes_quantize_features/tensor_fold")) return rc;
     }
     if (n == 0) return AES_OK;
-    const int64_t items = n * (vec ? F / 4 : F);
+    const int64_t items = vec ? aes::ceil_div(n, kEncodeRows) * (F / 4) : n * F;
     int64_t blocks = aes::ceil_div(items, kBlock);
-    if (blocks > 256 * 64) blocks = 256 * 64;
+    if (blocks > kMaxElementwiseBlocks) blocks = kMaxElementwiseBlocks;
     if (vec)
-        encode_kernel<4><<<dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, stream>>>(
+        encode_vec_kernel<<<dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, stream>>>(
             n, F, X, ldx, affine, per_tensor, scale, group_lo, group_d, Xq, ldq);
     else
-        encode_kernel<1><<<dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, stream>>>(
+        encode_scalar_kernel<<<dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, stream>>>(
             n, F, X, ldx, affine, per_tensor, scale, group_lo, group_d, Xq, ldq);
     return aes::check_launch("aes_quantize_features/encode");
 }
@@ -506,14 +583,14 @@ extern "C" int aes_dequantize_features(int64_t n, int32_t F, const int8_t *Xq, i
     if (Xq == nullptr || X == nullptr) return aes::fail(AES_ERR_INVALID_ARG, "%s: Xq / X is NULL", what);
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     const bool vec = aes::aligned(X, 16) && aes::aligned(Xq, 4) && F % 4 == 0 && ldx % 4 == 0 && ldq % 4 == 0;
-    const int64_t items = n * (vec ? F / 4 : F);
+    const int64_t items = vec ? aes::ceil_div(n, kEncodeRows) * (F / 4) : n * F;
     int64_t blocks = aes::ceil_div(items, kBlock);
-    if (blocks > 256 * 64) blocks = 256 * 64;
+    if (blocks > kMaxElementwiseBlocks) blocks = kMaxElementwiseBlocks;
     if (vec)
-        dequantize_kernel<4><<<dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, stream>>>(
+        dequantize_vec_kernel<<<dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, stream>>>(
             n, F, Xq, ldq, affine, granularity, scale, zero, X, ldx);
     else
-        dequantize_kernel<1><<<dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, stream>>>(
+        dequantize_scalar_kernel<<<dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, stream>>>(
             n, F, Xq, ldq, affine, granularity, scale, zero, X, ldx);
     return aes::check_launch(what);
 }
