@@ -7,6 +7,7 @@
     python -m paper_2503_18427_amd.studies graph       [workload]
     python -m paper_2503_18427_amd.studies sampling-rate [workload]
     python -m paper_2503_18427_amd.studies folded      [workload]
+    python -m paper_2503_18427_amd.studies table-size
 
 They reproduce the *shape* of the paper's evaluation on the synthetic workloads
 (the paper's datasets are not available): kernel time and error against the
@@ -296,15 +297,47 @@ def graph(name: str) -> None:
           f"{t_eager:.3f} ms vs {t_graph:.3f} ms\n")
 
 
+def table_size(_name=None):
+    """Where the multiply saturates: a synthetic plan (2^20 rows x 32 slots, uniformly random columns, no
+    reuse beyond what the table size forces) over feature tables that fit L2, the Infinity Cache, or
+    neither.  Separates what the kernel can issue from what each level of the memory system delivers."""
+    from .binding import Plan
+    n_rows, W = 1 << 20, 32
+    S = n_rows * W
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(1)
+    s_rowptr = torch.arange(n_rows + 1, device="cuda", dtype=torch.int64) * W
+    s_val = torch.rand(S, device="cuda", generator=gen)
+    print("### synthetic plan, uniformly random columns: algorithmic GB/s against the size of the feature table "
+          f"({n_rows} rows x {W} slots)\n")
+    print("| F | table rows | fp32 table MiB | aes_spmm_f32 ms | GB/s | int8 table MiB | aes_spmm_q8 ms (per column) | GB/s |")
+    print("|---|---|---|---|---|---|---|---|")
+    for F in (128, 256):
+        Y = torch.empty(n_rows, F, device="cuda")
+        for log_cols in (11, 13, 15, 17, 19, 21):
+            n_cols = 1 << log_cols
+            s_col = torch.randint(0, n_cols, (S,), device="cuda", dtype=torch.int32, generator=gen)
+            X = torch.randn(n_cols, F, device="cuda", generator=gen)
+            plan = Plan(n_rows, n_cols, W, s_rowptr, s_col, s_val, None, None)
+            t32 = _time_ms(lambda: aes.aes_spmm_f32(plan, X, Y))
+            q = aes.aes_quantize_features(X, aes.AES_Q_SYMMETRIC_RNE_I8, aes.AES_Q_PER_COLUMN)
+            t8 = _time_ms(lambda: aes.aes_spmm_q8(plan, q[0], aes.AES_Q_SYMMETRIC_RNE_I8, aes.AES_Q_PER_COLUMN,
+                                                  q[1], q[2], Y))
+            b32, b8 = _bytes(n_rows, S, F, 4), _bytes(n_rows, S, F, 1)
+            print(f"| {F} | 2^{log_cols} | {n_cols * F * 4 / 2**20:.0f} | {t32:.3f} | {b32 / t32 / 1e6:.0f} | "
+                  f"{n_cols * F / 2**20:.1f} | {t8:.3f} | {b8 / t8 / 1e6:.0f} |")
+    print()
+
+
 def main(argv) -> int:
-    if len(argv) < 2 or argv[1] not in ("width-sweep", "strategies", "loading", "layer", "graph", "sampling-rate", "folded"):
+    if len(argv) < 2 or argv[1] not in ("width-sweep", "strategies", "loading", "layer", "graph", "sampling-rate", "folded", "table-size"):
         print(__doc__)
         return 2
     assert torch.cuda.is_available(), "the studies need a GPU"
     name = argv[2] if len(argv) > 2 else {"width-sweep": "rmat20", "strategies": "reddit_like",
-                                          "loading": "products_like", "layer": "products_like", "graph": "arxiv_like", "sampling-rate": "reddit_like", "folded": "products_like"}[argv[1]]
+                                          "loading": "products_like", "layer": "products_like", "graph": "arxiv_like", "sampling-rate": "reddit_like", "folded": "products_like", "table-size": None}[argv[1]]
     {"width-sweep": width_sweep, "strategies": strategies, "loading": loading, "layer": layer,
-     "graph": graph, "sampling-rate": sampling_rate, "folded": folded}[argv[1]](name)
+     "graph": graph, "sampling-rate": sampling_rate, "folded": folded, "table-size": table_size}[argv[1]](name)
     return 0
 
 
