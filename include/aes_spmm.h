@@ -168,8 +168,10 @@ int aes_sample_build(int64_t n_rows, int64_t n_cols, int64_t nnz,
  *   Y        [dev]  out, n_rows x F float32, leading dimension ldy; must not
  *                   overlap X
  *   F               1 <= F < 2^24
- * The fast path needs X and Y 16-byte aligned and F, ldx, ldy multiples of 4;
- * anything else runs a slower element-wise kernel with the same results.
+ * No alignment beyond that of a float is required of X, Y, ldx or ldy (rows that
+ * start on 16-byte boundaries touch the fewest memory lines).  Columns
+ * 0 .. 4*floor(F/4) - 1 are computed four per lane; the last F % 4 columns, if
+ * any, by a second, element-wise launch over the same plan (same results).
  */
 int aes_spmm_f32(int64_t n_rows, int64_t n_cols, int32_t W,
                  const int64_t *s_rowptr, const int32_t *s_col, const float *s_val,
@@ -235,9 +237,8 @@ int aes_dequantize_features(int64_t n, int32_t F, const int8_t *Xq, int64_t ldq,
  *   scale, zero [dev]  as written by aes_quantize_features; zero may be NULL
  *                for SYMMETRIC_RNE_I8 (for AES_Q_PER_ROW_FOLDED see
  *                aes_plan_fold_row_constants)
- * Other arguments as aes_spmm_f32.  The fast path needs Xq 4-byte aligned,
- * F and ldq multiples of 4, Y 16-byte aligned and ldy a multiple of 4;
- * anything else runs the element-wise kernel.
+ * Other arguments as aes_spmm_f32, including the treatment of F % 4 columns;
+ * Xq and ldq need no particular alignment.
  */
 int aes_spmm_q8(int64_t n_rows, int64_t n_cols, int32_t W,
                 const int64_t *s_rowptr, const int32_t *s_col, const float *s_val,

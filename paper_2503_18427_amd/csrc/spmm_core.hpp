@@ -50,13 +50,21 @@ __device__ inline double fma_acc(float a, float b, double acc)
 // kBias * sum(v) in its epilogue.  kBias = 128 lets signed 8-bit codes be
 // converted as unsigned bytes (one conversion instruction per byte, after one
 // XOR per four bytes) instead of sign-extending each byte first.
+//
+// The vector loads and stores only assume the alignment of one element (4 bytes for
+// float32 rows, 1 byte for 8-bit rows): gfx950 global memory instructions accept that,
+// and a row that does not start on a 16-byte boundary costs at most one more 128-byte
+// line, so any leading dimension takes the vector path.
+struct __attribute__((packed, aligned(4))) Float4U { float x, y, z, w; };
+struct __attribute__((packed, aligned(1))) Word1U { uint32_t v; };
+
 template <int VEC_> struct FeatF32;
 template <> struct FeatF32<4> {
     static constexpr int VEC = 4;
     static constexpr int kBias = 0;
     using elem_t = float;
-    using raw_t = float4;
-    static __device__ inline raw_t load(const elem_t *p) { return *reinterpret_cast<const float4 *>(p); }
+    using raw_t = Float4U;
+    static __device__ inline raw_t load(const elem_t *p) { return *reinterpret_cast<const Float4U *>(p); }
     template <typename AccT>
     static __device__ inline void fma(AccT (&acc)[4], float v, const raw_t &x)
     {
@@ -93,7 +101,7 @@ template <bool SIGNED> struct FeatQ8<4, SIGNED> {
     static constexpr int kBias = SIGNED ? 128 : 0;
     using elem_t = int8_t;
     using raw_t = uint32_t;
-    static __device__ inline raw_t load(const elem_t *p) { return *reinterpret_cast<const uint32_t *>(p); }
+    static __device__ inline raw_t load(const elem_t *p) { return reinterpret_cast<const Word1U *>(p)->v; }
     template <typename AccT>
     static __device__ inline void fma(AccT (&acc)[4], float v, const raw_t &x) { fma_bytes<SIGNED>(acc, v, x); }
 };
@@ -262,7 +270,7 @@ __device__ __forceinline__ void finish_values(const AccT (&acc_in)[Feat::VEC], A
     }
 }
 
-// finish_values, then the store of the chunk to Y[r, f ...] (16-byte stores on the vector paths).
+// finish_values, then the store of the chunk to Y[r, f ...] (16-byte stores, 4-byte aligned, on the vector paths).
 template <typename Feat, int QMODE, bool QUANT, typename AccT>
 __device__ __forceinline__ void finish_chunk(const AccT (&acc_in)[Feat::VEC], AccT side_in, AccT vsum, bool lane_on,
                                              int32_t f, const QParams &qp, int64_t r, float *__restrict__ y)
@@ -274,7 +282,7 @@ __device__ __forceinline__ void finish_chunk(const AccT (&acc_in)[Feat::VEC], Ac
     if constexpr (VEC % 4 == 0) {
 #pragma unroll
         for (int i = 0; i < VEC; i += 4)
-            *reinterpret_cast<float4 *>(y + i) = make_float4(acc[i], acc[i + 1], acc[i + 2], acc[i + 3]);
+            *reinterpret_cast<Float4U *>(y + i) = Float4U{acc[i], acc[i + 1], acc[i + 2], acc[i + 3]};
     } else {
 #pragma unroll
         for (int i = 0; i < VEC; ++i) y[i] = acc[i];

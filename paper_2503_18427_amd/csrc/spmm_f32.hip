@@ -6,15 +6,23 @@ namespace {
 
 using namespace aes;
 
+// Features 0 .. 4*floor(F/4) - 1 go through the vector kernel (four per lane, any alignment); the
+// last F % 4 columns, if any, through a second launch of the element-wise kernel on the same plan.
+// Every output element sees its slots in the same order either way.
 template <bool FUSED>
 int run_f32(const char *what, int64_t n_rows, const SlotSource &src, const int32_t *row_perm, const float *X,
             int64_t ldx, int32_t F, float *Y, int64_t ldy, hipStream_t stream)
 {
-    const bool fast = aes::aligned(X, 16) && aes::aligned(Y, 16) && F % 4 == 0 && ldx % 4 == 0 && ldy % 4 == 0;
     const bool lr = long_rows_possible(src.W);
     QParams qp = {nullptr, nullptr, 0, 0};
-    if (fast) return dispatch_lanes<FeatF32<4>, kQNone, false, FUSED>(lr, n_rows, src, row_perm, X, ldx, F, qp, Y, ldy, stream, what);
-    return launch_rows<64, 4, FeatF32<1>, kQNone, false, FUSED>(lr, n_rows, src, row_perm, X, ldx, F, qp, Y, ldy, stream, what);
+    const int32_t F4 = F & ~3;
+    if (F4 > 0)
+        if (int rc = dispatch_lanes<FeatF32<4>, kQNone, false, FUSED>(lr, n_rows, src, row_perm, X, ldx, F4, qp, Y, ldy, stream, what))
+            return rc;
+    if (F4 < F)
+        return launch_rows<8, 8, FeatF32<1>, kQNone, false, FUSED>(lr, n_rows, src, row_perm, X + F4, ldx, F - F4, qp,
+                                                                  Y + F4, ldy, stream, what);
+    return AES_OK;
 }
 
 }  // namespace

@@ -6,15 +6,26 @@ namespace {
 
 using namespace aes;
 
-// 8-bit features: 4 codes per lane when rows are 4-byte aligned, else element-wise.
+// 8-bit features: four codes per lane (any alignment) for columns 0 .. 4*floor(F/4) - 1, then a second
+// launch of the element-wise kernel on the same plan for the last F % 4 columns, if any.
 template <bool SIGNED, int QMODE, bool FUSED>
-int dispatch_q8(bool fast, int64_t n_rows, const SlotSource &src, const int32_t *row_perm, const int8_t *Xq,
+int dispatch_q8(int64_t n_rows, const SlotSource &src, const int32_t *row_perm, const int8_t *Xq,
                 int64_t ldq, int32_t F, QParams qp, float *Y, int64_t ldy, hipStream_t stream, const char *what)
 {
     const bool lr = long_rows_possible(src.W);
-    if (fast)
-        return dispatch_lanes<FeatQ8<4, SIGNED>, QMODE, true, FUSED>(lr, n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
-    return launch_rows<64, 4, FeatQ8<1, SIGNED>, QMODE, true, FUSED>(lr, n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
+    const int32_t F4 = F & ~3;
+    if (F4 > 0)
+        if (int rc = dispatch_lanes<FeatQ8<4, SIGNED>, QMODE, true, FUSED>(lr, n_rows, src, row_perm, Xq, ldq, F4, qp, Y, ldy, stream, what))
+            return rc;
+    if (F4 < F) {
+        if (qp.granularity == AES_Q_PER_COLUMN) {        // the columns' own constants
+            qp.scale += F4;
+            if (qp.zero) qp.zero += F4;
+        }
+        return launch_rows<8, 8, FeatQ8<1, SIGNED>, QMODE, true, FUSED>(lr, n_rows, src, row_perm, Xq + F4, ldq, F - F4, qp,
+                                                                       Y + F4, ldy, stream, what);
+    }
+    return AES_OK;
 }
 
 template <bool FUSED>
@@ -34,21 +45,20 @@ int run_q8(const char *what, int64_t n_rows, const SlotSource &src, const int32_
     if (affine && zero == nullptr)
         return aes::fail(AES_ERR_INVALID_ARG, "%s: zero (the row bias, for folded constants) is NULL for the affine scheme", what);
     if (n_rows == 0) return AES_OK;
-    const bool fast = aes::aligned(Y, 16) && ldy % 4 == 0 && aes::aligned(Xq, 4) && F % 4 == 0 && ldq % 4 == 0;
     // folded: the kernel only adds zero[r] (the row bias) at the end; the affine flag of QParams,
     // which drives the per-slot zero-point sums, stays off, the unsigned decoding is in the loader
     QParams qp = {scale, folded && !affine ? nullptr : zero, granularity, (affine && !folded) ? 1 : 0};
     if (folded) {
-        if (affine) return dispatch_q8<false, kQNone, FUSED>(fast, n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
-        return dispatch_q8<true, kQNone, FUSED>(fast, n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
+        if (affine) return dispatch_q8<false, kQNone, FUSED>(n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
+        return dispatch_q8<true, kQNone, FUSED>(n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
     }
     const bool per_row = granularity == AES_Q_PER_ROW;
     if (affine) {
-        if (per_row) return dispatch_q8<false, kQRowScale, FUSED>(fast, n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
-        return dispatch_q8<false, kQNone, FUSED>(fast, n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
+        if (per_row) return dispatch_q8<false, kQRowScale, FUSED>(n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
+        return dispatch_q8<false, kQNone, FUSED>(n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
     }
-    if (per_row) return dispatch_q8<true, kQRowScale, FUSED>(fast, n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
-    return dispatch_q8<true, kQNone, FUSED>(fast, n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
+    if (per_row) return dispatch_q8<true, kQRowScale, FUSED>(n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
+    return dispatch_q8<true, kQNone, FUSED>(n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
 }
 
 // One group of 16 lanes per row: s_val_folded = s_val * scale[col], row_bias = sum s_val * zero[col].

@@ -103,7 +103,7 @@ def test_feature_widths_and_alignment(G, F):
     X = rng.standard_normal((n_cols, F)).astype(np.float32)
     plan, ref = G.check_plan(rowptr, col, val, n_cols, 32, 0)
     G.check_f32(plan, ref, X)
-    # padded leading dimension, and a misaligned view (element-wise kernel)
+    # padded leading dimension, and a view whose rows start at odd element offsets
     import paper_2503_18427_amd as aes
     buf = torch.zeros((n_cols, F + 9), device="cuda")
     buf[:, 1:F + 1] = G.to_dev(X)
@@ -116,7 +116,15 @@ def test_feature_widths_and_alignment(G, F):
     for scheme in (SYM, AFF):
         for gran in (TENSOR, COLUMN, ROW):
             qd, qr = G.check_quantize(X, scheme, gran)
-            G.check_q8(plan, ref, qd, qr, scheme, gran)
+            Yq, _, _ = G.check_q8(plan, ref, qd, qr, scheme, gran)
+            # codes at an odd byte offset with an odd leading dimension: same bits
+            qbuf = torch.zeros((n_cols, F + 3), dtype=qd[0].dtype, device="cuda")
+            qbuf[:, 1:F + 1] = qd[0]
+            Yb.fill_(7.0)
+            aes.aes_spmm_q8(plan, qbuf[:, 1:F + 1], scheme, gran, qd[1], qd[2], Yb[:, 2:F + 2])
+            torch.cuda.synchronize()
+            assert torch.equal(Yb[:, 2:F + 2], Yq)
+            assert torch.all(Yb[:, :2] == 7.0) and torch.all(Yb[:, F + 2:] == 7.0)
 
 
 def test_quantize_layouts_and_constants(G):
