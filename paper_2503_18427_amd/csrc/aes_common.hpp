@@ -16,6 +16,13 @@ constexpr int kWave = 64;          // gfx950 wavefront width
 constexpr int kBlock = 256;        // threads per workgroup used by every kernel here
 constexpr int kWavesPerBlock = kBlock / kWave;
 
+// 16-byte and 4-byte accesses that assume only the alignment of one element (4 bytes for float32
+// rows, 1 byte for rows of 8-bit codes): gfx950 global memory instructions accept them, and the
+// compiler still emits one dwordx4 / dword instruction, so leading dimensions and base addresses
+// need no padding; an unaligned row merely touches at most one more 128-byte line.
+struct __attribute__((packed, aligned(4))) Float4U { float x, y, z, w; };
+struct __attribute__((packed, aligned(1))) Word1U { uint32_t v; };
+
 // Thread-local message of the last failing call.
 char *error_buffer();
 int fail(int code, const char *fmt, ...) __attribute__((format(printf, 2, 3)));

@@ -78,7 +78,7 @@ quantize_rows_kernel(int64_t n, int32_t F, const float *__restrict__ X, int64_t 
         if (f < F) {
             float x[VEC];
             if constexpr (VEC == 4) {
-                const float4 v = *reinterpret_cast<const float4 *>(x_row + f);
+                const aes::Float4U v = *reinterpret_cast<const aes::Float4U *>(x_row + f);
                 x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
             } else {
                 x[0] = x_row[f];
@@ -112,7 +112,7 @@ quantize_rows_kernel(int64_t n, int32_t F, const float *__restrict__ X, int64_t 
 #pragma unroll
                 for (int i = 0; i < VEC; ++i) x[i] = keep[i];
             } else if constexpr (VEC == 4) {
-                const float4 v = *reinterpret_cast<const float4 *>(x_row + f);
+                const aes::Float4U v = *reinterpret_cast<const aes::Float4U *>(x_row + f);
                 x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
             } else {
                 x[0] = x_row[f];
@@ -120,7 +120,7 @@ quantize_rows_kernel(int64_t n, int32_t F, const float *__restrict__ X, int64_t 
             if constexpr (VEC == 4) {
                 uint32_t w = encode(x[0], lo, d, scale, affine) | (encode(x[1], lo, d, scale, affine) << 8) |
                              (encode(x[2], lo, d, scale, affine) << 16) | (encode(x[3], lo, d, scale, affine) << 24);
-                *reinterpret_cast<uint32_t *>(q_row + f) = w;
+                reinterpret_cast<aes::Word1U *>(q_row + f)->v = w;
             } else {
                 q_row[f] = static_cast<int8_t>(encode(x[0], lo, d, scale, affine));
             }
@@ -143,11 +143,11 @@ quantize_rows_batched_kernel(int64_t n, int32_t F, const float *__restrict__ X, 
     const int64_t r0 = (static_cast<int64_t>(blockIdx.x) * kGroups + threadIdx.x / LPR) * RPG;
     const int32_t f = lane * 4;
     const bool lane_on = f < F;
-    float4 v[RPG];
+    aes::Float4U v[RPG];
 #pragma unroll
     for (int j = 0; j < RPG; ++j) {
-        v[j] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (lane_on && r0 + j < n) v[j] = *reinterpret_cast<const float4 *>(X + (r0 + j) * ldx + f);
+        v[j] = aes::Float4U{0.f, 0.f, 0.f, 0.f};
+        if (lane_on && r0 + j < n) v[j] = *reinterpret_cast<const aes::Float4U *>(X + (r0 + j) * ldx + f);
     }
 #pragma unroll
     for (int j = 0; j < RPG; ++j) {
@@ -177,7 +177,7 @@ quantize_rows_batched_kernel(int64_t n, int32_t F, const float *__restrict__ X, 
         if (lane_on) {
             const uint32_t w = encode(x[0], lo, d, scale, affine) | (encode(x[1], lo, d, scale, affine) << 8) |
                                (encode(x[2], lo, d, scale, affine) << 16) | (encode(x[3], lo, d, scale, affine) << 24);
-            *reinterpret_cast<uint32_t *>(Xq + r * ldq + f) = w;
+            reinterpret_cast<aes::Word1U *>(Xq + r * ldq + f)->v = w;
         }
     }
 }
@@ -356,10 +356,10 @@ encode_vec_kernel(int64_t n, int32_t F, const float *__restrict__ X, int64_t ldx
     for (ItemWalk w(F / 4); w.r < n_groups; w.next()) {
         const int64_t r0 = w.r * kEncodeRows;
         const int32_t f = w.i * 4;
-        float4 v[kEncodeRows];
+        aes::Float4U v[kEncodeRows];
 #pragma unroll
         for (int b = 0; b < kEncodeRows; ++b)
-            if (r0 + b < n) v[b] = *reinterpret_cast<const float4 *>(X + (r0 + b) * ldx + f);
+            if (r0 + b < n) v[b] = *reinterpret_cast<const aes::Float4U *>(X + (r0 + b) * ldx + f);
         float sc[4], lo[4], d[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -375,7 +375,7 @@ encode_vec_kernel(int64_t n, int32_t F, const float *__restrict__ X, int64_t ldx
             uint32_t q = 0;
 #pragma unroll
             for (int i = 0; i < 4; ++i) q |= encode(x[i], lo[i], d[i], sc[i], affine) << (8 * i);
-            *reinterpret_cast<uint32_t *>(Xq + (r0 + b) * ldq + f) = q;
+            reinterpret_cast<aes::Word1U *>(Xq + (r0 + b) * ldq + f)->v = q;
         }
     }
 }
@@ -417,7 +417,7 @@ dequantize_vec_kernel(int64_t n, int32_t F, const int8_t *__restrict__ Xq, int64
         uint32_t word[kEncodeRows];
 #pragma unroll
         for (int b = 0; b < kEncodeRows; ++b)
-            if (r0 + b < n) word[b] = *reinterpret_cast<const uint32_t *>(Xq + (r0 + b) * ldq + f);
+            if (r0 + b < n) word[b] = reinterpret_cast<const aes::Word1U *>(Xq + (r0 + b) * ldq + f)->v;
 #pragma unroll
         for (int b = 0; b < kEncodeRows; ++b) {
             const int64_t r = r0 + b;
@@ -428,7 +428,7 @@ dequantize_vec_kernel(int64_t n, int32_t F, const int8_t *__restrict__ Xq, int64
                 const int64_t g = granularity == AES_Q_PER_TENSOR ? 0 : granularity == AES_Q_PER_COLUMN ? f + i : r;
                 out[i] = dequantize_one((word[b] >> (8 * i)) & 0xffu, affine, scale[g], affine ? zero[g] : 0.0f);
             }
-            *reinterpret_cast<float4 *>(X + r * ldx + f) = make_float4(out[0], out[1], out[2], out[3]);
+            *reinterpret_cast<aes::Float4U *>(X + r * ldx + f) = aes::Float4U{out[0], out[1], out[2], out[3]};
         }
     }
 }
@@ -507,8 +507,7 @@ extern "C" int aes_quantize_features(int64_t n, int32_t F, const float *X, int64
     if (need > 0 && !aes::aligned(workspace, 4))
         return aes::fail(AES_ERR_WORKSPACE, "%s: workspace must be 4-byte aligned", what);
     hipStream_t stream = static_cast<hipStream_t>(stream_);
-    const bool vec_in = aes::aligned(X, 16) && F % 4 == 0 && ldx % 4 == 0;
-    const bool vec = vec_in && aes::aligned(Xq, 4) && ldq % 4 == 0;
+    const bool vec = F % 4 == 0;      // four features per lane; no alignment needed beyond an element's
 
     if (granularity == AES_Q_PER_ROW) {
         if (n == 0) return AES_OK;
@@ -582,7 +581,7 @@ extern "C" int aes_dequantize_features(int64_t n, int32_t F, const int8_t *Xq, i
     if (n == 0) return AES_OK;
     if (Xq == nullptr || X == nullptr) return aes::fail(AES_ERR_INVALID_ARG, "%s: Xq / X is NULL", what);
     hipStream_t stream = static_cast<hipStream_t>(stream_);
-    const bool vec = aes::aligned(X, 16) && aes::aligned(Xq, 4) && F % 4 == 0 && ldx % 4 == 0 && ldq % 4 == 0;
+    const bool vec = F % 4 == 0;
     const int64_t items = vec ? aes::ceil_div(n, kEncodeRows) * (F / 4) : n * F;
     int64_t blocks = aes::ceil_div(items, kBlock);
     if (blocks > kMaxElementwiseBlocks) blocks = kMaxElementwiseBlocks;

@@ -51,13 +51,8 @@ __device__ inline double fma_acc(float a, float b, double acc)
 // converted as unsigned bytes (one conversion instruction per byte, after one
 // XOR per four bytes) instead of sign-extending each byte first.
 //
-// The vector loads and stores only assume the alignment of one element (4 bytes for
-// float32 rows, 1 byte for 8-bit rows): gfx950 global memory instructions accept that,
-// and a row that does not start on a 16-byte boundary costs at most one more 128-byte
-// line, so any leading dimension takes the vector path.
-struct __attribute__((packed, aligned(4))) Float4U { float x, y, z, w; };
-struct __attribute__((packed, aligned(1))) Word1U { uint32_t v; };
-
+// The vector loads and stores only assume the alignment of one element (Float4U / Word1U),
+// so any leading dimension takes the vector path.
 template <int VEC_> struct FeatF32;
 template <> struct FeatF32<4> {
     static constexpr int VEC = 4;

@@ -148,6 +148,23 @@ def test_quantize_layouts_and_constants(G):
     ref = aes.aes_quantize_features(G.to_dev(X), SYM, ROW)
     torch.cuda.synchronize()
     assert torch.equal(outq[:, 4:F + 4], ref[0]) and torch.equal(sc, ref[1])
+    # rows at odd element / byte offsets with odd leading dimensions: same codes, padding untouched
+    odd = torch.zeros((n, F + 7), device="cuda")
+    odd[:, 3:F + 3] = G.to_dev(X)
+    for scheme in (SYM, AFF):
+        for gran in (TENSOR, COLUMN, ROW):
+            want = aes.aes_quantize_features(G.to_dev(X), scheme, gran)
+            oq = torch.full((n, F + 5), 77, dtype=want[0].dtype, device="cuda")
+            groups = {TENSOR: 1, COLUMN: F, ROW: n}[gran]
+            s2, z2 = torch.empty(groups, device="cuda"), torch.zeros(groups, device="cuda")
+            aes.aes_quantize_features(odd[:, 3:F + 3], scheme, gran, out=(oq[:, 1:F + 1], s2, z2))
+            back = torch.full((n, F + 7), 9.0, device="cuda")
+            aes.aes_dequantize_features(oq[:, 1:F + 1], scheme, gran, s2, z2, back[:, 3:F + 3])
+            torch.cuda.synchronize()
+            assert torch.equal(oq[:, 1:F + 1], want[0]) and torch.equal(s2, want[1])
+            assert torch.all(oq[:, :1] == 77) and torch.all(oq[:, F + 1:] == 77)
+            assert torch.equal(back[:, 3:F + 3], aes.aes_dequantize_features(want[0], scheme, gran, want[1], want[2]))
+            assert torch.all(back[:, :3] == 9.0) and torch.all(back[:, F + 3:] == 9.0)
     assert torch.all(outq[:, :4] == 0) and torch.all(outq[:, F + 4:] == 0)
     # constant tensor
     C = np.full((33, 8), 1.25, dtype=np.float32)
