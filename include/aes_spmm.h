@@ -311,9 +311,9 @@ int aes_spmm_fused_q8(int64_t n_rows, int64_t n_cols,
  *
  *   plan, W         as for aes_spmm_f32 (rows are always handled by one lane
  *                   group here, whatever W says)
- *   X     [dev]     n_cols x F float32 (ldx); F <= 256, F and ldx multiples of 4,
- *                   16-byte aligned - otherwise AES_ERR_UNSUPPORTED (run
- *                   aes_spmm_f32 and a GEMM instead)
+ *   X     [dev]     n_cols x F float32 (ldx); F <= 256 and a multiple of 4 -
+ *                   otherwise AES_ERR_UNSUPPORTED (run aes_spmm_f32 and a GEMM
+ *                   instead); no alignment needed beyond a float's
  *   Theta [dev]     F x Fo float32, row-major, leading dimension ldt
  *   H     [dev]     out, n_rows x Fo float32 (ldh); must not overlap the inputs
  */
@@ -327,7 +327,7 @@ int aes_gcn_layer_f32(int64_t n_rows, int64_t n_cols, int32_t W,
  * The same layer on 8-bit features: H = (A_s x_hat) Theta with the dequantisation of Sec. 2.3
  * Eq. 2 fused into the gather exactly as in aes_spmm_q8 (same scheme / granularity / scale /
  * zero arguments, AES_Q_PER_ROW_FOLDED included), the aggregated tile multiplied by Theta on
- * the matrix cores.  Xq needs 4-byte aligned rows with F and ldq multiples of 4, F <= 256.
+ * the matrix cores.  F <= 256 and a multiple of 4; Xq and ldq need no particular alignment.
  */
 int aes_gcn_layer_q8(int64_t n_rows, int64_t n_cols, int32_t W,
                      const int64_t *s_rowptr, const int32_t *s_col, const float *s_val,

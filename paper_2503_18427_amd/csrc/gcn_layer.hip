@@ -177,9 +177,9 @@ int dispatch_gcn(const char *what, int64_t n_rows, const SlotSource &src, const 
     }
 }
 
-// Argument checks shared by the float32 and the 8-bit entry point (elem_bytes = bytes per feature).
+// Argument checks shared by the float32 and the 8-bit entry point.
 int check_layer(const char *what, int64_t n_rows, int64_t n_cols, int32_t W, const int64_t *s_rowptr, const void *X,
-                int64_t ldx, int32_t F, int elem_bytes, const float *Theta, int64_t ldt, int32_t Fo, const float *H,
+                int64_t ldx, int32_t F, const float *Theta, int64_t ldt, int32_t Fo, const float *H,
                 int64_t ldh)
 {
     if (n_rows < 0 || n_cols < 0)
@@ -198,11 +198,10 @@ int check_layer(const char *what, int64_t n_rows, int64_t n_cols, int32_t W, con
         return fail(AES_ERR_UNSUPPORTED, "%s: feature leading dimension %lld does not fit 32 bits", what, (long long)ldx);
     if (ldt >= (1 << 28) || ldh >= (1 << 28))
         return fail(AES_ERR_UNSUPPORTED, "%s: ldt / ldh must stay below 2^28 (32-bit lane offsets)", what);
-    if (F > kMaxFeatures || F % 4 != 0 || ldx % 4 != 0 || !aligned(X, 4 * elem_bytes))
+    if (F > kMaxFeatures || F % 4 != 0)
         return fail(AES_ERR_UNSUPPORTED,
-                    "%s: needs F <= %d, F and the feature leading dimension multiples of 4 and aligned feature rows "
-                    "(F=%d ld=%lld); use the SpMM entry point and a GEMM instead", what, kMaxFeatures, (int)F,
-                    (long long)ldx);
+                    "%s: needs F <= %d and a multiple of 4 (F=%d); use the SpMM entry point and a GEMM instead", what,
+                    kMaxFeatures, (int)F);
     return AES_OK;
 }
 
@@ -215,7 +214,7 @@ extern "C" int aes_gcn_layer_f32(int64_t n_rows, int64_t n_cols, int32_t W,
                                  float *H, int64_t ldh, void *stream)
 {
     const char *what = "aes_gcn_layer_f32";
-    if (int rc = check_layer(what, n_rows, n_cols, W, s_rowptr, X, ldx, F, 4, Theta, ldt, Fo, H, ldh)) return rc;
+    if (int rc = check_layer(what, n_rows, n_cols, W, s_rowptr, X, ldx, F, Theta, ldt, Fo, H, ldh)) return rc;
     if (n_rows == 0) return AES_OK;
     const SlotSource src = {s_rowptr, s_col, s_val, W, 0, 0};
     const QParams qp = {nullptr, nullptr, 0, 0};
@@ -231,7 +230,7 @@ extern "C" int aes_gcn_layer_q8(int64_t n_rows, int64_t n_cols, int32_t W,
                                 float *H, int64_t ldh, void *stream_)
 {
     const char *what = "aes_gcn_layer_q8";
-    if (int rc = check_layer(what, n_rows, n_cols, W, s_rowptr, Xq, ldq, F, 1, Theta, ldt, Fo, H, ldh)) return rc;
+    if (int rc = check_layer(what, n_rows, n_cols, W, s_rowptr, Xq, ldq, F, Theta, ldt, Fo, H, ldh)) return rc;
     if (scheme != AES_Q_AFFINE_FLOOR_U8 && scheme != AES_Q_SYMMETRIC_RNE_I8)
         return fail(AES_ERR_INVALID_ARG, "%s: unknown scheme %d", what, (int)scheme);
     if (granularity < AES_Q_PER_TENSOR || granularity > AES_Q_PER_ROW_FOLDED)

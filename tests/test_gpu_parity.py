@@ -331,7 +331,9 @@ def test_gcn_layer_fused_with_matrix_cores(G, F, Fo):
         Hb = torch.full((rowptr.size - 1, Fo + 3), 5.0, device="cuda")
         Tb = torch.zeros((F, Fo + 7), device="cuda")
         Tb[:, 2:Fo + 2] = G.to_dev(Theta)
-        aes.aes_gcn_layer_f32(plan, G.to_dev(X), Tb[:, 2:Fo + 2], Hb[:, 1:Fo + 1])
+        Xb = torch.zeros((n_cols, F + 5), device="cuda")
+        Xb[:, 3:F + 3] = G.to_dev(X)
+        aes.aes_gcn_layer_f32(plan, Xb[:, 3:F + 3], Tb[:, 2:Fo + 2], Hb[:, 1:Fo + 1])
         torch.cuda.synchronize()
         assert torch.equal(Hb[:, 1:Fo + 1], H)
         assert torch.all(Hb[:, 0] == 5.0) and torch.all(Hb[:, Fo + 1:] == 5.0)
