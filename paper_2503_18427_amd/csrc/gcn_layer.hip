@@ -22,10 +22,12 @@ constexpr int kMaxFeatures = 256;    // one chunk of four features per lane, at 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 // Feat / QMODE / QUANT as in the SpMM kernel: float32 features, or 8-bit codes dequantised in the gather.
-// At least four waves per SIMD: the gather phase needs the occupancy, and the register allocator
-// would otherwise spend the whole file on the unrolled MFMA phase.
+// The register budget is set per variant.  float32: at least four waves per SIMD (the gather phase needs
+// the occupancy, and the register allocator would otherwise spend the whole file on the unrolled MFMA
+// phase).  8-bit: its gather phase is short and bound by latency, so it wants six to seven waves per SIMD
+// more than it wants a deep Theta prefetch (kChunk below): 65-75 registers, no spills.
 template <int LPR, typename Feat, int QMODE, bool QUANT>
-__global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(4)))
+__global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(QUANT ? 6 : 4)))
 gcn_layer_kernel(int64_t n_rows, SlotSource src, const typename Feat::elem_t *__restrict__ X, int64_t ldx, int32_t F,
                  QParams qp, const float *__restrict__ Theta, int64_t ldt, int32_t Fo, float *__restrict__ H,
                  int64_t ldh)
@@ -68,12 +70,12 @@ gcn_layer_kernel(int64_t n_rows, SlotSource src, const typename Feat::elem_t *__
     // it receives D[8 * (v / 4) + 4 * (l / 32) + v % 4][l % 32] in result register v.
     //
     // A wave owns the 32-column blocks nb = wave, wave + 4, ...  Its Theta operands are held in
-    // registers in chunks of kChunk MFMAs (64 rows of Theta): the first two chunks are requested
+    // registers in chunks of kChunk MFMAs (2 * kChunk rows of Theta): the first two chunks are requested
     // BEFORE the workgroup barrier, right after the wave's last gather, so their latency - long,
     // because the vector memory path is saturated by the gathers of the other workgroups - passes
     // while the wave waits for the rest of the tile; a chunk's registers are refilled as soon as it
     // has been consumed.  The gather loop's registers are dead by then, so this costs no occupancy.
-    constexpr int kChunk = 32;
+    constexpr int kChunk = QUANT ? 8 : 32;
     const int i = wl % 32, h = wl / 32;
     const int n_chunks = (F + 2 * kChunk - 1) / (2 * kChunk);
     float b0[kChunk], b1[kChunk];
@@ -110,12 +112,15 @@ gcn_layer_kernel(int64_t n_rows, SlotSource src, const typename Feat::elem_t *__
         load_a(0, a_cur);
 #pragma unroll
         for (int u0 = 0; u0 < kChunk; u0 += kBatch) {
-            if (u0 + kBatch < kChunk) load_a(u0 + kBatch, a_nxt);
+            const bool more = u0 + kBatch < kChunk;  // known at compile time: the loop is unrolled
+            if (more) load_a(u0 + kBatch, a_nxt);
             __builtin_amdgcn_sched_barrier(0);       // keep the read-ahead at one batch: registers
 #pragma unroll
             for (int u = 0; u < kBatch; ++u) c = __builtin_amdgcn_mfma_f32_32x32x2f32(a_cur[u], b[u0 + u], c, 0, 0, 0);
+            if (more) {
 #pragma unroll
-            for (int u = 0; u < kBatch; ++u) a_cur[u] = a_nxt[u];
+                for (int u = 0; u < kBatch; ++u) a_cur[u] = a_nxt[u];
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
     };
