@@ -151,6 +151,24 @@ def test_argument_errors_are_host_side(lib):
     assert q8(0, 4, 0, fake, fake, fake, None, fake, 8, 8, 1, 1, fake, None, None, 8, None) == 0
 
 
+def test_header_and_library_from_plain_c(lib, tmp_path):
+    """include/aes_spmm.h is valid C99 and the library links and answers from a C program."""
+    import shutil
+    import subprocess
+    import paper_2503_18427_amd as aes
+    if shutil.which("gcc") is None:
+        pytest.skip("gcc not available")
+    from paper_2503_18427_amd import build as aes_build
+    so = aes_build.LIB
+    exe = str(tmp_path / "abi_c_client")
+    cmd = ["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+           os.path.join(ROOT, "tests", "abi_c_client.c"), "-o", exe, so, "-Wl,-rpath," + os.path.dirname(so)]
+    build = subprocess.run(cmd, capture_output=True, text=True)
+    assert build.returncode == 0, build.stderr
+    run = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    assert run.returncode == 0 and "abi c client ok" in run.stdout, run.stdout + run.stderr
+
+
 def test_binding_rejects_host_tensors():
     import torch
     import paper_2503_18427_amd as aes
