@@ -280,6 +280,11 @@ def cpu_baseline(d, plan, Y, Yq, qbuf, W, scheme, gran, n_rows_sample, leg_bytes
     orc.spmm_plan(ref[0], ref[1], ref[2], X, rows=rows_st)
     t_st = time.perf_counter() - t
     orc.set_num_threads(threads)
+    # the exact (unsampled) product on the same bounded row sample, all cores: the CSR is its own W = 0 plan
+    nnz_st = int((rowptr[rows_st + 1] - rowptr[rows_st]).sum())
+    t = time.perf_counter()
+    orc.spmm_plan(rowptr, colidx, val, X, rows=rows_st)
+    t_exact = time.perf_counter() - t
 
     groups_q = {0: 1, 1: F, 2: nq}[gran]
     rate = {
@@ -310,6 +315,8 @@ def cpu_baseline(d, plan, Y, Yq, qbuf, W, scheme, gran, n_rows_sample, leg_bytes
         "leg_GBps": {k: v / 1e9 for k, v in rate.items()},
         "single_thread": {"spmm_f32_GBps": algorithmic_bytes(rows_st.size, slots_st, F, 4, False) / t_st / 1e9,
                           "rows": int(rows_st.size), "seconds": t_st},
+        "exact_spmm": {"GBps": algorithmic_bytes(rows_st.size, nnz_st, F, 4, False) / t_exact / 1e9,
+                       "rows": int(rows_st.size), "entries": nnz_st, "seconds": t_exact},
     }
     errs = {"fp32_vs_oracle": e32, "int8_vs_oracle_dequantised": e8, "plan_bit_exact": plan_ok,
             "int8_codes_and_scales_bit_exact": codes_ok,
