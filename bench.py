@@ -32,16 +32,16 @@ TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.json")
 
 def algorithmic_bytes(n_rows, S, F, elem_bytes, per_row_scale):
     """Bytes one multiply over a plan must move if nothing is reused:
-    (col, val) per slot, one feature row per slot, Y once, s_rowptr + row_perm."""
-    b = 8 * S + S * F * elem_bytes + 4 * n_rows * F + 8 * n_rows + 4 * n_rows
+    (col, val) per slot, one feature row per slot, Y once, s_rowptr (no row_perm: natural row order)."""
+    b = 8 * S + S * F * elem_bytes + 4 * n_rows * F + 8 * n_rows
     if per_row_scale:
         b += 4 * S
     return b
 
 
 def build_bytes(n_rows, S):
-    """rowptr in, sampled (col, val) in and out, s_rowptr and row_perm out."""
-    return 8 * (n_rows + 1) + 8 * S + 8 * S + 8 * (n_rows + 1) + 4 * n_rows
+    """rowptr in, sampled (col, val) in and out, s_rowptr out (no row_perm requested)."""
+    return 8 * (n_rows + 1) + 8 * S + 8 * S + 8 * (n_rows + 1)
 
 
 def quantize_bytes(n, F, groups):
@@ -156,7 +156,7 @@ def main() -> int:
             traffic = None
     # Compulsory traffic with a perfect cache: every distinct feature row once.
     distinct_cols = int(torch.unique(plan.s_col[:S]).numel()) if S > 0 else 0
-    compulsory = 8 * S + distinct_cols * F * 4 + 4 * n * F + 12 * n
+    compulsory = 8 * S + distinct_cols * F * 4 + 4 * n * F + 8 * n
     t_min_ms = compulsory / (HBM_PEAK_GBPS * 1e9) * 1e3
     roofline = {
         "kernel": "spmm_rows_kernel (aes_spmm_f32)",

@@ -74,7 +74,7 @@ def _rel_fro(Y: torch.Tensor, Yex: torch.Tensor) -> float:
 
 
 def _bytes(n, S, F, e, per_row_scale=False):
-    return 8 * S + S * F * e + 4 * n * F + 12 * n + (4 * S if per_row_scale else 0)
+    return 8 * S + S * F * e + 4 * n * F + 8 * n + (4 * S if per_row_scale else 0)
 
 
 def _vendor_exact(d, Yex) -> str:
