@@ -51,16 +51,16 @@ gcn_layer_kernel(int64_t n_rows, SlotSource src, const typename Feat::elem_t *__
     for (int rr = wave * kGroups + group; rr < kTileRows; rr += kGroupsPerBlock) {
         const int64_t r = row0 + rr;
         float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-        float side = 0.0f, vsum = 0.0f;
+        float side = 0.0f;
         if (r < n_rows) {
             const RowInfo ri = row_info<false>(src, r);
             accumulate_tiles<LPR, 8, Feat, QMODE, QUANT, false, float>(src, ri, stage[wave][group], lane, lane_on, X, ldx, f,
-                                                                       qp, 0, 1, acc, side, vsum);
+                                                                       qp, 0, 1, acc, side);
         }
         if (QUANT && qp.affine) side = group_sum<LPR, float>(side);
         if (lane_on) {
             float y[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-            if (r < n_rows) finish_values<Feat, QMODE, QUANT, float>(acc, side, vsum, f, qp, r, y);
+            if (r < n_rows) finish_values<Feat, QMODE, QUANT, float>(acc, side, f, qp, r, y);
 #pragma unroll
             for (int i = 0; i < 4; ++i) ys[rr * y_stride + f + i] = y[i];
         }

@@ -46,17 +46,13 @@ __device__ inline double fma_acc(float a, float b, double acc)
 }
 
 // ---- feature loaders: VEC consecutive features of one row of X --------------
-// fma(acc, v, x) adds v * (feature + kBias) to acc; the kernel removes
-// kBias * sum(v) in its epilogue.  kBias = 128 lets signed 8-bit codes be
-// converted as unsigned bytes (one conversion instruction per byte, after one
-// XOR per four bytes) instead of sign-extending each byte first.
+// fma(acc, v, x) adds v * feature to acc for each of the VEC features.
 //
 // The vector loads and stores only assume the alignment of one element (Float4U / Word1U),
 // so any leading dimension takes the vector path.
 template <int VEC_> struct FeatF32;
 template <> struct FeatF32<4> {
     static constexpr int VEC = 4;
-    static constexpr int kBias = 0;
     using elem_t = float;
     using raw_t = Float4U;
     static __device__ inline raw_t load(const elem_t *p) { return *reinterpret_cast<const Float4U *>(p); }
@@ -71,7 +67,6 @@ template <> struct FeatF32<4> {
 };
 template <> struct FeatF32<1> {
     static constexpr int VEC = 1;
-    static constexpr int kBias = 0;
     using elem_t = float;
     using raw_t = float;
     static __device__ inline raw_t load(const elem_t *p) { return *p; }
@@ -79,21 +74,27 @@ template <> struct FeatF32<1> {
     static __device__ inline void fma(AccT (&acc)[1], float v, const raw_t &x) { acc[0] = fma_acc(v, x, acc[0]); }
 };
 
-// Four packed bytes -> four floats (unsigned; signed codes arrive biased by 128).
+// Four packed bytes -> four floats: one conversion instruction per byte, which selects its byte and, for
+// signed codes, sign-extends it (v_cvt_f32_ubyteN / v_cvt_f32_i32 with a byte selector).
 template <bool SIGNED, typename AccT>
 __device__ inline void fma_bytes(AccT *acc, float v, uint32_t w)
 {
-    if (SIGNED) w ^= 0x80808080u;
-    acc[0] = fma_acc(v, static_cast<float>(w & 0xffu), acc[0]);
-    acc[1] = fma_acc(v, static_cast<float>((w >> 8) & 0xffu), acc[1]);
-    acc[2] = fma_acc(v, static_cast<float>((w >> 16) & 0xffu), acc[2]);
-    acc[3] = fma_acc(v, static_cast<float>(w >> 24), acc[3]);
+    if (SIGNED) {
+        acc[0] = fma_acc(v, static_cast<float>(static_cast<int8_t>(w & 0xffu)), acc[0]);
+        acc[1] = fma_acc(v, static_cast<float>(static_cast<int8_t>((w >> 8) & 0xffu)), acc[1]);
+        acc[2] = fma_acc(v, static_cast<float>(static_cast<int8_t>((w >> 16) & 0xffu)), acc[2]);
+        acc[3] = fma_acc(v, static_cast<float>(static_cast<int8_t>(w >> 24)), acc[3]);
+    } else {
+        acc[0] = fma_acc(v, static_cast<float>(w & 0xffu), acc[0]);
+        acc[1] = fma_acc(v, static_cast<float>((w >> 8) & 0xffu), acc[1]);
+        acc[2] = fma_acc(v, static_cast<float>((w >> 16) & 0xffu), acc[2]);
+        acc[3] = fma_acc(v, static_cast<float>(w >> 24), acc[3]);
+    }
 }
 
 template <int VEC_, bool SIGNED> struct FeatQ8;
 template <bool SIGNED> struct FeatQ8<4, SIGNED> {
     static constexpr int VEC = 4;
-    static constexpr int kBias = SIGNED ? 128 : 0;
     using elem_t = int8_t;
     using raw_t = uint32_t;
     static __device__ inline raw_t load(const elem_t *p) { return reinterpret_cast<const Word1U *>(p)->v; }
@@ -102,7 +103,6 @@ template <bool SIGNED> struct FeatQ8<4, SIGNED> {
 };
 template <bool SIGNED> struct FeatQ8<1, SIGNED> {
     static constexpr int VEC = 1;
-    static constexpr int kBias = 0;
     using elem_t = int8_t;
     using raw_t = int8_t;
     static __device__ inline raw_t load(const elem_t *p) { return *p; }
@@ -156,13 +156,12 @@ __device__ inline RowInfo row_info(const SlotSource &src, int64_t r)
 }
 
 // Adds the row's tiles first_tile, first_tile + tile_step, ... into acc (one chunk of
-// features).  side / vsum collect the sums the 8-bit epilogue needs.
+// features).  side collects the zero-point sum the affine 8-bit epilogue needs.
 template <int LPR, int UNROLL, typename Feat, int QMODE, bool QUANT, bool FUSED, typename AccT>
 __device__ __forceinline__ void accumulate_tiles(const SlotSource &src, const RowInfo &ri, int2 *my_stage, int lane,
                                                  bool lane_on, const typename Feat::elem_t *__restrict__ X,
                                                  int64_t ldx, int32_t f, const QParams &qp, int64_t first_tile,
-                                                 int64_t tile_step, AccT (&acc)[Feat::VEC], AccT &side,
-                                                 AccT &vsum)
+                                                 int64_t tile_step, AccT (&acc)[Feat::VEC], AccT &side)
 {
     // Column indices are non-negative and the host has checked ldx < 2^32: the row offset is one
     // 32 x 32 -> 64-bit multiply-add per gather instead of a sign-extended 64 x 64-bit product.
@@ -204,10 +203,7 @@ __device__ __forceinline__ void accumulate_tiles(const SlotSource &src, const Ro
 #pragma unroll
                 for (int u = 0; u < UNROLL; ++u) x[u] = Feat::load(row_of(cv[u].x));
 #pragma unroll
-                for (int u = 0; u < UNROLL; ++u) {
-                    Feat::fma(acc, __int_as_float(cv[u].y), x[u]);
-                    if (Feat::kBias != 0) vsum += __int_as_float(cv[u].y);
-                }
+                for (int u = 0; u < UNROLL; ++u) Feat::fma(acc, __int_as_float(cv[u].y), x[u]);
             }
             // Ragged last round: the missing slots are predicated off (value 0, no load), so
             // short rows and row tails keep their gathers in flight together as well.
@@ -222,29 +218,22 @@ __device__ __forceinline__ void accumulate_tiles(const SlotSource &src, const Ro
                     if (cv[u].x >= 0) x[u] = Feat::load(row_of(cv[u].x));
                 }
 #pragma unroll
-                for (int u = 0; u < UNROLL; ++u) {
-                    Feat::fma(acc, __int_as_float(cv[u].y), x[u]);
-                    if (Feat::kBias != 0) vsum += __int_as_float(cv[u].y);
-                }
+                for (int u = 0; u < UNROLL; ++u) Feat::fma(acc, __int_as_float(cv[u].y), x[u]);
             }
         }
     }
 }
 
-// Removes the loader's bias and applies the 8-bit group constants to one chunk of a row:
+// Applies the 8-bit group constants to one chunk of a row:
 // out[] holds the finished float32 values of features f .. f + VEC - 1 of row r.
 // `side` must already be summed over the lanes of the group.
 template <typename Feat, int QMODE, bool QUANT, typename AccT>
-__device__ __forceinline__ void finish_values(const AccT (&acc_in)[Feat::VEC], AccT side_in, AccT vsum, int32_t f,
+__device__ __forceinline__ void finish_values(const AccT (&acc_in)[Feat::VEC], AccT side_in, int32_t f,
                                               const QParams &qp, int64_t r, float (&out)[Feat::VEC])
 {
     constexpr int VEC = Feat::VEC;
 #pragma unroll
-    for (int i = 0; i < VEC; ++i) {
-        AccT a = acc_in[i];
-        if (Feat::kBias != 0) a = a - static_cast<AccT>(Feat::kBias) * vsum;   // exact product, one rounding
-        out[i] = static_cast<float>(a);
-    }
+    for (int i = 0; i < VEC; ++i) out[i] = static_cast<float>(acc_in[i]);
     const float side = static_cast<float>(side_in);
     if (QUANT) {
         // x_hat = q*scale_g + zero_g, with the group constants taken out of the sum:
@@ -267,13 +256,13 @@ __device__ __forceinline__ void finish_values(const AccT (&acc_in)[Feat::VEC], A
 
 // finish_values, then the store of the chunk to Y[r, f ...] (16-byte stores, 4-byte aligned, on the vector paths).
 template <typename Feat, int QMODE, bool QUANT, typename AccT>
-__device__ __forceinline__ void finish_chunk(const AccT (&acc_in)[Feat::VEC], AccT side_in, AccT vsum, bool lane_on,
+__device__ __forceinline__ void finish_chunk(const AccT (&acc_in)[Feat::VEC], AccT side_in, bool lane_on,
                                              int32_t f, const QParams &qp, int64_t r, float *__restrict__ y)
 {
     constexpr int VEC = Feat::VEC;
     if (!lane_on) return;
     float acc[VEC];
-    finish_values<Feat, QMODE, QUANT, AccT>(acc_in, side_in, vsum, f, qp, r, acc);
+    finish_values<Feat, QMODE, QUANT, AccT>(acc_in, side_in, f, qp, r, acc);
     if constexpr (VEC % 4 == 0) {
 #pragma unroll
         for (int i = 0; i < VEC; i += 4)

@@ -76,18 +76,17 @@ spmm_rows_kernel(int64_t n_rows, SlotSource src, const int32_t *__restrict__ row
 #pragma unroll
             for (int i = 0; i < VEC; ++i) acc[i] = 0.0f;
             float side = 0.0f;      // this lane's share of sum(val * zero-point weight)
-            float vsum = 0.0f;      // sum of the staged edge values (only when the loader is biased)
             accumulate_tiles<LPR, UNROLL, Feat, QMODE, QUANT, FUSED, float>(src, ri, my_stage, lane, lane_on, X, ldx, f,
-                                                                            qp, 0, 1, acc, side, vsum);
+                                                                            qp, 0, 1, acc, side);
             if (QUANT && qp.affine) side = group_sum<LPR, float>(side);
-            finish_chunk<Feat, QMODE, QUANT, float>(acc, side, vsum, lane_on, f, qp, r, Y + r * ldy + f);
+            finish_chunk<Feat, QMODE, QUANT, float>(acc, side, lane_on, f, qp, r, Y + r * ldy + f);
         }
     }
 
     if constexpr (LONG) {
         __shared__ int sh_n_long;
         __shared__ int64_t sh_long_row[kRowsPerBlock];
-        __shared__ double sh_part[kRowsPerBlock][LPR][VEC + 2];
+        __shared__ double sh_part[kRowsPerBlock][LPR][VEC + 1];
         if (threadIdx.x == 0) sh_n_long = 0;
         __syncthreads();
         if (is_long && lane == 0) sh_long_row[atomicAdd(&sh_n_long, 1)] = r;   // order affects no sum
@@ -103,24 +102,22 @@ spmm_rows_kernel(int64_t n_rows, SlotSource src, const int32_t *__restrict__ row
                 double acc[VEC];                         // long sums are carried in float64
 #pragma unroll
                 for (int j = 0; j < VEC; ++j) acc[j] = 0.0;
-                double side = 0.0, vsum = 0.0;
+                double side = 0.0;
                 accumulate_tiles<LPR, UNROLL, Feat, QMODE, QUANT, FUSED, double>(src, lri, my_stage, lane, lane_on, X,
                                                                                  ldx, f, qp, gib, kRowsPerBlock, acc,
-                                                                                 side, vsum);
+                                                                                 side);
                 if (QUANT && qp.affine) side = group_sum<LPR, double>(side);
 #pragma unroll
                 for (int j = 0; j < VEC; ++j) sh_part[gib][lane][j] = acc[j];
                 sh_part[gib][lane][VEC] = side;
-                sh_part[gib][lane][VEC + 1] = vsum;
                 __syncthreads();
                 if (gib == 0) {
                     for (int g = 1; g < kRowsPerBlock; ++g) {   // fixed order: bit-reproducible
 #pragma unroll
                         for (int j = 0; j < VEC; ++j) acc[j] += sh_part[g][lane][j];
                         side += sh_part[g][lane][VEC];
-                        vsum += sh_part[g][lane][VEC + 1];
                     }
-                    finish_chunk<Feat, QMODE, QUANT, double>(acc, side, vsum, lane_on, f, qp, lr, Y + lr * ldy + f);
+                    finish_chunk<Feat, QMODE, QUANT, double>(acc, side, lane_on, f, qp, lr, Y + lr * ldy + f);
                 }
                 __syncthreads();
             }
