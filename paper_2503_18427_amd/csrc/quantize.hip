@@ -302,7 +302,7 @@ tensor_fold_kernel(int32_t F, int affine_, float *__restrict__ lo_io, float *__r
     sh_lo[threadIdx.x] = lo;
     sh_hi[threadIdx.x] = hi;
     __syncthreads();
-    for (int s = kBlock / 2; s >= 1; s >>= 1) {
+    for (unsigned s = kBlock / 2; s >= 1; s >>= 1) {
         if (threadIdx.x < s) {
             sh_lo[threadIdx.x] = fminf(sh_lo[threadIdx.x], sh_lo[threadIdx.x + s]);
             sh_hi[threadIdx.x] = fmaxf(sh_hi[threadIdx.x], sh_hi[threadIdx.x + s]);

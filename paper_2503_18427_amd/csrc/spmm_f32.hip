@@ -34,7 +34,7 @@ extern "C" int aes_spmm_f32(int64_t n_rows, int64_t n_cols, int32_t W,
                             float *Y, int64_t ldy, void *stream)
 {
     const char *what = "aes_spmm_f32";
-    if (int rc = check_common(what, n_rows, n_cols, s_rowptr, s_col, s_val, X, ldx, F, Y, ldy)) return rc;
+    if (int rc = check_common(what, n_rows, n_cols, s_rowptr, X, ldx, F, Y, ldy)) return rc;
     if (int rc = check_sampling(what, W, AES_STRATEGY_ADAPTIVE)) return rc;
     if (n_rows == 0) return AES_OK;
     const SlotSource src = {s_rowptr, s_col, s_val, W, 0, 0};   // W: only the bound on slots per row
@@ -48,7 +48,7 @@ extern "C" int aes_spmm_fused_f32(int64_t n_rows, int64_t n_cols,
                                   float *Y, int64_t ldy, void *stream)
 {
     const char *what = "aes_spmm_fused_f32";
-    if (int rc = check_common(what, n_rows, n_cols, rowptr, colidx, val, X, ldx, F, Y, ldy)) return rc;
+    if (int rc = check_common(what, n_rows, n_cols, rowptr, X, ldx, F, Y, ldy)) return rc;
     if (int rc = check_sampling(what, W, strategy)) return rc;
     if (n_rows == 0) return AES_OK;
     const SlotSource src = {rowptr, colidx, val, W, strategy, seed};

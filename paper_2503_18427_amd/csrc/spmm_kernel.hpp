@@ -175,8 +175,9 @@ inline int check_sampling(const char *what, int32_t W, int32_t strategy)
     return AES_OK;
 }
 
-inline int check_common(const char *what, int64_t n_rows, int64_t n_cols, const int64_t *s_rowptr, const int32_t *s_col,
-                 const float *s_val, const void *X, int64_t ldx, int32_t F, const float *Y, int64_t ldy)
+// s_col / s_val are not examined: they may be NULL for a plan without slots, which the host cannot see.
+inline int check_common(const char *what, int64_t n_rows, int64_t n_cols, const int64_t *s_rowptr, const void *X,
+                        int64_t ldx, int32_t F, const float *Y, int64_t ldy)
 {
     if (n_rows < 0 || n_cols < 0)
         return aes::fail(AES_ERR_INVALID_ARG, "%s: negative size (n_rows=%lld n_cols=%lld)", what, (long long)n_rows,
@@ -190,7 +191,6 @@ inline int check_common(const char *what, int64_t n_rows, int64_t n_cols, const 
         return aes::fail(AES_ERR_UNSUPPORTED, "%s: feature leading dimension %lld does not fit 32 bits", what, (long long)ldx);
     if (s_rowptr == nullptr) return aes::fail(AES_ERR_INVALID_ARG, "%s: s_rowptr is NULL", what);
     if (n_rows > 0 && Y == nullptr) return aes::fail(AES_ERR_INVALID_ARG, "%s: Y is NULL", what);
-    // s_col / s_val may be NULL only for a plan without slots; that cannot be seen from the host
     if (n_rows > 0 && n_cols > 0 && X == nullptr) return aes::fail(AES_ERR_INVALID_ARG, "%s: X is NULL", what);
     return AES_OK;
 }

@@ -148,7 +148,7 @@ extern "C" int aes_spmm_q8(int64_t n_rows, int64_t n_cols, int32_t W,
                            float *Y, int64_t ldy, void *stream)
 {
     const char *what = "aes_spmm_q8";
-    if (int rc = check_common(what, n_rows, n_cols, s_rowptr, s_col, s_val, Xq, ldq, F, Y, ldy)) return rc;
+    if (int rc = check_common(what, n_rows, n_cols, s_rowptr, Xq, ldq, F, Y, ldy)) return rc;
     if (int rc = check_sampling(what, W, AES_STRATEGY_ADAPTIVE)) return rc;
     const SlotSource src = {s_rowptr, s_col, s_val, W, 0, 0};   // W: only the bound on slots per row
     return run_q8<false>(what, n_rows, src, row_perm, Xq, ldq, F, scheme, granularity, scale, zero, Y, ldy,
@@ -164,7 +164,7 @@ extern "C" int aes_spmm_fused_q8(int64_t n_rows, int64_t n_cols,
                                  float *Y, int64_t ldy, void *stream)
 {
     const char *what = "aes_spmm_fused_q8";
-    if (int rc = check_common(what, n_rows, n_cols, rowptr, colidx, val, Xq, ldq, F, Y, ldy)) return rc;
+    if (int rc = check_common(what, n_rows, n_cols, rowptr, Xq, ldq, F, Y, ldy)) return rc;
     if (int rc = check_sampling(what, W, strategy)) return rc;
     const SlotSource src = {rowptr, colidx, val, W, strategy, seed};
     return run_q8<true>(what, n_rows, src, nullptr, Xq, ldq, F, scheme, granularity, scale, zero, Y, ldy,
