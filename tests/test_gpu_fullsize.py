@@ -19,7 +19,7 @@ def G():
     return gpu_common
 
 
-def _run(G, name, widths, exact=False, schemes=(SYM,)):
+def _run(G, name, widths, exact=False, schemes=(SYM,), layer=False):
     from workloads import configs
     d = configs.make(name, "cuda")
     w = d["workload"]
@@ -52,20 +52,44 @@ def _run(G, name, widths, exact=False, schemes=(SYM,)):
         for s in schemes:
             _, c, g = G.check_q8(plan, ref, q[s][0], q[s][1], s, w.q_granularity, rows=rows, use_perm=False)
             print(f"[{name}] W={W} int8 scheme={s} err comp={c:.2e} glob={g:.2e}", flush=True)
+        if layer and W == widths[0]:
+            _check_layer(G, name, d, plan, ref, Xh, q[SYM], w.q_granularity, rows)
         del plan, ref
     return d
 
 
+def _check_layer(G, name, d, plan, ref, Xh, q, gran, rows, Fo=64):
+    """The fused layer at full size: sampled rows of H against the oracle's aggregate-then-combine
+    in double, for float32 features and for the symmetric 8-bit codes."""
+    import oracle as orc
+    import paper_2503_18427_amd as aes
+    F = d["F"]
+    Theta = (np.random.default_rng(3).standard_normal((F, Fo)) / np.sqrt(F)).astype(np.float32)
+    Td = G.to_dev(Theta)
+    rt = torch.from_numpy(rows).cuda()
+    H = aes.aes_gcn_layer_f32(plan, d["X"], Td)
+    Hq = aes.aes_gcn_layer_q8(plan, q[0][0], SYM, gran, q[0][1], q[0][2], Td)
+    torch.cuda.synchronize()
+    Yref, Yabs = orc.spmm_plan(ref[0], ref[1], ref[2], Xh, rows=rows, want_abs=True)
+    Habs = orc.combine(Yabs, np.abs(Theta))
+    e32 = float(np.max(np.abs(H[rt].cpu().numpy() - orc.combine(Yref, Theta)) / np.where(Habs > 0, Habs, 1.0)))
+    Yqref, Yqabs = orc.spmm_q8(ref[0], ref[1], ref[2], q[1][0], SYM, gran, q[1][1], q[1][2], rows=rows, want_abs=True)
+    Hqabs = orc.combine(Yqabs, np.abs(Theta))
+    e8 = float(np.max(np.abs(Hq[rt].cpu().numpy() - orc.combine(Yqref, Theta)) / np.where(Hqabs > 0, Hqabs, 1.0)))
+    print(f"[{name}] fused layer Fo={Fo}: fp32 err {e32:.2e}, int8 err {e8:.2e}", flush=True)
+    assert e32 <= 2e-5 and e8 <= G.Q8_TOL
+
+
 def test_arxiv_like(G):
-    _run(G, "arxiv_like", (32, 64), schemes=(SYM, AFF))
+    _run(G, "arxiv_like", (32, 64), schemes=(SYM, AFF), layer=True)
 
 
 def test_products_like(G):
-    _run(G, "products_like", (64,), schemes=(SYM,))
+    _run(G, "products_like", (64,), schemes=(SYM,), layer=True)
 
 
 def test_reddit_like(G):
-    _run(G, "reddit_like", (64, 128, 256), exact=True, schemes=(SYM,))
+    _run(G, "reddit_like", (64, 128, 256), exact=True, schemes=(SYM,), layer=True)
 
 
 def test_rmat20(G):
