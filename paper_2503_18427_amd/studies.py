@@ -197,6 +197,23 @@ def loading(name: str) -> None:
               f"{(1 - tl / t_l32) * 100:.1f} % |")
     print(f"\nhost-to-device rates: fp32 {X.numel() * 4 / t_l32 / 1e6:.1f} GB/s, "
           f"8-bit {(q[0].numel() + 8 * q[1].numel()) / t_l8 / 1e6:.1f} GB/s\n")
+    # The loading share against the sampling width (the layout of the paper's Table 3): loading and the
+    # Eq. 2 pass do not depend on W, the multiply does.
+    widths = (16, 32, 64, 128, 256, 512, 1024)
+    print(f"loading share of (load + dequantise + SpMM) against W, `{name}`:\n")
+    print("| pipeline | " + " | ".join(f"W = {x}" for x in widths) + " |")
+    print("|---|" + "---|" * len(widths))
+    shares = {label: [] for label, *_ in rows}
+    for Wx in widths:
+        px = aes.aes_sample_build(d["rowptr"], d["colidx"], d["val"], n, Wx)
+        tx32 = _time_ms(lambda: aes.aes_spmm_f32(px, X_dev, Y), iters=5)
+        tx8 = _time_ms(lambda: aes.aes_spmm_q8(px, Xq_dev, scheme, gran, sc_dev, zr_dev, Y), iters=5)
+        for (label, tl, td, _), ts in zip(rows, (tx32, tx32, tx8)):
+            shares[label].append(tl / (tl + td + ts) * 100)
+        del px
+    for label, vals in shares.items():
+        print(f"| {label} | " + " | ".join(f"{v:.1f} %" for v in vals) + " |")
+    print()
 
 
 def layer(name: str) -> None:
