@@ -306,6 +306,37 @@ def test_long_rows_shared_by_the_workgroup(G, F, W):
         assert torch.equal(Yqf, Yq)
 
 
+@pytest.mark.parametrize("W", [0, 4096, 64])
+@pytest.mark.parametrize("F", [128, 24])
+def test_slot_counts_around_tile_and_unroll_boundaries(G, W, F):
+    """Rows whose slot counts sit on and next to every internal boundary of the multiply: the 8-slot
+    unrolled round, the 64-slot LDS tile, the 2048-slot hand-over to the whole workgroup; plan build,
+    plan multiply, single-kernel form, fused layer."""
+    import oracle as orc
+    import paper_2503_18427_amd as aes
+    rng = np.random.default_rng(W + F)
+    deg = np.array([1, 7, 8, 9, 15, 16, 17, 55, 56, 57, 63, 64, 65, 71, 72, 73, 127, 128, 129, 191, 192, 193, 2040,
+                    2047, 2048, 2049, 2055, 2056, 2057, 2111, 2112, 2113, 4095, 4096, 4097, 0])
+    n, n_cols = deg.size, 1200
+    rowptr, col, val = random_csr(n, n_cols, deg, rng)
+    X = rng.standard_normal((n_cols, F)).astype(np.float32)
+    plan, ref = G.check_plan(rowptr, col, val, n_cols, W, 0)
+    Y, _, _ = G.check_f32(plan, ref, X, use_perm=False)
+    d = [G.to_dev(a) for a in (rowptr, col, val)]
+    Yf = aes.aes_spmm_fused_f32(d[0], d[1], d[2], n_cols, W, G.to_dev(X))
+    torch.cuda.synchronize()
+    assert torch.equal(Yf, Y)
+    qd, qr = G.check_quantize(X, SYM, COLUMN)
+    G.check_q8(plan, ref, qd, qr, SYM, COLUMN, use_perm=False)
+    Theta = (rng.standard_normal((F, 40)) / np.sqrt(F)).astype(np.float32)
+    H = aes.aes_gcn_layer_f32(plan, G.to_dev(X), G.to_dev(Theta))
+    torch.cuda.synchronize()
+    Yref, Yabs = orc.spmm_plan(ref[0], ref[1], ref[2], X, want_abs=True)
+    Habs = orc.combine(Yabs, np.abs(Theta))
+    err = np.abs(H.cpu().numpy() - orc.combine(Yref, Theta)) / np.where(Habs > 0, Habs, 1.0)
+    assert float(err.max()) <= 2e-5, float(err.max())
+
+
 @pytest.mark.parametrize("F,Fo", [(128, 128), (256, 256), (64, 32), (32, 200), (100, 48), (8, 1), (256, 64), (128, 33)])
 def test_gcn_layer_fused_with_matrix_cores(G, F, Fo):
     """Aggregation + combination in one kernel against the oracle (double), with
