@@ -138,6 +138,30 @@ int aes_sample_build(int64_t n_rows, int64_t n_cols, int64_t nnz,
                      int32_t *row_perm,
                      void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * aes_sample_build for callers that cannot allocate device memory and have no
+ * workspace to hand over: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments (minus the workspace), same
+ * kernels, same results bit for bit; the workspace is a fixed array inside the
+ * library's code object (2 228 232 bytes, resident on every GPU the library is
+ * used on until the process ends) whose device address is looked up once per
+ * device, on the first call made with that device current.  The call allocates
+ * and frees nothing.
+ *
+ *   n_rows          at most AES_NOALLOC_MAX_ROWS, else AES_ERR_UNSUPPORTED
+ *                   (nothing is launched)
+ * All calls on one GPU share that GPU's array: calls that may overlap in time
+ * (different streams, different host threads) race on it and must be
+ * serialised by the caller.  Nothing in it has to survive or be cleared between
+ * calls: every element a kernel reads is written earlier in the same call.
+ */
+enum { AES_NOALLOC_MAX_ROWS = 1 << 24 };
+int aes_sample_build_noalloc(int64_t n_rows, int64_t n_cols, int64_t nnz,
+                             const int64_t *rowptr, const int32_t *colidx, const float *val,
+                             int32_t W, uint64_t seed, int32_t strategy,
+                             int64_t *s_rowptr, int32_t *s_col, float *s_val, int64_t *s_eid,
+                             int32_t *row_perm, void *stream);
+
 /* ------------------------------------------------------------------------- */
 /* Multiply stage (Algorithm 1, accumulation loop) on a plan                   */
 

@@ -7,6 +7,7 @@ There is no CPU or eager fallback: if the library is missing or cannot be
 loaded the import of a function's first call raises.
 """
 from .binding import (  # noqa: F401
+    AES_NOALLOC_MAX_ROWS,
     AES_Q_AFFINE_FLOOR_U8,
     AES_Q_PER_COLUMN,
     AES_Q_PER_ROW,
@@ -26,6 +27,7 @@ from .binding import (  # noqa: F401
     aes_quantize_features,
     aes_quantize_workspace_bytes,
     aes_sample_build,
+    aes_sample_build_noalloc,
     aes_sample_capacity,
     aes_sample_workspace_bytes,
     aes_spmm_f32,

@@ -13,6 +13,7 @@ AES_OK, AES_ERR_INVALID_ARG, AES_ERR_UNSUPPORTED, AES_ERR_WORKSPACE, AES_ERR_HIP
 AES_Q_PER_TENSOR, AES_Q_PER_COLUMN, AES_Q_PER_ROW, AES_Q_PER_ROW_FOLDED = 0, 1, 2, 3
 AES_Q_AFFINE_FLOOR_U8, AES_Q_SYMMETRIC_RNE_I8 = 0, 1
 AES_STRATEGY_ADAPTIVE, AES_STRATEGY_AFS, AES_STRATEGY_SFS = 0, 1, 2
+AES_NOALLOC_MAX_ROWS = 1 << 24
 
 _i64, _i32, _u64, _vp, _sz = ctypes.c_int64, ctypes.c_int32, ctypes.c_uint64, ctypes.c_void_p, ctypes.c_size_t
 
@@ -23,6 +24,8 @@ SIGNATURES = {
     "aes_sample_workspace_bytes": (_sz, [_i64]),
     "aes_sample_build": (ctypes.c_int, [_i64, _i64, _i64, _vp, _vp, _vp, _i32, _u64, _i32, _vp, _vp, _vp, _vp, _vp,
                                         _vp, _sz, _vp]),
+    "aes_sample_build_noalloc": (ctypes.c_int, [_i64, _i64, _i64, _vp, _vp, _vp, _i32, _u64, _i32, _vp, _vp, _vp, _vp,
+                                                _vp, _vp]),
     "aes_spmm_fused_f32": (ctypes.c_int, [_i64, _i64, _vp, _vp, _vp, _i32, _u64, _i32, _vp, _i64, _i32, _vp, _i64,
                                           _vp]),
     "aes_spmm_fused_q8": (ctypes.c_int, [_i64, _i64, _vp, _vp, _vp, _i32, _u64, _i32, _vp, _i64, _i32, _i32, _i32,
@@ -161,6 +164,25 @@ def aes_sample_build(rowptr, colidx, val, n_cols: int, W: int, seed: int = 0, *,
                                       int(seed) & (2 ** 64 - 1), int(strategy), _ptr(out.s_rowptr), _ptr(out.s_col),
                                       _ptr(out.s_val), _ptr(out.s_eid), _ptr(out.row_perm), _ptr(workspace),
                                       workspace.numel(), _stream(stream)))
+    return out._replace(n_rows=n_rows, n_cols=int(n_cols), W=int(W))
+
+
+def aes_sample_build_noalloc(rowptr, colidx, val, n_cols: int, W: int, seed: int = 0, *, out: Plan,
+                             strategy: int = AES_STRATEGY_ADAPTIVE, stream=None) -> Plan:
+    """aes_sample_build without a workspace and without any allocation: the plan buffers `out`
+    are the caller's, the scratch is the library's built-in array (at most AES_NOALLOC_MAX_ROWS rows)."""
+    rowptr, colidx, val = _csr(rowptr, colidx, val)
+    n_rows = rowptr.numel() - 1
+    nnz = colidx.numel()
+    cap = aes_sample_capacity(n_rows, nnz, W)
+    if out.s_rowptr.numel() < n_rows + 1 or out.s_col.numel() < cap or out.s_val.numel() < cap:
+        raise ValueError("out: plan buffers too small")
+    if (out.s_eid is not None and out.s_eid.numel() < cap) or (out.row_perm is not None and out.row_perm.numel() < n_rows):
+        raise ValueError("out: s_eid / row_perm too small")
+    _check(library().aes_sample_build_noalloc(n_rows, int(n_cols), nnz, _ptr(rowptr), _ptr(colidx), _ptr(val), int(W),
+                                              int(seed) & (2 ** 64 - 1), int(strategy), _ptr(out.s_rowptr),
+                                              _ptr(out.s_col), _ptr(out.s_val), _ptr(out.s_eid), _ptr(out.row_perm),
+                                              _stream(stream)))
     return out._replace(n_rows=n_rows, n_cols=int(n_cols), W=int(W))
 
 

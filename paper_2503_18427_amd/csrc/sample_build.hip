@@ -10,8 +10,18 @@
 //   2 scan     : exclusive scans of the block totals and of the histogram
 //   3 offsets  : s_rowptr and the class-ordered row permutation
 //   4 sample   : one thread per output slot copies / samples a (col, val) pair
+#include <mutex>
+
 #include "aes_common.hpp"
 #include "aes_sampling.hpp"
+
+// Scratch of aes_sample_build_noalloc: the workspace of a build of up to AES_NOALLOC_MAX_ROWS rows,
+// part of the code object, so every GPU the library runs on holds its own copy until the process
+// ends.  In host code this name is only a handle for hipGetSymbolAddress; the device address that
+// call yields (one per device) is what kernels receive.  No attribute may keep the symbol local to
+// the code object: the runtime finds it by name.
+constexpr size_t kScratchBytes = 2228232;   // the workspace of AES_NOALLOC_MAX_ROWS rows (asserted where it is used)
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
 
 namespace {
 
@@ -24,6 +34,14 @@ constexpr int kRowsPerBlock = kBlock * kSubTiles;     // 1024
 constexpr int kClasses = 32;                          // class = bit length of the slot count
 constexpr int kScanThreads = 1024;
 constexpr int kScanItems = 8;
+
+// Workspace layout of one build: block slot totals (nblk + 1 int64), then the class histogram
+// (kClasses * nblk int32), nblk = ceil(n_rows / kRowsPerBlock).
+constexpr size_t workspace_bytes_for(int64_t n_rows)
+{
+    return static_cast<size_t>(8 * ((n_rows + kRowsPerBlock - 1) / kRowsPerBlock + 1) +
+                               4 * static_cast<int64_t>(kClasses) * ((n_rows + kRowsPerBlock - 1) / kRowsPerBlock));
+}
 
 __device__ inline int slot_class(int64_t slots)
 {
@@ -323,6 +341,68 @@ int bit_length(int64_t v)
     return b;
 }
 
+// Argument checks of both entry points (everything but the workspace).
+int check_build_args(const char *what, int64_t n_rows, int64_t n_cols, int64_t nnz, const int64_t *rowptr,
+                     const int32_t *colidx, const float *val, int32_t W, int32_t strategy, const int64_t *s_rowptr,
+                     const int32_t *s_col, const float *s_val, const int32_t *row_perm)
+{
+    if (n_rows < 0 || n_cols < 0 || nnz < 0)
+        return aes::fail(AES_ERR_INVALID_ARG, "%s: negative size (n_rows=%lld n_cols=%lld nnz=%lld)", what,
+                         (long long)n_rows, (long long)n_cols, (long long)nnz);
+    if (n_cols > INT32_MAX)
+        return aes::fail(AES_ERR_UNSUPPORTED, "%s: n_cols=%lld does not fit int32 column indices", what,
+                         (long long)n_cols);
+    if (W < 0 || W > AES_MAX_W) return aes::fail(AES_ERR_INVALID_ARG, "%s: W=%d outside 0..%d", what, (int)W, (int)AES_MAX_W);
+    if (strategy < AES_STRATEGY_ADAPTIVE || strategy > AES_STRATEGY_SFS)
+        return aes::fail(AES_ERR_INVALID_ARG, "%s: unknown strategy %d", what, (int)strategy);
+    if (rowptr == nullptr || s_rowptr == nullptr) return aes::fail(AES_ERR_INVALID_ARG, "%s: rowptr / s_rowptr is NULL", what);
+    if (nnz > 0 && (colidx == nullptr || val == nullptr || s_col == nullptr || s_val == nullptr))
+        return aes::fail(AES_ERR_INVALID_ARG, "%s: colidx / val / s_col / s_val is NULL with nnz > 0", what);
+    if (row_perm != nullptr && n_rows > INT32_MAX) return aes::fail(AES_ERR_UNSUPPORTED, "%s: row_perm needs n_rows < 2^31", what);
+    if (aes::ceil_div(n_rows, kRowsPerBlock) > INT32_MAX || aes::ceil_div(n_rows, kSampleRows) > INT32_MAX)
+        return aes::fail(AES_ERR_UNSUPPORTED, "%s: n_rows=%lld too large", what, (long long)n_rows);
+    return AES_OK;
+}
+
+// The four launches; `workspace` holds aes_sample_workspace_bytes(n_rows) bytes, 8-byte aligned.
+// Every workspace element a kernel reads has been written by an earlier kernel of the same call
+// (block totals by classify, the histogram by classify when a permutation is wanted), so the
+// workspace needs no clearing, whatever an earlier call left in it.
+int enqueue_build(const char *what, int64_t n_rows, int64_t nnz, const int64_t *rowptr, const int32_t *colidx,
+                  const float *val, int32_t W, uint64_t seed, int32_t strategy, int64_t *s_rowptr, int32_t *s_col,
+                  float *s_val, int64_t *s_eid, int32_t *row_perm, void *workspace, hipStream_t stream)
+{
+    const int64_t nblk = aes::ceil_div(n_rows, kRowsPerBlock);
+    int64_t *blk_slots = static_cast<int64_t *>(workspace);            // nblk + 1
+    int32_t *hist = reinterpret_cast<int32_t *>(blk_slots + nblk + 1);  // kClasses * nblk
+    const int want_hist = row_perm != nullptr ? 1 : 0;
+    const int n_classes = W == 0 ? kClasses : bit_length(W) + 1;        // slot counts are <= W
+    char stage[96];
+
+    if (nblk > 0) {
+        classify_kernel<<<dim3(static_cast<unsigned>(nblk)), dim3(kBlock), 0, stream>>>(
+            n_rows, rowptr, W, strategy, nblk, blk_slots, hist, want_hist);
+        snprintf(stage, sizeof stage, "%s/classify", what);
+        if (int rc = aes::check_launch(stage)) return rc;
+    }
+    scan_kernel<<<dim3(1), dim3(kScanThreads), 0, stream>>>(n_rows, nblk, blk_slots,
+                                                            want_hist ? hist : nullptr, n_classes, s_rowptr);
+    snprintf(stage, sizeof stage, "%s/scan", what);
+    if (int rc = aes::check_launch(stage)) return rc;
+    if (nblk == 0) return AES_OK;
+    offsets_kernel<<<dim3(static_cast<unsigned>(nblk)), dim3(kBlock), 0, stream>>>(
+        n_rows, rowptr, W, strategy, nblk, blk_slots, hist, n_classes, s_rowptr, row_perm);
+    snprintf(stage, sizeof stage, "%s/offsets", what);
+    if (int rc = aes::check_launch(stage)) return rc;
+    if (nnz == 0) return AES_OK;
+
+    const int64_t sample_blocks = aes::ceil_div(n_rows, kSampleRows);
+    sample_slots_kernel<<<dim3(static_cast<unsigned>(sample_blocks)), dim3(kBlock), 0, stream>>>(
+        n_rows, rowptr, colidx, val, W, seed, strategy, s_rowptr, s_col, s_val, s_eid);
+    snprintf(stage, sizeof stage, "%s/sample", what);
+    return aes::check_launch(stage);
+}
+
 }  // namespace
 
 extern "C" int64_t aes_sample_capacity(int64_t n_rows, int64_t nnz, int32_t W)
@@ -340,8 +420,7 @@ extern "C" int64_t aes_sample_capacity(int64_t n_rows, int64_t nnz, int32_t W)
 extern "C" size_t aes_sample_workspace_bytes(int64_t n_rows)
 {
     if (n_rows < 0) return 0;
-    const int64_t nblk = aes::ceil_div(n_rows, kRowsPerBlock);
-    return static_cast<size_t>(8 * (nblk + 1) + 4 * static_cast<int64_t>(kClasses) * nblk);
+    return workspace_bytes_for(n_rows);
 }
 
 extern "C" int aes_sample_build(int64_t n_rows, int64_t n_cols, int64_t nnz,
@@ -351,56 +430,69 @@ extern "C" int aes_sample_build(int64_t n_rows, int64_t n_cols, int64_t nnz,
                                 int32_t *row_perm,
                                 void *workspace, size_t workspace_bytes, void *stream_)
 {
-    if (n_rows < 0 || n_cols < 0 || nnz < 0)
-        return aes::fail(AES_ERR_INVALID_ARG, "aes_sample_build: negative size (n_rows=%lld n_cols=%lld nnz=%lld)",
-                         (long long)n_rows, (long long)n_cols, (long long)nnz);
-    if (n_cols > INT32_MAX)
-        return aes::fail(AES_ERR_UNSUPPORTED, "aes_sample_build: n_cols=%lld does not fit int32 column indices",
-                         (long long)n_cols);
-    if (W < 0 || W > AES_MAX_W)
-        return aes::fail(AES_ERR_INVALID_ARG, "aes_sample_build: W=%d outside 0..%d", (int)W, (int)AES_MAX_W);
-    if (strategy < AES_STRATEGY_ADAPTIVE || strategy > AES_STRATEGY_SFS)
-        return aes::fail(AES_ERR_INVALID_ARG, "aes_sample_build: unknown strategy %d", (int)strategy);
-    if (rowptr == nullptr || s_rowptr == nullptr)
-        return aes::fail(AES_ERR_INVALID_ARG, "aes_sample_build: rowptr / s_rowptr is NULL");
-    if (nnz > 0 && (colidx == nullptr || val == nullptr || s_col == nullptr || s_val == nullptr))
-        return aes::fail(AES_ERR_INVALID_ARG, "aes_sample_build: colidx / val / s_col / s_val is NULL with nnz > 0");
-    if (row_perm != nullptr && n_rows > INT32_MAX)
-        return aes::fail(AES_ERR_UNSUPPORTED, "aes_sample_build: row_perm needs n_rows < 2^31");
-    const int64_t nblk = aes::ceil_div(n_rows, kRowsPerBlock);
-    if (nblk > INT32_MAX)
-        return aes::fail(AES_ERR_UNSUPPORTED, "aes_sample_build: n_rows=%lld too large", (long long)n_rows);
+    const char *what = "aes_sample_build";
+    if (int rc = check_build_args(what, n_rows, n_cols, nnz, rowptr, colidx, val, W, strategy, s_rowptr, s_col, s_val,
+                                  row_perm))
+        return rc;
     const size_t need = aes_sample_workspace_bytes(n_rows);
     if (workspace == nullptr || workspace_bytes < need)
         return aes::fail(AES_ERR_WORKSPACE, "aes_sample_build: workspace of %zu bytes needed, %zu given%s", need,
                          workspace_bytes, workspace == nullptr ? " (NULL)" : "");
     if (!aes::aligned(workspace, 8))
         return aes::fail(AES_ERR_WORKSPACE, "aes_sample_build: workspace must be 8-byte aligned");
+    return enqueue_build(what, n_rows, nnz, rowptr, colidx, val, W, seed, strategy, s_rowptr, s_col, s_val, s_eid,
+                         row_perm, workspace, static_cast<hipStream_t>(stream_));
+}
 
-    hipStream_t stream = static_cast<hipStream_t>(stream_);
-    int64_t *blk_slots = static_cast<int64_t *>(workspace);            // nblk + 1
-    int32_t *hist = reinterpret_cast<int32_t *>(blk_slots + nblk + 1);  // kClasses * nblk
-    const int want_hist = row_perm != nullptr ? 1 : 0;
-    const int n_classes = W == 0 ? kClasses : bit_length(W) + 1;        // slot counts are <= W
+// ---- the variant that allocates nothing and takes no workspace -----------------------------
+namespace {
 
-    if (nblk > 0) {
-        classify_kernel<<<dim3(static_cast<unsigned>(nblk)), dim3(kBlock), 0, stream>>>(
-            n_rows, rowptr, W, strategy, nblk, blk_slots, hist, want_hist);
-        if (int rc = aes::check_launch("aes_sample_build/classify")) return rc;
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mutex;
+void *scratch_address[kMaxDevices];          // device address of `scratch` on each device, once resolved
+
+// Device address of this device's copy of `scratch`; resolved on the first call per device, with
+// that device current.  NULL (and the error message set) on failure.
+void *scratch_on_current_device(const char *what)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        aes::fail(AES_ERR_HIP, "%s: hipGetDevice: %s (device %d)", what, hipGetErrorString(e), dev);
+        return nullptr;
     }
-    scan_kernel<<<dim3(1), dim3(kScanThreads), 0, stream>>>(n_rows, nblk, blk_slots,
-                                                            want_hist ? hist : nullptr, n_classes, s_rowptr);
-    if (int rc = aes::check_launch("aes_sample_build/scan")) return rc;
-    if (nblk == 0) return AES_OK;
-    offsets_kernel<<<dim3(static_cast<unsigned>(nblk)), dim3(kBlock), 0, stream>>>(
-        n_rows, rowptr, W, strategy, nblk, blk_slots, hist, n_classes, s_rowptr, row_perm);
-    if (int rc = aes::check_launch("aes_sample_build/offsets")) return rc;
-    if (nnz == 0) return AES_OK;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (scratch_address[dev] == nullptr) {
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || ptr == nullptr) {
+            aes::fail(AES_ERR_HIP, "%s: hipGetSymbolAddress(scratch): %s", what, hipGetErrorString(e));
+            return nullptr;
+        }
+        scratch_address[dev] = ptr;
+    }
+    return scratch_address[dev];
+}
 
-    const int64_t sample_blocks = aes::ceil_div(n_rows, kSampleRows);
-    if (sample_blocks > INT32_MAX)
-        return aes::fail(AES_ERR_UNSUPPORTED, "aes_sample_build: n_rows=%lld too large", (long long)n_rows);
-    sample_slots_kernel<<<dim3(static_cast<unsigned>(sample_blocks)), dim3(kBlock), 0, stream>>>(
-        n_rows, rowptr, colidx, val, W, seed, strategy, s_rowptr, s_col, s_val, s_eid);
-    return aes::check_launch("aes_sample_build/sample");
+}  // namespace
+
+extern "C" int aes_sample_build_noalloc(int64_t n_rows, int64_t n_cols, int64_t nnz,
+                                        const int64_t *rowptr, const int32_t *colidx, const float *val,
+                                        int32_t W, uint64_t seed, int32_t strategy,
+                                        int64_t *s_rowptr, int32_t *s_col, float *s_val, int64_t *s_eid,
+                                        int32_t *row_perm, void *stream_)
+{
+    const char *what = "aes_sample_build_noalloc";
+    if (int rc = check_build_args(what, n_rows, n_cols, nnz, rowptr, colidx, val, W, strategy, s_rowptr, s_col, s_val,
+                                  row_perm))
+        return rc;
+    if (n_rows > AES_NOALLOC_MAX_ROWS)
+        return aes::fail(AES_ERR_UNSUPPORTED,
+                         "%s: n_rows=%lld exceeds the built-in scratch (at most %lld rows); use aes_sample_build with a "
+                         "workspace", what, (long long)n_rows, (long long)AES_NOALLOC_MAX_ROWS);
+    static_assert(workspace_bytes_for(AES_NOALLOC_MAX_ROWS) == kScratchBytes, "scratch covers the largest build");
+    void *ws = scratch_on_current_device(what);
+    if (ws == nullptr) return AES_ERR_HIP;
+    return enqueue_build(what, n_rows, nnz, rowptr, colidx, val, W, seed, strategy, s_rowptr, s_col, s_val, s_eid,
+                         row_perm, ws, static_cast<hipStream_t>(stream_));
 }

@@ -73,6 +73,12 @@ def test_argument_errors_are_host_side(lib):
 
     assert sb(4, 4, 8, fake, fake, fake, 4, 0, 3, fake, fake, fake, None, None, fake, 1 << 20, None) == -1
     assert "strategy" in aes.aes_last_error()
+    na = lib.aes_sample_build_noalloc
+    assert na(-1, 1, 0, fake, fake, fake, 4, 0, 0, fake, fake, fake, None, None, None) == -1
+    assert na(4, 4, 8, fake, fake, fake, 4, 0, 3, fake, fake, fake, None, None, None) == -1
+    assert na(4, 4, 8, None, fake, fake, 4, 0, 0, fake, fake, fake, None, None, None) == -1
+    assert na(aes.AES_NOALLOC_MAX_ROWS + 1, 4, 8, fake, fake, fake, 4, 0, 0, fake, fake, fake, None, None, None) == -2
+    assert "built-in scratch" in aes.aes_last_error()
     ff = lib.aes_spmm_fused_f32
     assert ff(4, 4, fake, fake, fake, -1, 0, 0, fake, 8, 8, fake, 8, None) == -1
     assert ff(4, 4, fake, fake, fake, 16, 0, 5, fake, 8, 8, fake, 8, None) == -1
@@ -197,3 +203,35 @@ def test_last_error_is_per_thread(lib):
     t.join()
     assert seen["before"] == "" and "aes_quantize_features" in seen["after"]
     assert aes.aes_last_error() == mine and "aes_spmm_f32" in mine
+
+
+def test_builtin_scratch_symbol_is_visible_to_the_runtime(lib, tmp_path):
+    """The device-side array behind aes_sample_build_noalloc is looked up by name at run time
+    (hipGetSymbolAddress); a symbol local to the code object cannot be found and the runtime aborts.
+    Checks the device code objects inside the built library: exactly one global `scratch` object."""
+    import shutil
+    import subprocess
+    import paper_2503_18427_amd as aes
+    bundler, readelf = "/opt/rocm/llvm/bin/clang-offload-bundler", "/opt/rocm/llvm/bin/llvm-readelf"
+    if shutil.which("objcopy") is None or not (os.path.exists(bundler) and os.path.exists(readelf)):
+        pytest.skip("binutils / LLVM tools not available")
+    fat = tmp_path / "lib.fat"
+    subprocess.run(["objcopy", "-O", "binary", "--only-section=.hip_fatbin", aes.build.lib_path(), str(fat)], check=True)
+    data = fat.read_bytes()
+    magic = b"__CLANG_OFFLOAD_BUNDLE__"
+    starts = [m.start() for m in re.finditer(re.escape(magic), data)]
+    assert starts, "no device code in the library"
+    found = []
+    for n, (a, b) in enumerate(zip(starts, starts[1:] + [len(data)])):
+        part, co = tmp_path / f"b{n}.fat", tmp_path / f"b{n}.co"
+        part.write_bytes(data[a:b])
+        subprocess.run([bundler, "--unbundle", "--type=o", f"--input={part}",
+                        "--targets=hipv4-amdgcn-amd-amdhsa--gfx950", f"--output={co}"], check=True)
+        table = subprocess.run([readelf, "-s", "--dyn-syms", str(co)], capture_output=True, text=True, check=True).stdout
+        for line in table.splitlines():
+            f = line.split()
+            if len(f) >= 8 and f[3] == "OBJECT" and f[7].endswith("scratch"):
+                found.append((f[4], int(f[2])))
+    assert found, "device array `scratch` is missing from the code objects"
+    assert all(bind == "GLOBAL" for bind, _ in found), found
+    assert {size for _, size in found} == {8 * (16384 + 1) + 4 * 32 * 16384}, found
