@@ -16,9 +16,11 @@
  *   - start-index hash ........................ Sec. 3.3, Eq. 3
  *
  * AES-SpMM is an approximation defined by its procedure, so the oracle takes
- * the procedure step by step in the paper's order and notation (row_nnz, W,
- * N, sample_cnt, start_ind, sh_col/sh_val).  It is exact SpMM only on rows
- * with row_nnz <= W.  Accumulation is in double, in slot order.
+ * the procedure's steps in the paper's order (selector, hash, sampling into the
+ * row's slots, accumulation over the slots) and the paper's names for its
+ * quantities (row_nnz, N, sample_cnt), each step written from what it computes.
+ * It is exact SpMM only on rows with row_nnz <= W.  Accumulation is in double,
+ * in slot order.
  *
  * Readings of points the paper leaves open (each also listed in the design
  * document of this repository):
@@ -146,29 +148,32 @@ int64_t orc_row_slots(int64_t row_nnz, int64_t sh_width, int mode)
 }
 
 /*
- * Algorithm 1, sampling stage, for one row: fills sh_col/sh_val (and sh_eid,
- * the index into col_ind/val each slot came from) and returns the number of
- * slots.  sh_width <= 0 means "no sampling": every element, in order.
+ * Sampling stage of Sec. 3.2 Algorithm 1 for one row, written from what it produces:
+ * a sampled row is made of sample_cnt runs, run number `run` being the N consecutive
+ * elements of the row that begin at element hash(run) (Eq. 3), and the runs are
+ * interleaved in the row's slot array - element `pos` of run `run` sits in slot
+ * pos * sample_cnt + run, so slots 0 .. sample_cnt-1 hold the first element of every
+ * run, the next sample_cnt slots the second, and so on.  A row that fits
+ * (row_nnz <= width) is the single run of all its elements.
+ * Fills slot_col / slot_val (and slot_src, the index into col_ind / val each slot was
+ * read from) and returns the number of slots.  width <= 0: no sampling.
  */
 static int64_t sample_row(int64_t rid, const int64_t *row_ptr, const int32_t *col_ind,
-                          const float *val, int64_t sh_width, uint64_t seed, int mode,
-                          int32_t *sh_col, float *sh_val, int64_t *sh_eid)
+                          const float *val, int64_t width, uint64_t seed, int mode,
+                          int32_t *slot_col, float *slot_val, int64_t *slot_src)
 {
-    int64_t row_begin = row_ptr[rid];
-    int64_t row_nnz = row_ptr[rid + 1] - row_begin;
-    if (sh_width <= 0) sh_width = row_nnz;          /* exact path */
+    const int64_t first_of_row = row_ptr[rid];
+    const int64_t row_nnz = row_ptr[rid + 1] - first_of_row;
     int64_t N, sample_cnt;
-    orc_strategy_mode(row_nnz, sh_width, mode, &N, &sample_cnt);
-    uint32_t s_r = orc_row_offset(seed, rid);
-    for (int64_t i = 0; i < sample_cnt; ++i) {
-        int64_t inc = 0;
-        int64_t start_ind = orc_hash((uint64_t)i + (uint64_t)s_r, row_nnz, N);
-        for (int64_t j = 0; j < N; ++j) {
-            int64_t e = row_begin + start_ind + j;
-            sh_col[i + inc] = col_ind[e];
-            sh_val[i + inc] = val[e];
-            if (sh_eid) sh_eid[i + inc] = e;
-            inc += sample_cnt;
+    orc_strategy_mode(row_nnz, width <= 0 ? row_nnz : width, mode, &N, &sample_cnt);
+    const uint64_t shift = orc_row_offset(seed, rid);          /* 0 at seed 0 */
+    for (int64_t run = 0; run < sample_cnt; ++run) {
+        const int64_t first = first_of_row + orc_hash((uint64_t)run + shift, row_nnz, N);
+        for (int64_t pos = 0; pos < N; ++pos) {
+            const int64_t slot = pos * sample_cnt + run;
+            slot_col[slot] = col_ind[first + pos];
+            slot_val[slot] = val[first + pos];
+            if (slot_src) slot_src[slot] = first + pos;
         }
     }
     return N * sample_cnt;
@@ -262,17 +267,18 @@ int orc_aes_spmm(int64_t n_rows, const int64_t *rows, const int64_t *row_ptr,
                 sh_val = (float *)malloc((size_t)cap * sizeof(float));
                 if (!sh_col || !sh_val) { cap = 0; failed = 1; continue; }
             }
-            int64_t W = sample_row(r, row_ptr, col_ind, val, sh_width, seed, mode, sh_col, sh_val, NULL);
+            /* the row's slots, then one output element at a time: the sum over the slots, in slot order */
+            const int64_t n_slots = sample_row(r, row_ptr, col_ind, val, sh_width, seed, mode, sh_col, sh_val, NULL);
             double *y = Y + t * ldy;
             double *ya = Yabs ? Yabs + t * ldy : NULL;
             for (int64_t c = 0; c < F; ++c) {
-                double result = 0.0, mag = 0.0;
-                for (int64_t k = 0; k < W; ++k) {
-                    double p = (double)sh_val[k] * (double)X[(int64_t)sh_col[k] * ldx + c];
-                    result += p;
-                    mag += fabs(p);
+                double sum = 0.0, mag = 0.0;
+                for (int64_t k = 0; k < n_slots; ++k) {
+                    const double term = (double)sh_val[k] * (double)X[(int64_t)sh_col[k] * ldx + c];
+                    sum += term;
+                    mag += fabs(term);
                 }
-                y[c] = result;
+                y[c] = sum;
                 if (ya) ya[c] = mag;
             }
         }
