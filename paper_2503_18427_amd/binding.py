@@ -2,6 +2,7 @@
 from __future__ import annotations
 
 import ctypes
+import functools
 import os
 from typing import NamedTuple, Optional
 
@@ -53,11 +54,12 @@ class AesError(RuntimeError):
 
 
 def library() -> ctypes.CDLL:
-    """The loaded shared library; built first if no build is present."""
+    """The loaded shared library; built first if no build is present or if the build that is present
+    was made from other sources than the ones beside it (a stale library is never loaded silently)."""
     global _lib
     if _lib is None:
         path = _build.lib_path()
-        if not os.path.exists(path):
+        if not _build.is_current():
             _build.build()
         lib = ctypes.CDLL(path)
         for name, (res, args) in SIGNATURES.items():
@@ -85,6 +87,21 @@ def _stream(stream) -> int:
     if stream is None:
         stream = torch.cuda.current_stream()
     return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _on_stream(fn):
+    """Runs a binding function with the caller's `stream=` as torch's current stream, so that every
+    tensor the function allocates itself (outputs, workspaces) belongs to the stream its kernels
+    run on: the caching allocator then cannot hand such a block to other work on another stream
+    while those kernels still use it.  A raw hipStream_t handle (an int) is wrapped, not copied."""
+    @functools.wraps(fn)
+    def wrapper(*args, stream=None, **kwargs):
+        if stream is None:
+            return fn(*args, stream=None, **kwargs)
+        s = stream if isinstance(stream, torch.cuda.Stream) else torch.cuda.ExternalStream(int(stream))
+        with torch.cuda.stream(s):
+            return fn(*args, stream=s, **kwargs)
+    return wrapper
 
 
 def _dev(t: torch.Tensor, dtype, name: str, dims: int = 1) -> torch.Tensor:
@@ -132,6 +149,7 @@ def aes_quantize_workspace_bytes(n: int, F: int, granularity: int) -> int:
     return int(library().aes_quantize_workspace_bytes(n, F, granularity))
 
 
+@_on_stream
 def aes_sample_build(rowptr, colidx, val, n_cols: int, W: int, seed: int = 0, *,
                      strategy: int = AES_STRATEGY_ADAPTIVE, want_eid: bool = False,
                      want_perm: bool = False, out: Optional[Plan] = None, workspace=None, stream=None) -> Plan:
@@ -167,6 +185,7 @@ def aes_sample_build(rowptr, colidx, val, n_cols: int, W: int, seed: int = 0, *,
     return out._replace(n_rows=n_rows, n_cols=int(n_cols), W=int(W))
 
 
+@_on_stream
 def aes_sample_build_noalloc(rowptr, colidx, val, n_cols: int, W: int, seed: int = 0, *, out: Plan,
                              strategy: int = AES_STRATEGY_ADAPTIVE, stream=None) -> Plan:
     """aes_sample_build without a workspace and without any allocation: the plan buffers `out`
@@ -186,6 +205,7 @@ def aes_sample_build_noalloc(rowptr, colidx, val, n_cols: int, W: int, seed: int
     return out._replace(n_rows=n_rows, n_cols=int(n_cols), W=int(W))
 
 
+@_on_stream
 def aes_spmm_f32(plan: Plan, X, Y=None, *, use_perm: bool = True, stream=None):
     """Y = A_s X for float32 features."""
     X = _dev(X, torch.float32, "X", 2)
@@ -203,6 +223,7 @@ def aes_spmm_f32(plan: Plan, X, Y=None, *, use_perm: bool = True, stream=None):
     return Y
 
 
+@_on_stream
 def aes_quantize_features(X, scheme: int, granularity: int, *, out=None, workspace=None, stream=None):
     """Returns (Xq, scale, zero); Xq is uint8 for the affine scheme, int8 for the symmetric one."""
     X = _dev(X, torch.float32, "X", 2)
@@ -224,6 +245,7 @@ def aes_quantize_features(X, scheme: int, granularity: int, *, out=None, workspa
     return Xq, scale, zero
 
 
+@_on_stream
 def aes_spmm_q8(plan: Plan, Xq, scheme: int, granularity: int, scale, zero=None, Y=None, *, use_perm: bool = True,
                 stream=None):
     """Y = A_s x_hat with the dequantisation fused into the gather."""
@@ -265,6 +287,7 @@ def _csr(rowptr, colidx, val):
     return rowptr, colidx, val
 
 
+@_on_stream
 def aes_spmm_fused_f32(rowptr, colidx, val, n_cols: int, W: int, X, seed: int = 0, *,
                        strategy: int = AES_STRATEGY_ADAPTIVE, Y=None, stream=None):
     """Y = A_s X with the sampling done inside the SpMM kernel (no plan)."""
@@ -284,6 +307,7 @@ def aes_spmm_fused_f32(rowptr, colidx, val, n_cols: int, W: int, X, seed: int = 
     return Y
 
 
+@_on_stream
 def aes_spmm_fused_q8(rowptr, colidx, val, n_cols: int, W: int, Xq, scheme: int, granularity: int, scale,
                       zero=None, seed: int = 0, *, strategy: int = AES_STRATEGY_ADAPTIVE, Y=None, stream=None):
     """Fused sampling + 8-bit SpMM (no plan)."""
@@ -312,6 +336,7 @@ def aes_spmm_fused_q8(rowptr, colidx, val, n_cols: int, W: int, Xq, scheme: int,
     return Y
 
 
+@_on_stream
 def aes_dequantize_features(Xq, scheme: int, granularity: int, scale, zero=None, X=None, *, stream=None):
     """Eq. 2 as a separate pass: float32 features from 8-bit codes."""
     if not isinstance(Xq, torch.Tensor) or Xq.dtype not in (torch.int8, torch.uint8):
@@ -334,6 +359,7 @@ def aes_dequantize_features(Xq, scheme: int, granularity: int, scale, zero=None,
     return X
 
 
+@_on_stream
 def aes_gcn_layer_f32(plan: Plan, X, Theta, H=None, *, stream=None):
     """H = (A_s X) Theta in one kernel (aggregation + combination of a layer)."""
     X = _dev(X, torch.float32, "X", 2)
@@ -352,6 +378,7 @@ def aes_gcn_layer_f32(plan: Plan, X, Theta, H=None, *, stream=None):
     return H
 
 
+@_on_stream
 def aes_plan_fold_row_constants(plan: Plan, scheme: int, scale, zero=None, *, s_val_folded=None, row_bias=None,
                                 stream=None):
     """Fold per-node dequantisation constants into a plan.  Returns (folded plan, row_bias or None);
@@ -372,6 +399,7 @@ def aes_plan_fold_row_constants(plan: Plan, scheme: int, scale, zero=None, *, s_
     return plan._replace(s_val=s_val_folded), (row_bias if affine else None)
 
 
+@_on_stream
 def aes_gcn_layer_q8(plan: Plan, Xq, scheme: int, granularity: int, scale, zero, Theta, H=None, *, stream=None):
     """H = (A_s x_hat) Theta with 8-bit features dequantised inside the gather."""
     if not isinstance(Xq, torch.Tensor) or Xq.dtype not in (torch.int8, torch.uint8):

@@ -22,8 +22,31 @@ HIPCC_FLAGS = [
 ]
 
 
+STAMP = LIB + ".srchash"      # hash of the sources and flags the library next to it was built from
+
+
 def lib_path() -> str:
     return LIB
+
+
+def source_hash() -> str:
+    """Hash of everything the library is built from: csrc/*, the public header, the compiler flags."""
+    import hashlib
+    h = hashlib.sha256(" ".join(HIPCC_FLAGS).encode())
+    files = sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith((".hip", ".hpp", ".cpp", ".h")))
+    for path in files + [os.path.join(ROOT, "include", "aes_spmm.h")]:
+        h.update(os.path.basename(path).encode())
+        with open(path, "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
+def is_current() -> bool:
+    """True if a built library is present and was built from the sources as they are now."""
+    if not (os.path.exists(LIB) and os.path.exists(STAMP)):
+        return False
+    with open(STAMP) as f:
+        return f.read().strip() == source_hash()
 
 
 def _compile(hipcc: str, src: str, obj: str, verbose: bool) -> None:
@@ -47,7 +70,12 @@ def build(verbose: bool = False) -> str:
     link = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-fno-gpu-rdc"] + [o for _, o in jobs] + ["-o", LIB]
     if verbose:
         print(" ".join(link), flush=True)
+    if os.path.exists(STAMP):
+        os.remove(STAMP)
+    stamp = source_hash()
     subprocess.run(link, check=True)
+    with open(STAMP, "w") as f:
+        f.write(stamp + "\n")
     return LIB
 
 

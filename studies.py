@@ -1,13 +1,13 @@
 """Measurement studies around the hot path, on one MI355X.
 
-    python -m paper_2503_18427_amd.studies width-sweep [workload]
-    python -m paper_2503_18427_amd.studies strategies  [workload]
-    python -m paper_2503_18427_amd.studies loading     [workload]
-    python -m paper_2503_18427_amd.studies layer       [workload]
-    python -m paper_2503_18427_amd.studies graph       [workload]
-    python -m paper_2503_18427_amd.studies sampling-rate [workload]
-    python -m paper_2503_18427_amd.studies folded      [workload]
-    python -m paper_2503_18427_amd.studies table-size
+    python studies.py width-sweep [workload]
+    python studies.py strategies  [workload]
+    python studies.py loading     [workload]
+    python studies.py layer       [workload]
+    python studies.py graph       [workload]
+    python studies.py sampling-rate [workload]
+    python studies.py folded      [workload]
+    python studies.py table-size
 
 They reproduce the *shape* of the paper's evaluation on the synthetic workloads
 (the paper's datasets are not available): kernel time and error against the
@@ -23,7 +23,7 @@ from __future__ import annotations
 import os
 import sys
 
-ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
@@ -77,21 +77,6 @@ def _bytes(n, S, F, e, per_row_scale=False):
     return 8 * S + S * F * e + 4 * n * F + 8 * n + (4 * S if per_row_scale else 0)
 
 
-def _vendor_exact(d, Yex) -> str:
-    """Context only: the exact product through the vendor's sparse library (torch's CSR matmul on ROCm), the
-    stand-in for the library baseline that the paper's speedups are quoted against."""
-    import warnings
-    try:
-        with warnings.catch_warnings():
-            warnings.simplefilter("ignore")
-            A = torch.sparse_csr_tensor(d["rowptr"], d["colidx"].to(torch.int64), d["val"], size=(d["n"], d["n"]))
-        Yv = A @ d["X"]
-        t = _time_ms(lambda: torch.matmul(A, d["X"]), iters=5, warmup=1)
-        return f"; vendor library CSR SpMM (torch.sparse, context only) {t:.3f} ms, agrees to {_rel_fro(Yv, Yex):.1e}"
-    except Exception as exc:      # not every build ships the sparse backend
-        return f"; vendor library CSR SpMM unavailable ({type(exc).__name__})"
-
-
 def width_sweep(name: str) -> None:
     d = configs.make(name, "cuda")
     w = d["workload"]
@@ -104,7 +89,7 @@ def width_sweep(name: str) -> None:
     t_ex = _time_ms(lambda: aes.aes_spmm_f32(exact, X, Yex))
     deg = (d["rowptr"][1:] - d["rowptr"][:-1]).double()
     print(f"### width sweep, `{name}`: n = {n}, nnz = {d['nnz']}, F = {F}, exact SpMM {t_ex:.3f} ms "
-          f"({_bytes(n, d['nnz'], F, 4) / t_ex / 1e6:.0f} GB/s effective){_vendor_exact(d, Yex)}\n")
+          f"({_bytes(n, d['nnz'], F, 4) / t_ex / 1e6:.0f} GB/s effective)\n")
     print("| W | slots S | sampled rows | median / mean row sampling rate | build ms | fp32 ms (cold) | fp32 GB/s | "
           "fused fp32 ms | int8 ms (cold) | int8 GB/s | speedup vs exact | rel. Frobenius error fp32 | int8 |")
     print("|---|---|---|---|---|---|---|---|---|---|---|---|---|")
@@ -334,7 +319,7 @@ def table_size(_name=None):
     """Where the multiply saturates: a synthetic plan (2^20 rows x 32 slots, uniformly random columns, no
     reuse beyond what the table size forces) over feature tables that fit L2, the Infinity Cache, or
     neither.  Separates what the kernel can issue from what each level of the memory system delivers."""
-    from .binding import Plan
+    from paper_2503_18427_amd import Plan
     n_rows, W = 1 << 20, 32
     S = n_rows * W
     gen = torch.Generator(device="cuda")

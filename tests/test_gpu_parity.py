@@ -226,6 +226,36 @@ def test_side_stream(G):
     assert torch.equal(Y0, Y1)
 
 
+def test_explicit_stream_argument_without_workspace(G):
+    """`stream=` given explicitly (a torch stream, then its raw handle) and no workspace / output
+    passed: everything the binding allocates must belong to that stream.  The allocations are
+    provoked to be reused right away by work on the default stream; results must not change."""
+    import paper_2503_18427_amd as aes
+    rowptr, col, val, X, w = _workload("arxiv_small")
+    d = [G.to_dev(a) for a in (rowptr, col, val)]
+    Xd = G.to_dev(X)
+    plan0 = aes.aes_sample_build(d[0], d[1], d[2], w.n, 32, 0)
+    Y0 = aes.aes_spmm_f32(plan0, Xd)
+    q0 = aes.aes_quantize_features(Xd, SYM, COLUMN)
+    Yq0 = aes.aes_spmm_q8(plan0, q0[0], SYM, COLUMN, q0[1], q0[2])
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    for handle in (s, s.cuda_stream):
+        s.wait_stream(torch.cuda.current_stream())
+        plan = aes.aes_sample_build(d[0], d[1], d[2], w.n, 32, 0, stream=handle)
+        Y = aes.aes_spmm_f32(plan, Xd, stream=handle)
+        q = aes.aes_quantize_features(Xd, SYM, COLUMN, stream=handle)
+        Yq = aes.aes_spmm_q8(plan, q[0], SYM, COLUMN, q[1], q[2], stream=handle)
+        # default-stream work that would grab any block freed by the calls above
+        junk = [torch.full((1 << 16,), float(i), device="cuda") for i in range(16)]
+        s.synchronize()
+        torch.cuda.synchronize()
+        S = int(plan0.s_rowptr[-1].item())
+        assert torch.equal(plan.s_rowptr, plan0.s_rowptr) and torch.equal(plan.s_col[:S], plan0.s_col[:S])
+        assert torch.equal(Y, Y0) and torch.equal(q[0], q0[0]) and torch.equal(q[1], q0[1]) and torch.equal(Yq, Yq0)
+        del junk
+
+
 def test_hip_graph_capture_replays(G):
     """Every entry point only enqueues kernels on the caller's stream (no
     allocation, no memset, no synchronisation), so a whole step can be captured
