@@ -58,9 +58,11 @@ def library() -> ctypes.CDLL:
     was made from other sources than the ones beside it (a stale library is never loaded silently)."""
     global _lib
     if _lib is None:
-        path = _build.lib_path()
-        if not _build.is_current():
-            _build.build()
+        path = os.environ.get("AES_SPMM_LIBRARY")       # an explicitly named build is loaded as it is
+        if not path:
+            path = _build.lib_path()
+            if not _build.is_current():
+                _build.build()
         lib = ctypes.CDLL(path)
         for name, (res, args) in SIGNATURES.items():
             fn = getattr(lib, name)          # AttributeError if a declared symbol is missing
