@@ -21,13 +21,13 @@ constexpr int kMaxFeatures = 256;    // one chunk of four features per lane, at 
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-// Feat / QMODE / QUANT as in the SpMM kernel: float32 features, or 8-bit codes dequantised in the gather.
+// Feat / QMODE as in the SpMM kernel: float32 features, or 8-bit codes dequantised in the gather.
 // The register budget is set per variant.  float32: at least four waves per SIMD (the gather phase needs
 // the occupancy, and the register allocator would otherwise spend the whole file on the unrolled MFMA
 // phase).  8-bit: its gather phase is short and bound by latency, so it wants six to seven waves per SIMD
 // more than it wants a deep Theta prefetch (kChunk below): 65-75 registers, no spills.
-template <int LPR, typename Feat, int QMODE, bool QUANT>
-__global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(QUANT ? 6 : 4)))
+template <int LPR, typename Feat, int QMODE>
+__global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(QMODE != kQNone ? 6 : 4)))
 gcn_layer_kernel(int64_t n_rows, SlotSource src, const typename Feat::elem_t *__restrict__ X, int64_t ldx, int32_t F,
                  QParams qp, const float *__restrict__ Theta, int64_t ldt, int32_t Fo, float *__restrict__ H,
                  int64_t ldh)
@@ -52,15 +52,17 @@ gcn_layer_kernel(int64_t n_rows, SlotSource src, const typename Feat::elem_t *__
         const int64_t r = row0 + rr;
         float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
         float side = 0.0f;
+        LaneConstants<Feat, QMODE> k;
         if (r < n_rows) {
             const RowInfo ri = row_info<false>(src, r);
-            accumulate_tiles<LPR, 8, Feat, QMODE, QUANT, false, float>(src, ri, stage[wave][group], lane, lane_on, X, ldx, f,
-                                                                       qp, 0, 1, acc, side);
+            accumulate_tiles<LPR, 8, Feat, QMODE, false, float>(src, ri, stage[wave][group], lane, lane_on, X, ldx, f, qp, 0,
+                                                                1, acc, side);
+            load_lane_constants<Feat, QMODE>(qp, f, lane_on, r, k);
         }
-        if (QUANT && qp.affine) side = group_sum<LPR, float>(side);
+        if constexpr (QTraits<Feat, QMODE>::kAffine) side = group_sum<LPR, float>(side);
         if (lane_on) {
             float y[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-            if (r < n_rows) finish_values<Feat, QMODE, QUANT, float>(acc, side, f, qp, r, y);
+            if (r < n_rows) finish_values<Feat, QMODE, float>(acc, side, k, y);
 #pragma unroll
             for (int i = 0; i < 4; ++i) ys[rr * y_stride + f + i] = y[i];
         }
@@ -75,7 +77,7 @@ gcn_layer_kernel(int64_t n_rows, SlotSource src, const typename Feat::elem_t *__
     // because the vector memory path is saturated by the gathers of the other workgroups - passes
     // while the wave waits for the rest of the tile; a chunk's registers are refilled as soon as it
     // has been consumed.  The gather loop's registers are dead by then, so this costs no occupancy.
-    constexpr int kChunk = QUANT ? 8 : 32;
+    constexpr int kChunk = QMODE != kQNone ? 8 : 32;
     const int i = wl % 32, h = wl / 32;
     const int n_chunks = (F + 2 * kChunk - 1) / (2 * kChunk);
     float b0[kChunk], b1[kChunk];
@@ -154,7 +156,7 @@ gcn_layer_kernel(int64_t n_rows, SlotSource src, const typename Feat::elem_t *__
     }
 }
 
-template <int LPR, typename Feat, int QMODE, bool QUANT>
+template <int LPR, typename Feat, int QMODE>
 int launch_gcn(const char *what, int64_t n_rows, const SlotSource &src, const typename Feat::elem_t *X, int64_t ldx,
                int32_t F, QParams qp, const float *Theta, int64_t ldt, int32_t Fo, float *H, int64_t ldh,
                hipStream_t stream)
@@ -162,12 +164,12 @@ int launch_gcn(const char *what, int64_t n_rows, const SlotSource &src, const ty
     const int64_t grid = ceil_div(n_rows, kTileRows);
     if (grid > INT32_MAX) return fail(AES_ERR_UNSUPPORTED, "%s: n_rows=%lld too large", what, (long long)n_rows);
     const size_t shmem = static_cast<size_t>(kTileRows) * (F + 1) * sizeof(float);
-    gcn_layer_kernel<LPR, Feat, QMODE, QUANT><<<dim3(static_cast<unsigned>(grid)), dim3(kBlock), shmem, stream>>>(
+    gcn_layer_kernel<LPR, Feat, QMODE><<<dim3(static_cast<unsigned>(grid)), dim3(kBlock), shmem, stream>>>(
         n_rows, src, X, ldx, F, qp, Theta, ldt, Fo, H, ldh);
     return check_launch(what);
 }
 
-template <typename Feat, int QMODE, bool QUANT>
+template <typename Feat, int QMODE>
 int dispatch_gcn(const char *what, int64_t n_rows, const SlotSource &src, const typename Feat::elem_t *X, int64_t ldx,
                  int32_t F, QParams qp, const float *Theta, int64_t ldt, int32_t Fo, float *H, int64_t ldh,
                  hipStream_t stream)
@@ -175,10 +177,10 @@ int dispatch_gcn(const char *what, int64_t n_rows, const SlotSource &src, const 
     int l = pow2_ceil(ceil_div(F, 4));
     l = l < 8 ? 8 : l;
     switch (l) {
-        case 8: return launch_gcn<8, Feat, QMODE, QUANT>(what, n_rows, src, X, ldx, F, qp, Theta, ldt, Fo, H, ldh, stream);
-        case 16: return launch_gcn<16, Feat, QMODE, QUANT>(what, n_rows, src, X, ldx, F, qp, Theta, ldt, Fo, H, ldh, stream);
-        case 32: return launch_gcn<32, Feat, QMODE, QUANT>(what, n_rows, src, X, ldx, F, qp, Theta, ldt, Fo, H, ldh, stream);
-        default: return launch_gcn<64, Feat, QMODE, QUANT>(what, n_rows, src, X, ldx, F, qp, Theta, ldt, Fo, H, ldh, stream);
+        case 8: return launch_gcn<8, Feat, QMODE>(what, n_rows, src, X, ldx, F, qp, Theta, ldt, Fo, H, ldh, stream);
+        case 16: return launch_gcn<16, Feat, QMODE>(what, n_rows, src, X, ldx, F, qp, Theta, ldt, Fo, H, ldh, stream);
+        case 32: return launch_gcn<32, Feat, QMODE>(what, n_rows, src, X, ldx, F, qp, Theta, ldt, Fo, H, ldh, stream);
+        default: return launch_gcn<64, Feat, QMODE>(what, n_rows, src, X, ldx, F, qp, Theta, ldt, Fo, H, ldh, stream);
     }
 }
 
@@ -222,8 +224,8 @@ extern "C" int aes_gcn_layer_f32(int64_t n_rows, int64_t n_cols, int32_t W,
     if (int rc = check_layer(what, n_rows, n_cols, W, s_rowptr, X, ldx, F, Theta, ldt, Fo, H, ldh)) return rc;
     if (n_rows == 0) return AES_OK;
     const SlotSource src = {s_rowptr, s_col, s_val, W, 0, 0};
-    const QParams qp = {nullptr, nullptr, 0, 0};
-    return dispatch_gcn<FeatF32<4>, kQNone, false>(what, n_rows, src, X, ldx, F, qp, Theta, ldt, Fo, H, ldh,
+    const QParams qp = {nullptr, nullptr};
+    return dispatch_gcn<FeatF32<4>, kQNone>(what, n_rows, src, X, ldx, F, qp, Theta, ldt, Fo, H, ldh,
                                                    static_cast<hipStream_t>(stream));
 }
 
@@ -247,14 +249,14 @@ extern "C" int aes_gcn_layer_q8(int64_t n_rows, int64_t n_cols, int32_t W,
     if (n_rows == 0) return AES_OK;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     const SlotSource src = {s_rowptr, s_col, s_val, W, 0, 0};
-    const QParams qp = {scale, folded && !affine ? nullptr : zero, granularity, (affine && !folded) ? 1 : 0};
-    const bool row_scale = granularity == AES_Q_PER_ROW;
-    if (affine) {
-        if (row_scale)
-            return dispatch_gcn<FeatQ8<4, false>, kQRowScale, true>(what, n_rows, src, Xq, ldq, F, qp, Theta, ldt, Fo, H, ldh, stream);
-        return dispatch_gcn<FeatQ8<4, false>, kQNone, true>(what, n_rows, src, Xq, ldq, F, qp, Theta, ldt, Fo, H, ldh, stream);
+    const QParams qp = {scale, affine ? zero : nullptr};
+#define AES_GCN_Q8(SIGNED, MODE) \
+    dispatch_gcn<FeatQ8<4, SIGNED>, MODE>(what, n_rows, src, Xq, ldq, F, qp, Theta, ldt, Fo, H, ldh, stream)
+    switch (granularity) {
+        case AES_Q_PER_TENSOR: return affine ? AES_GCN_Q8(false, kQTensor) : AES_GCN_Q8(true, kQTensor);
+        case AES_Q_PER_COLUMN: return affine ? AES_GCN_Q8(false, kQColumn) : AES_GCN_Q8(true, kQColumn);
+        case AES_Q_PER_ROW: return affine ? AES_GCN_Q8(false, kQRowScale) : AES_GCN_Q8(true, kQRowScale);
+        default: return affine ? AES_GCN_Q8(false, kQFolded) : AES_GCN_Q8(true, kQFolded);
     }
-    if (row_scale)
-        return dispatch_gcn<FeatQ8<4, true>, kQRowScale, true>(what, n_rows, src, Xq, ldq, F, qp, Theta, ldt, Fo, H, ldh, stream);
-    return dispatch_gcn<FeatQ8<4, true>, kQNone, true>(what, n_rows, src, Xq, ldq, F, qp, Theta, ldt, Fo, H, ldh, stream);
+#undef AES_GCN_Q8
 }

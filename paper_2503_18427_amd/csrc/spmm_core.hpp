@@ -12,9 +12,14 @@ namespace aes {
 
 constexpr int kTile = 64;          // slots staged in LDS per group per round
 
+// How the constants of Eq. 2 reach an output of the 8-bit path.  Known at compile time, so that the
+// epilogue of a row is straight-line code: one vector load of constants per lane at most.
 enum QMode {
-    kQNone = 0,      // float32 features, or 8-bit features with per-tensor / per-column constants
-    kQRowScale = 1   // 8-bit features with per-row constants: folded into the staged edge value
+    kQNone = 0,      // float32 features: no constants
+    kQRowScale = 1,  // one pair per node (= per gathered row): folded into the staged edge value
+    kQTensor = 2,    // one pair for the whole matrix: applied once per output
+    kQColumn = 3,    // one pair per feature column: applied once per output
+    kQFolded = 4     // per-node pairs already multiplied into the plan's values; zero = row bias or NULL
 };
 
 // Where a row's (col, val) slots come from: a materialised plan (FUSED = false: the
@@ -30,10 +35,16 @@ struct SlotSource {
 };
 
 struct QParams {
-    const float *scale;   // per-row: indexed by column of A (= row of X)
-    const float *zero;    // may be NULL
-    int granularity;      // aes_q_granularity
-    int affine;           // 1: x_hat = q*scale + zero, q unsigned; 0: x_hat = q*scale, q signed
+    const float *scale;   // kQRowScale: indexed by column of A (= row of X); kQFolded: unused
+    const float *zero;    // NULL for signed codes; kQFolded: the row bias, or NULL
+};
+
+// Unsigned codes carry a zero point (x_hat = q*scale + zero), signed codes do not (x_hat = q*scale).
+// With folded constants the zero points already sit in the row bias: no per-slot sums are needed.
+template <typename Feat, int QMODE>
+struct QTraits {
+    static constexpr bool kQuant = QMODE != kQNone;
+    static constexpr bool kAffine = kQuant && QMODE != kQFolded && !Feat::kSigned;
 };
 
 // acc + a * b in the accumulator's precision: one fused multiply-add in float32 for
@@ -53,6 +64,7 @@ __device__ inline double fma_acc(float a, float b, double acc)
 template <int VEC_> struct FeatF32;
 template <> struct FeatF32<4> {
     static constexpr int VEC = 4;
+    static constexpr bool kSigned = true;
     using elem_t = float;
     using raw_t = Float4U;
     static __device__ inline raw_t load(const elem_t *p) { return *reinterpret_cast<const Float4U *>(p); }
@@ -67,6 +79,7 @@ template <> struct FeatF32<4> {
 };
 template <> struct FeatF32<1> {
     static constexpr int VEC = 1;
+    static constexpr bool kSigned = true;
     using elem_t = float;
     using raw_t = float;
     static __device__ inline raw_t load(const elem_t *p) { return *p; }
@@ -95,6 +108,7 @@ __device__ inline void fma_bytes(AccT *acc, float v, uint32_t w)
 template <int VEC_, bool SIGNED> struct FeatQ8;
 template <bool SIGNED> struct FeatQ8<4, SIGNED> {
     static constexpr int VEC = 4;
+    static constexpr bool kSigned = SIGNED;
     using elem_t = int8_t;
     using raw_t = uint32_t;
     static __device__ inline raw_t load(const elem_t *p) { return reinterpret_cast<const Word1U *>(p)->v; }
@@ -103,6 +117,7 @@ template <bool SIGNED> struct FeatQ8<4, SIGNED> {
 };
 template <bool SIGNED> struct FeatQ8<1, SIGNED> {
     static constexpr int VEC = 1;
+    static constexpr bool kSigned = SIGNED;
     using elem_t = int8_t;
     using raw_t = int8_t;
     static __device__ inline raw_t load(const elem_t *p) { return *p; }
@@ -157,7 +172,7 @@ __device__ inline RowInfo row_info(const SlotSource &src, int64_t r)
 
 // Adds the row's tiles first_tile, first_tile + tile_step, ... into acc (one chunk of
 // features).  side collects the zero-point sum the affine 8-bit epilogue needs.
-template <int LPR, int UNROLL, typename Feat, int QMODE, bool QUANT, bool FUSED, typename AccT>
+template <int LPR, int UNROLL, typename Feat, int QMODE, bool FUSED, typename AccT>
 __device__ __forceinline__ void accumulate_tiles(const SlotSource &src, const RowInfo &ri, int2 *my_stage, int lane,
                                                  bool lane_on, const typename Feat::elem_t *__restrict__ X,
                                                  int64_t ldx, int32_t f, const QParams &qp, int64_t first_tile,
@@ -180,13 +195,11 @@ __device__ __forceinline__ void accumulate_tiles(const SlotSource &src, const Ro
                                            static_cast<int32_t>(t0) + s);
                 const int32_t c = src.col[e];
                 float v = src.val[e];
-                if (QUANT) {
-                    if (QMODE == kQRowScale) {
-                        if (qp.affine) side = fma_acc(v, qp.zero[c], side);
-                        v *= qp.scale[c];
-                    } else if (qp.affine) {
-                        side += v;
-                    }
+                if constexpr (QMODE == kQRowScale) {
+                    if constexpr (QTraits<Feat, QMODE>::kAffine) side = fma_acc(v, qp.zero[c], side);
+                    v *= qp.scale[c];
+                } else if constexpr (QTraits<Feat, QMODE>::kAffine) {
+                    side += v;
                 }
                 my_stage[s] = make_int2(c, __float_as_int(v));
             }
@@ -224,45 +237,100 @@ __device__ __forceinline__ void accumulate_tiles(const SlotSource &src, const Ro
     }
 }
 
+// The constants one lane needs for the epilogue of its VEC features: fetched by one (vector) load per
+// array, not one dependent load per feature - on short rows the epilogue's memory round trips are a
+// large part of a row's life.
+template <typename Feat, int QMODE>
+struct LaneConstants {
+    float scale[Feat::VEC];
+    float zero[Feat::VEC];
+    bool bias;            // kQFolded: the plan comes with a row bias (held in zero[])
+};
+
+template <typename Feat, int QMODE>
+__device__ __forceinline__ void load_lane_constants(const QParams &qp, int32_t f, bool lane_on, int64_t r,
+                                                    LaneConstants<Feat, QMODE> &k)
+{
+    constexpr int VEC = Feat::VEC;
+    constexpr bool AFFINE = QTraits<Feat, QMODE>::kAffine;
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) {
+        k.scale[i] = 1.0f;
+        k.zero[i] = 0.0f;
+    }
+    k.bias = false;
+    if constexpr (QMODE == kQTensor) {
+        const float s = qp.scale[0];                 // uniform address: a scalar load
+        float z = 0.0f;
+        if constexpr (AFFINE) z = qp.zero[0];
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) {
+            k.scale[i] = s;
+            k.zero[i] = z;
+        }
+    } else if constexpr (QMODE == kQColumn) {
+        if (lane_on) {
+            if constexpr (VEC == 4) {
+                const Float4U s = *reinterpret_cast<const Float4U *>(qp.scale + f);
+                k.scale[0] = s.x; k.scale[1] = s.y; k.scale[2] = s.z; k.scale[3] = s.w;
+                if constexpr (AFFINE) {
+                    const Float4U z = *reinterpret_cast<const Float4U *>(qp.zero + f);
+                    k.zero[0] = z.x; k.zero[1] = z.y; k.zero[2] = z.z; k.zero[3] = z.w;
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) {
+                    k.scale[i] = qp.scale[f + i];
+                    if constexpr (AFFINE) k.zero[i] = qp.zero[f + i];
+                }
+            }
+        }
+    } else if constexpr (QMODE == kQFolded) {
+        if (qp.zero != nullptr) {                    // uniform: the plan carries a row bias or it does not
+            const float b = qp.zero[r];
+            k.bias = true;
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) k.zero[i] = b;
+        }
+    }
+}
+
 // Applies the 8-bit group constants to one chunk of a row:
 // out[] holds the finished float32 values of features f .. f + VEC - 1 of row r.
 // `side` must already be summed over the lanes of the group.
-template <typename Feat, int QMODE, bool QUANT, typename AccT>
-__device__ __forceinline__ void finish_values(const AccT (&acc_in)[Feat::VEC], AccT side_in, int32_t f,
-                                              const QParams &qp, int64_t r, float (&out)[Feat::VEC])
+//   per tensor / column: Y = scale_c * sum(v*q) + zero_c * sum(v)
+//   per row            : Y = sum((v*scale_col)*q) + sum(v*zero_col)
+//   folded             : Y = sum(v'*q) + bias_r
+template <typename Feat, int QMODE, typename AccT>
+__device__ __forceinline__ void finish_values(const AccT (&acc_in)[Feat::VEC], AccT side_in,
+                                              const LaneConstants<Feat, QMODE> &k, float (&out)[Feat::VEC])
 {
     constexpr int VEC = Feat::VEC;
-#pragma unroll
-    for (int i = 0; i < VEC; ++i) out[i] = static_cast<float>(acc_in[i]);
+    constexpr bool AFFINE = QTraits<Feat, QMODE>::kAffine;
     const float side = static_cast<float>(side_in);
-    if (QUANT) {
-        // x_hat = q*scale_g + zero_g, with the group constants taken out of the sum:
-        //   per tensor / column: Y = scale_c * sum(v*q) + zero_c * sum(v)
-        //   per row            : Y = sum((v*scale_col)*q) + sum(v*zero_col)
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) {
-            if (QMODE == kQRowScale) {
-                if (qp.affine) out[i] += side;
-            } else if (qp.granularity == AES_Q_PER_ROW_FOLDED) {
-                if (qp.zero) out[i] += qp.zero[r];   // constants live in the plan's values; zero = row bias
-            } else {
-                const int g = qp.granularity == AES_Q_PER_COLUMN ? f + i : 0;
-                out[i] *= qp.scale[g];
-                if (qp.affine) out[i] = __builtin_fmaf(side, qp.zero[g], out[i]);
-            }
+    for (int i = 0; i < VEC; ++i) {
+        out[i] = static_cast<float>(acc_in[i]);
+        if constexpr (QMODE == kQRowScale) {
+            if constexpr (AFFINE) out[i] += side;
+        } else if constexpr (QMODE == kQFolded) {
+            if (k.bias) out[i] += k.zero[i];
+        } else if constexpr (QMODE == kQTensor || QMODE == kQColumn) {
+            out[i] *= k.scale[i];
+            if constexpr (AFFINE) out[i] = __builtin_fmaf(side, k.zero[i], out[i]);
         }
     }
 }
 
 // finish_values, then the store of the chunk to Y[r, f ...] (16-byte stores, 4-byte aligned, on the vector paths).
-template <typename Feat, int QMODE, bool QUANT, typename AccT>
+template <typename Feat, int QMODE, typename AccT>
 __device__ __forceinline__ void finish_chunk(const AccT (&acc_in)[Feat::VEC], AccT side_in, bool lane_on,
-                                             int32_t f, const QParams &qp, int64_t r, float *__restrict__ y)
+                                             const LaneConstants<Feat, QMODE> &k, float *__restrict__ y)
 {
     constexpr int VEC = Feat::VEC;
     if (!lane_on) return;
     float acc[VEC];
-    finish_values<Feat, QMODE, QUANT, AccT>(acc_in, side_in, f, qp, r, acc);
+    finish_values<Feat, QMODE, AccT>(acc_in, side_in, k, acc);
     if constexpr (VEC % 4 == 0) {
 #pragma unroll
         for (int i = 0; i < VEC; i += 4)

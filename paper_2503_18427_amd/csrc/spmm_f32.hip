@@ -14,13 +14,13 @@ int run_f32(const char *what, int64_t n_rows, const SlotSource &src, const int32
             int64_t ldx, int32_t F, float *Y, int64_t ldy, hipStream_t stream)
 {
     const bool lr = long_rows_possible(src.W);
-    QParams qp = {nullptr, nullptr, 0, 0};
+    const QParams qp = {nullptr, nullptr};
     const int32_t F4 = F & ~3;
     if (F4 > 0)
-        if (int rc = dispatch_lanes<FeatF32<4>, kQNone, false, FUSED>(lr, n_rows, src, row_perm, X, ldx, F4, qp, Y, ldy, stream, what))
+        if (int rc = dispatch_lanes<FeatF32<4>, kQNone, FUSED>(lr, n_rows, src, row_perm, X, ldx, F4, qp, Y, ldy, stream, what))
             return rc;
     if (F4 < F)
-        return launch_rows<8, 8, FeatF32<1>, kQNone, false, FUSED>(lr, n_rows, src, row_perm, X + F4, ldx, F - F4, qp,
+        return launch_rows<8, 8, FeatF32<1>, kQNone, FUSED>(lr, n_rows, src, row_perm, X + F4, ldx, F - F4, qp,
                                                                   Y + F4, ldy, stream, what);
     return AES_OK;
 }

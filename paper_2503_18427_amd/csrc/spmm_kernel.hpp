@@ -35,13 +35,14 @@ constexpr int kLongRow = 2048;
 // LPR   lanes per output row (8, 16, 32 or 64); a wavefront holds 64/LPR rows
 // Feat  feature loader: Feat::VEC features per lane per chunk (4 on the aligned
 //       fast paths, 1 otherwise)
-// QMODE see above; QUANT: apply the 8-bit epilogue; FUSED: sample from the CSR on the fly
+// QMODE how the constants of the 8-bit path are applied (kQNone: float32 features); FUSED: sample
+//       from the CSR on the fly
 // LONG  rows above kLongRow slots are processed by the whole workgroup: its lane groups
 //       take the row's tiles round-robin and their partial sums (carried in float64,
 //       since such sums run over up to millions of terms) are added in a fixed order
 //       through LDS, so the result stays bit-reproducible.  Without LONG the kernel
 //       has no workgroup barrier at all.
-template <int LPR, int UNROLL, typename Feat, int QMODE, bool QUANT, bool FUSED, bool LONG>
+template <int LPR, int UNROLL, typename Feat, int QMODE, bool FUSED, bool LONG>
 __global__ void __launch_bounds__(kBlock)
 spmm_rows_kernel(int64_t n_rows, SlotSource src, const int32_t *__restrict__ row_perm,
                  const typename Feat::elem_t *__restrict__ X, int64_t ldx, int32_t F, QParams qp,
@@ -51,6 +52,11 @@ spmm_rows_kernel(int64_t n_rows, SlotSource src, const int32_t *__restrict__ row
     constexpr int kGroups = kWave / LPR;                 // rows per wavefront
     constexpr int kRowsPerBlock = kGroups * aes::kWavesPerBlock;
     constexpr int kStride = kTile + 1;                   // +1 slot: groups start in different LDS banks
+    // Where a row's per-column constants are requested: before its gathers, so that their latency passes
+    // behind the gathers, where the four registers that hold them meanwhile fit under 64 (8 wavefronts
+    // per SIMD: signed codes, wide lane groups); after the gathers otherwise.  Measured: 2-7 % on the
+    // short-row workloads where it applies, 10-15 % slower where it costs a wavefront of occupancy.
+    constexpr bool kEarlyConstants = QMODE == kQColumn && Feat::kSigned && LPR >= 32;
     __shared__ int2 stage[aes::kWavesPerBlock][kGroups][kStride];
 
     const int wave = threadIdx.x / kWave;
@@ -76,10 +82,13 @@ spmm_rows_kernel(int64_t n_rows, SlotSource src, const int32_t *__restrict__ row
 #pragma unroll
             for (int i = 0; i < VEC; ++i) acc[i] = 0.0f;
             float side = 0.0f;      // this lane's share of sum(val * zero-point weight)
-            accumulate_tiles<LPR, UNROLL, Feat, QMODE, QUANT, FUSED, float>(src, ri, my_stage, lane, lane_on, X, ldx, f,
-                                                                            qp, 0, 1, acc, side);
-            if (QUANT && qp.affine) side = group_sum<LPR, float>(side);
-            finish_chunk<Feat, QMODE, QUANT, float>(acc, side, lane_on, f, qp, r, Y + r * ldy + f);
+            LaneConstants<Feat, QMODE> k;
+            if constexpr (kEarlyConstants) load_lane_constants<Feat, QMODE>(qp, f, lane_on, r, k);
+            accumulate_tiles<LPR, UNROLL, Feat, QMODE, FUSED, float>(src, ri, my_stage, lane, lane_on, X, ldx, f, qp, 0, 1,
+                                                                     acc, side);
+            if constexpr (!kEarlyConstants) load_lane_constants<Feat, QMODE>(qp, f, lane_on, r, k);
+            if constexpr (QTraits<Feat, QMODE>::kAffine) side = group_sum<LPR, float>(side);
+            finish_chunk<Feat, QMODE, float>(acc, side, lane_on, k, Y + r * ldy + f);
         }
     }
 
@@ -103,10 +112,9 @@ spmm_rows_kernel(int64_t n_rows, SlotSource src, const int32_t *__restrict__ row
 #pragma unroll
                 for (int j = 0; j < VEC; ++j) acc[j] = 0.0;
                 double side = 0.0;
-                accumulate_tiles<LPR, UNROLL, Feat, QMODE, QUANT, FUSED, double>(src, lri, my_stage, lane, lane_on, X,
-                                                                                 ldx, f, qp, gib, kRowsPerBlock, acc,
-                                                                                 side);
-                if (QUANT && qp.affine) side = group_sum<LPR, double>(side);
+                accumulate_tiles<LPR, UNROLL, Feat, QMODE, FUSED, double>(src, lri, my_stage, lane, lane_on, X, ldx, f, qp,
+                                                                          gib, kRowsPerBlock, acc, side);
+                if constexpr (QTraits<Feat, QMODE>::kAffine) side = group_sum<LPR, double>(side);
 #pragma unroll
                 for (int j = 0; j < VEC; ++j) sh_part[gib][lane][j] = acc[j];
                 sh_part[gib][lane][VEC] = side;
@@ -117,7 +125,9 @@ spmm_rows_kernel(int64_t n_rows, SlotSource src, const int32_t *__restrict__ row
                         for (int j = 0; j < VEC; ++j) acc[j] += sh_part[g][lane][j];
                         side += sh_part[g][lane][VEC];
                     }
-                    finish_chunk<Feat, QMODE, QUANT, double>(acc, side, lane_on, f, qp, lr, Y + lr * ldy + f);
+                    LaneConstants<Feat, QMODE> k;
+                    load_lane_constants<Feat, QMODE>(qp, f, lane_on, lr, k);
+                    finish_chunk<Feat, QMODE, double>(acc, side, lane_on, k, Y + lr * ldy + f);
                 }
                 __syncthreads();
             }
@@ -125,7 +135,7 @@ spmm_rows_kernel(int64_t n_rows, SlotSource src, const int32_t *__restrict__ row
     }
 }
 
-template <int LPR, int UNROLL, typename Feat, int QMODE, bool QUANT, bool FUSED>
+template <int LPR, int UNROLL, typename Feat, int QMODE, bool FUSED>
 inline int launch_rows(bool long_rows, int64_t n_rows, const SlotSource &src,
                 const int32_t *row_perm, const typename Feat::elem_t *X, int64_t ldx, int32_t F, QParams qp,
                 float *Y, int64_t ldy, hipStream_t stream, const char *what)
@@ -135,10 +145,10 @@ inline int launch_rows(bool long_rows, int64_t n_rows, const SlotSource &src,
     if (grid > INT32_MAX) return aes::fail(AES_ERR_UNSUPPORTED, "%s: n_rows=%lld too large", what, (long long)n_rows);
     const dim3 g(static_cast<unsigned>(grid)), b(kBlock);
     if (long_rows)
-        spmm_rows_kernel<LPR, UNROLL, Feat, QMODE, QUANT, FUSED, true>
+        spmm_rows_kernel<LPR, UNROLL, Feat, QMODE, FUSED, true>
             <<<g, b, 0, stream>>>(n_rows, src, row_perm, X, ldx, F, qp, Y, ldy);
     else
-        spmm_rows_kernel<LPR, UNROLL, Feat, QMODE, QUANT, FUSED, false>
+        spmm_rows_kernel<LPR, UNROLL, Feat, QMODE, FUSED, false>
             <<<g, b, 0, stream>>>(n_rows, src, row_perm, X, ldx, F, qp, Y, ldy);
     return aes::check_launch(what);
 }
@@ -154,16 +164,16 @@ inline int lanes_per_row(int32_t F, int vec)
 inline bool long_rows_possible(int32_t W) { return W == 0 || W > kLongRow; }
 
 // Vector path: pick the lane-group width from F.
-template <typename Feat, int QMODE, bool QUANT, bool FUSED>
+template <typename Feat, int QMODE, bool FUSED>
 int dispatch_lanes(bool lr, int64_t n_rows, const SlotSource &src, const int32_t *row_perm,
                    const typename Feat::elem_t *X, int64_t ldx, int32_t F, QParams qp, float *Y, int64_t ldy,
                    hipStream_t stream, const char *what)
 {
     switch (lanes_per_row(F, Feat::VEC)) {
-        case 8: return launch_rows<8, 8, Feat, QMODE, QUANT, FUSED>(lr, n_rows, src, row_perm, X, ldx, F, qp, Y, ldy, stream, what);
-        case 16: return launch_rows<16, 8, Feat, QMODE, QUANT, FUSED>(lr, n_rows, src, row_perm, X, ldx, F, qp, Y, ldy, stream, what);
-        case 32: return launch_rows<32, 8, Feat, QMODE, QUANT, FUSED>(lr, n_rows, src, row_perm, X, ldx, F, qp, Y, ldy, stream, what);
-        default: return launch_rows<64, 8, Feat, QMODE, QUANT, FUSED>(lr, n_rows, src, row_perm, X, ldx, F, qp, Y, ldy, stream, what);
+        case 8: return launch_rows<8, 8, Feat, QMODE, FUSED>(lr, n_rows, src, row_perm, X, ldx, F, qp, Y, ldy, stream, what);
+        case 16: return launch_rows<16, 8, Feat, QMODE, FUSED>(lr, n_rows, src, row_perm, X, ldx, F, qp, Y, ldy, stream, what);
+        case 32: return launch_rows<32, 8, Feat, QMODE, FUSED>(lr, n_rows, src, row_perm, X, ldx, F, qp, Y, ldy, stream, what);
+        default: return launch_rows<64, 8, Feat, QMODE, FUSED>(lr, n_rows, src, row_perm, X, ldx, F, qp, Y, ldy, stream, what);
     }
 }
 

@@ -15,17 +15,32 @@ int dispatch_q8(int64_t n_rows, const SlotSource &src, const int32_t *row_perm, 
     const bool lr = long_rows_possible(src.W);
     const int32_t F4 = F & ~3;
     if (F4 > 0)
-        if (int rc = dispatch_lanes<FeatQ8<4, SIGNED>, QMODE, true, FUSED>(lr, n_rows, src, row_perm, Xq, ldq, F4, qp, Y, ldy, stream, what))
+        if (int rc = dispatch_lanes<FeatQ8<4, SIGNED>, QMODE, FUSED>(lr, n_rows, src, row_perm, Xq, ldq, F4, qp, Y, ldy, stream, what))
             return rc;
     if (F4 < F) {
-        if (qp.granularity == AES_Q_PER_COLUMN) {        // the columns' own constants
+        if (QMODE == kQColumn) {                         // the columns' own constants
             qp.scale += F4;
             if (qp.zero) qp.zero += F4;
         }
-        return launch_rows<8, 8, FeatQ8<1, SIGNED>, QMODE, true, FUSED>(lr, n_rows, src, row_perm, Xq + F4, ldq, F - F4, qp,
-                                                                       Y + F4, ldy, stream, what);
+        return launch_rows<8, 8, FeatQ8<1, SIGNED>, QMODE, FUSED>(lr, n_rows, src, row_perm, Xq + F4, ldq, F - F4, qp,
+                                                                 Y + F4, ldy, stream, what);
     }
     return AES_OK;
+}
+
+template <bool SIGNED, bool FUSED>
+int dispatch_granularity(int32_t granularity, int64_t n_rows, const SlotSource &src, const int32_t *row_perm,
+                         const int8_t *Xq, int64_t ldq, int32_t F, QParams qp, float *Y, int64_t ldy,
+                         hipStream_t stream, const char *what)
+{
+    switch (granularity) {
+        case AES_Q_PER_TENSOR: return dispatch_q8<SIGNED, kQTensor, FUSED>(n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
+        case AES_Q_PER_COLUMN: return dispatch_q8<SIGNED, kQColumn, FUSED>(n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
+        case AES_Q_PER_ROW: return dispatch_q8<SIGNED, kQRowScale, FUSED>(n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
+        default:
+            if constexpr (FUSED) return aes::fail(AES_ERR_INVALID_ARG, "%s: folded constants need a materialised plan", what);
+            else return dispatch_q8<SIGNED, kQFolded, false>(n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
+    }
 }
 
 template <bool FUSED>
@@ -45,20 +60,11 @@ int run_q8(const char *what, int64_t n_rows, const SlotSource &src, const int32_
     if (affine && zero == nullptr)
         return aes::fail(AES_ERR_INVALID_ARG, "%s: zero (the row bias, for folded constants) is NULL for the affine scheme", what);
     if (n_rows == 0) return AES_OK;
-    // folded: the kernel only adds zero[r] (the row bias) at the end; the affine flag of QParams,
-    // which drives the per-slot zero-point sums, stays off, the unsigned decoding is in the loader
-    QParams qp = {scale, folded && !affine ? nullptr : zero, granularity, (affine && !folded) ? 1 : 0};
-    if (folded) {
-        if (affine) return dispatch_q8<false, kQNone, FUSED>(n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
-        return dispatch_q8<true, kQNone, FUSED>(n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
-    }
-    const bool per_row = granularity == AES_Q_PER_ROW;
-    if (affine) {
-        if (per_row) return dispatch_q8<false, kQRowScale, FUSED>(n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
-        return dispatch_q8<false, kQNone, FUSED>(n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
-    }
-    if (per_row) return dispatch_q8<true, kQRowScale, FUSED>(n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
-    return dispatch_q8<true, kQNone, FUSED>(n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
+    // Unsigned codes (the affine scheme) use zero; signed codes ignore it.  Folded: zero is the row
+    // bias the fold pass wrote for the affine scheme, and nothing otherwise.
+    const QParams qp = {scale, affine ? zero : nullptr};
+    if (affine) return dispatch_granularity<false, FUSED>(granularity, n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
+    return dispatch_granularity<true, FUSED>(granularity, n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
 }
 
 // One group of 16 lanes per row: s_val_folded = s_val * scale[col], row_bias = sum s_val * zero[col].
