@@ -333,12 +333,18 @@ int aes_spmm_fused_q8(int64_t n_rows, int64_t n_cols,
  * them by Theta on the matrix cores (float32 MFMA, float32 accumulate); the
  * aggregated features are never written to memory.  No bias, no activation.
  *
- *   plan, W         as for aes_spmm_f32 (rows are always handled by one lane
- *                   group here, whatever W says)
- *   X     [dev]     n_cols x F float32 (ldx); F <= 256 and a multiple of 4 -
- *                   otherwise AES_ERR_UNSUPPORTED (run aes_spmm_f32 and a GEMM
- *                   instead); no alignment needed beyond a float's
- *   Theta [dev]     F x Fo float32, row-major, leading dimension ldt
+ *   plan, W         as for aes_spmm_f32, including the treatment of rows above
+ *                   2048 slots when W == 0 or W > 2048 (shared by the
+ *                   workgroup, float64 partial sums in a fixed order)
+ *   X     [dev]     n_cols x F float32 (ldx); any F in 1 .. 2^24-1, no alignment
+ *                   needed beyond a float's.  F <= 256 with F % 4 == 0 (and a W
+ *                   that rules out long rows) runs a specialised kernel that
+ *                   holds whole aggregated rows in LDS; any other shape walks
+ *                   the features in chunks of 256 and keeps the MFMA
+ *                   accumulators in registers across the chunks
+ *   Theta [dev]     F x Fo float32, row-major, leading dimension ldt; output
+ *                   columns beyond 512 take one more launch per 512 (each
+ *                   aggregates again)
  *   H     [dev]     out, n_rows x Fo float32 (ldh); must not overlap the inputs
  */
 int aes_gcn_layer_f32(int64_t n_rows, int64_t n_cols, int32_t W,
@@ -351,7 +357,7 @@ int aes_gcn_layer_f32(int64_t n_rows, int64_t n_cols, int32_t W,
  * The same layer on 8-bit features: H = (A_s x_hat) Theta with the dequantisation of Sec. 2.3
  * Eq. 2 fused into the gather exactly as in aes_spmm_q8 (same scheme / granularity / scale /
  * zero arguments, AES_Q_PER_ROW_FOLDED included), the aggregated tile multiplied by Theta on
- * the matrix cores.  F <= 256 and a multiple of 4; Xq and ldq need no particular alignment.
+ * the matrix cores.  Any F, as for aes_gcn_layer_f32; Xq and ldq need no particular alignment.
  */
 int aes_gcn_layer_q8(int64_t n_rows, int64_t n_cols, int32_t W,
                      const int64_t *s_rowptr, const int32_t *s_col, const float *s_val,

@@ -17,7 +17,7 @@ namespace {
 using namespace aes;
 
 constexpr int kTileRows = 32;        // rows per workgroup = M of the MFMA block
-constexpr int kMaxFeatures = 256;    // one chunk of four features per lane, at most 64 lanes
+constexpr int kMaxFeatures = 256;    // the specialised kernel: one chunk of four features per lane, at most 64 lanes
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
@@ -184,6 +184,193 @@ int dispatch_gcn(const char *what, int64_t n_rows, const SlotSource &src, const 
     }
 }
 
+// ---- the general form: any F, any row length --------------------------------------------------
+// The kernel above keeps a whole aggregated row (F <= 256 features, F % 4 == 0) in LDS and leaves
+// every row to one lane group.  This one walks the features in chunks of kChunkF:
+//   for each chunk: aggregate the chunk of the 32 rows into LDS, then add tile_chunk * Theta_chunk
+//   to the wavefront's MFMA accumulators, which live in registers across the chunks
+// so F is unbounded and the LDS tile is 33 KB whatever F is.  One lane group is a whole wavefront
+// (64 lanes x 4 features = one chunk); the last lane of a row whose length is not a multiple of
+// four loads its 1-3 features one by one.  LONG (plans whose width allows rows above kLongRowLayer
+// slots: W == 0 or W > 2048): such a row is shared by the four wavefronts, partial sums carried in
+// float64 and added in a fixed order through LDS, exactly as in the SpMM kernel.
+// NB = 32-column blocks of H per wavefront (1: Fo <= 128, 4: Fo <= 512).
+constexpr int kChunkF = 256;
+constexpr int kLongRowLayer = 2048;
+
+template <typename Feat, int QMODE, int NB, bool LONG>
+__global__ void __launch_bounds__(kBlock)
+gcn_layer_wide_kernel(int64_t n_rows, SlotSource src, const typename Feat::elem_t *__restrict__ X, int64_t ldx,
+                      int32_t F, QParams qp, const float *__restrict__ Theta, int64_t ldt, int32_t Fo,
+                      float *__restrict__ H, int64_t ldh)
+{
+    constexpr int LPR = kWave;
+    constexpr int kStride = kTile + 1;
+    constexpr int kYStride = kChunkF + 1;             // 32 rows of an A operand fall in 32 different banks
+    __shared__ int2 stage[kWavesPerBlock][kStride];
+    __shared__ float ys[kTileRows * kYStride];
+    __shared__ double sh_part[LONG ? kWavesPerBlock : 1][LONG ? LPR : 1][5];
+
+    const int wave = threadIdx.x / kWave;
+    const int lane = threadIdx.x % kWave;
+    const int64_t row0 = static_cast<int64_t>(blockIdx.x) * kTileRows;
+    const int i = lane % 32, h = lane / 32;           // MFMA operand coordinates of this lane
+
+    floatx16 c[NB];
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) c[j][v] = 0.0f;
+
+    for (int32_t f0 = 0; f0 < F; f0 += kChunkF) {
+        const int32_t chunk_len = F - f0 < kChunkF ? F - f0 : kChunkF;
+        const int32_t f = f0 + lane * 4;
+        const bool lane_on = f < F;
+        const int nv = lane_on ? (F - f < 4 ? F - f : 4) : 0;
+
+        // ---- aggregation of the chunk: Algorithm 1's accumulation loop, one wavefront per row ----
+        for (int rr = wave; rr < kTileRows; rr += kWavesPerBlock) {
+            const int64_t r = row0 + rr;
+            float y[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+            if (r < n_rows) {
+                const RowInfo ri = row_info<false>(src, r);
+                if (!(LONG && ri.n_slots > kLongRowLayer)) {
+                    float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+                    float side = 0.0f;
+                    LaneConstants<Feat, QMODE> k;
+                    accumulate_tiles<LPR, 8, Feat, QMODE, false, float, true>(src, ri, stage[wave], lane, lane_on, X, ldx, f,
+                                                                              qp, 0, 1, acc, side, nv);
+                    load_lane_constants<Feat, QMODE>(qp, f, lane_on, r, k, nv);
+                    if constexpr (QTraits<Feat, QMODE>::kAffine) side = group_sum<LPR, float>(side);
+                    if (lane_on) finish_values<Feat, QMODE, float>(acc, side, k, y);
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) ys[rr * kYStride + lane * 4 + q] = (lane_on && q < nv) ? y[q] : 0.0f;
+        }
+        if constexpr (LONG) {
+            // Long rows of the tile, one after another, by all four wavefronts (uniform control flow:
+            // every thread reads the same row pointers).
+            for (int rr = 0; rr < kTileRows; ++rr) {
+                const int64_t r = row0 + rr;
+                if (r >= n_rows) break;
+                const RowInfo ri = row_info<false>(src, r);
+                if (ri.n_slots <= kLongRowLayer) continue;
+                double acc[4] = {0.0, 0.0, 0.0, 0.0};
+                double side = 0.0;
+                accumulate_tiles<LPR, 8, Feat, QMODE, false, double, true>(src, ri, stage[wave], lane, lane_on, X, ldx, f,
+                                                                           qp, wave, kWavesPerBlock, acc, side, nv);
+                if constexpr (QTraits<Feat, QMODE>::kAffine) side = group_sum<LPR, double>(side);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) sh_part[wave][lane][q] = acc[q];
+                sh_part[wave][lane][4] = side;
+                __syncthreads();
+                if (wave == 0) {
+                    for (int g = 1; g < kWavesPerBlock; ++g) {     // fixed order: bit-reproducible
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) acc[q] += sh_part[g][lane][q];
+                        side += sh_part[g][lane][4];
+                    }
+                    float y[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+                    LaneConstants<Feat, QMODE> k;
+                    load_lane_constants<Feat, QMODE>(qp, f, lane_on, r, k, nv);
+                    if (lane_on) finish_values<Feat, QMODE, double>(acc, side, k, y);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) ys[rr * kYStride + lane * 4 + q] = (lane_on && q < nv) ? y[q] : 0.0f;
+                }
+                __syncthreads();
+            }
+        }
+        __syncthreads();
+
+        // ---- combination of the chunk: c[j] += ys (32 x chunk_len) * Theta[f0 .. f0 + chunk_len, block] ----
+        // v_mfma_f32_32x32x2_f32: lane l supplies A[l % 32][l / 32] and B[l / 32][l % 32].
+        const int32_t k_end = (chunk_len + 1) & ~1;
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            const int nb = wave + j * kWavesPerBlock;
+            if (nb * 32 < Fo) {
+                const int col = nb * 32 + i;
+                const bool col_on = col < Fo;
+                const float *t_col = Theta + (col_on ? col : 0);
+                for (int32_t k0 = 0; k0 < k_end; k0 += 16) {
+                    float a[8], b[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const int32_t kk = k0 + 2 * u + h;             // feature within the chunk
+                        a[u] = kk < chunk_len ? ys[i * kYStride + kk] : 0.0f;
+                        b[u] = (kk < chunk_len && col_on) ? t_col[static_cast<int64_t>(f0 + kk) * ldt] : 0.0f;
+                    }
+#pragma unroll
+                    for (int u = 0; u < 8; ++u)
+                        if (k0 + 2 * u < k_end) c[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u], b[u], c[j], 0, 0, 0);
+                }
+            }
+        }
+        __syncthreads();                               // the tile is overwritten by the next chunk
+    }
+
+    // result register v of lane l holds D[8 * (v / 4) + 4 * (l / 32) + v % 4][l % 32]
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+        const int col = (wave + j * kWavesPerBlock) * 32 + i;
+        if (col < Fo) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int64_t r = row0 + 8 * (v / 4) + 4 * h + (v % 4);
+                if (r < n_rows) H[r * ldh + col] = c[j][v];
+            }
+        }
+    }
+}
+
+template <typename Feat, int QMODE, int NB>
+int launch_gcn_wide(const char *what, bool long_rows, int64_t n_rows, const SlotSource &src,
+                    const typename Feat::elem_t *X, int64_t ldx, int32_t F, QParams qp, const float *Theta,
+                    int64_t ldt, int32_t Fo, float *H, int64_t ldh, hipStream_t stream)
+{
+    const int64_t grid = ceil_div(n_rows, kTileRows);
+    if (grid > INT32_MAX) return fail(AES_ERR_UNSUPPORTED, "%s: n_rows=%lld too large", what, (long long)n_rows);
+    const dim3 g(static_cast<unsigned>(grid)), b(kBlock);
+    if (long_rows)
+        gcn_layer_wide_kernel<Feat, QMODE, NB, true><<<g, b, 0, stream>>>(n_rows, src, X, ldx, F, qp, Theta, ldt, Fo, H, ldh);
+    else
+        gcn_layer_wide_kernel<Feat, QMODE, NB, false><<<g, b, 0, stream>>>(n_rows, src, X, ldx, F, qp, Theta, ldt, Fo, H, ldh);
+    return check_launch(what);
+}
+
+// Output columns in groups of at most 512 (four 32-column blocks per wavefront); a wider Theta takes
+// one launch per group, each of which aggregates again.
+template <typename Feat, int QMODE>
+int dispatch_gcn_wide(const char *what, bool long_rows, int64_t n_rows, const SlotSource &src,
+                      const typename Feat::elem_t *X, int64_t ldx, int32_t F, QParams qp, const float *Theta,
+                      int64_t ldt, int32_t Fo, float *H, int64_t ldh, hipStream_t stream)
+{
+    constexpr int kGroupCols = 4 * kWavesPerBlock * 32;
+    for (int32_t o = 0; o < Fo; o += kGroupCols) {
+        const int32_t fo = Fo - o < kGroupCols ? Fo - o : kGroupCols;
+        int rc;
+        if (fo <= kWavesPerBlock * 32)
+            rc = launch_gcn_wide<Feat, QMODE, 1>(what, long_rows, n_rows, src, X, ldx, F, qp, Theta + o, ldt, fo, H + o, ldh, stream);
+        else
+            rc = launch_gcn_wide<Feat, QMODE, 4>(what, long_rows, n_rows, src, X, ldx, F, qp, Theta + o, ldt, fo, H + o, ldh, stream);
+        if (rc) return rc;
+    }
+    return AES_OK;
+}
+
+// The specialised kernel where it applies, the general one otherwise.
+template <typename Feat, int QMODE>
+int run_gcn(const char *what, int32_t W, int64_t n_rows, const SlotSource &src, const typename Feat::elem_t *X,
+            int64_t ldx, int32_t F, QParams qp, const float *Theta, int64_t ldt, int32_t Fo, float *H, int64_t ldh,
+            hipStream_t stream)
+{
+    const bool long_rows = W == 0 || W > kLongRowLayer;
+    if (F <= kMaxFeatures && F % 4 == 0 && !long_rows)
+        return dispatch_gcn<Feat, QMODE>(what, n_rows, src, X, ldx, F, qp, Theta, ldt, Fo, H, ldh, stream);
+    return dispatch_gcn_wide<Feat, QMODE>(what, long_rows, n_rows, src, X, ldx, F, qp, Theta, ldt, Fo, H, ldh, stream);
+}
+
 // Argument checks shared by the float32 and the 8-bit entry point.
 int check_layer(const char *what, int64_t n_rows, int64_t n_cols, int32_t W, const int64_t *s_rowptr, const void *X,
                 int64_t ldx, int32_t F, const float *Theta, int64_t ldt, int32_t Fo, const float *H,
@@ -205,10 +392,7 @@ int check_layer(const char *what, int64_t n_rows, int64_t n_cols, int32_t W, con
         return fail(AES_ERR_UNSUPPORTED, "%s: feature leading dimension %lld does not fit 32 bits", what, (long long)ldx);
     if (ldt >= (1 << 28) || ldh >= (1 << 28))
         return fail(AES_ERR_UNSUPPORTED, "%s: ldt / ldh must stay below 2^28 (32-bit lane offsets)", what);
-    if (F > kMaxFeatures || F % 4 != 0)
-        return fail(AES_ERR_UNSUPPORTED,
-                    "%s: needs F <= %d and a multiple of 4 (F=%d); use the SpMM entry point and a GEMM instead", what,
-                    kMaxFeatures, (int)F);
+    if (F >= (1 << 24)) return fail(AES_ERR_INVALID_ARG, "%s: F=%d outside 1..2^24-1", what, (int)F);
     return AES_OK;
 }
 
@@ -225,8 +409,8 @@ extern "C" int aes_gcn_layer_f32(int64_t n_rows, int64_t n_cols, int32_t W,
     if (n_rows == 0) return AES_OK;
     const SlotSource src = {s_rowptr, s_col, s_val, W, 0, 0};
     const QParams qp = {nullptr, nullptr};
-    return dispatch_gcn<FeatF32<4>, kQNone>(what, n_rows, src, X, ldx, F, qp, Theta, ldt, Fo, H, ldh,
-                                                   static_cast<hipStream_t>(stream));
+    return run_gcn<FeatF32<4>, kQNone>(what, W, n_rows, src, X, ldx, F, qp, Theta, ldt, Fo, H, ldh,
+                                       static_cast<hipStream_t>(stream));
 }
 
 extern "C" int aes_gcn_layer_q8(int64_t n_rows, int64_t n_cols, int32_t W,
@@ -251,7 +435,7 @@ extern "C" int aes_gcn_layer_q8(int64_t n_rows, int64_t n_cols, int32_t W,
     const SlotSource src = {s_rowptr, s_col, s_val, W, 0, 0};
     const QParams qp = {scale, affine ? zero : nullptr};
 #define AES_GCN_Q8(SIGNED, MODE) \
-    dispatch_gcn<FeatQ8<4, SIGNED>, MODE>(what, n_rows, src, Xq, ldq, F, qp, Theta, ldt, Fo, H, ldh, stream)
+    run_gcn<FeatQ8<4, SIGNED>, MODE>(what, W, n_rows, src, Xq, ldq, F, qp, Theta, ldt, Fo, H, ldh, stream)
     switch (granularity) {
         case AES_Q_PER_TENSOR: return affine ? AES_GCN_Q8(false, kQTensor) : AES_GCN_Q8(true, kQTensor);
         case AES_Q_PER_COLUMN: return affine ? AES_GCN_Q8(false, kQColumn) : AES_GCN_Q8(true, kQColumn);

@@ -68,6 +68,15 @@ template <> struct FeatF32<4> {
     using elem_t = float;
     using raw_t = Float4U;
     static __device__ inline raw_t load(const elem_t *p) { return *reinterpret_cast<const Float4U *>(p); }
+    // The first nv (1..3) features only, zeros for the rest: the last lane of a row whose length is not
+    // a multiple of four.
+    static __device__ inline raw_t load_n(const elem_t *p, int nv)
+    {
+        raw_t x = {p[0], 0.0f, 0.0f, 0.0f};
+        if (nv > 1) x.y = p[1];
+        if (nv > 2) x.z = p[2];
+        return x;
+    }
     template <typename AccT>
     static __device__ inline void fma(AccT (&acc)[4], float v, const raw_t &x)
     {
@@ -83,6 +92,7 @@ template <> struct FeatF32<1> {
     using elem_t = float;
     using raw_t = float;
     static __device__ inline raw_t load(const elem_t *p) { return *p; }
+    static __device__ inline raw_t load_n(const elem_t *p, int) { return *p; }
     template <typename AccT>
     static __device__ inline void fma(AccT (&acc)[1], float v, const raw_t &x) { acc[0] = fma_acc(v, x, acc[0]); }
 };
@@ -112,6 +122,13 @@ template <bool SIGNED> struct FeatQ8<4, SIGNED> {
     using elem_t = int8_t;
     using raw_t = uint32_t;
     static __device__ inline raw_t load(const elem_t *p) { return reinterpret_cast<const Word1U *>(p)->v; }
+    static __device__ inline raw_t load_n(const elem_t *p, int nv)     // missing codes read as 0
+    {
+        uint32_t w = static_cast<uint8_t>(p[0]);
+        if (nv > 1) w |= static_cast<uint32_t>(static_cast<uint8_t>(p[1])) << 8;
+        if (nv > 2) w |= static_cast<uint32_t>(static_cast<uint8_t>(p[2])) << 16;
+        return w;
+    }
     template <typename AccT>
     static __device__ inline void fma(AccT (&acc)[4], float v, const raw_t &x) { fma_bytes<SIGNED>(acc, v, x); }
 };
@@ -121,6 +138,7 @@ template <bool SIGNED> struct FeatQ8<1, SIGNED> {
     using elem_t = int8_t;
     using raw_t = int8_t;
     static __device__ inline raw_t load(const elem_t *p) { return *p; }
+    static __device__ inline raw_t load_n(const elem_t *p, int) { return *p; }
     template <typename AccT>
     static __device__ inline void fma(AccT (&acc)[1], float v, const raw_t &x)
     {
@@ -172,12 +190,21 @@ __device__ inline RowInfo row_info(const SlotSource &src, int64_t r)
 
 // Adds the row's tiles first_tile, first_tile + tile_step, ... into acc (one chunk of
 // features).  side collects the zero-point sum the affine 8-bit epilogue needs.
-template <int LPR, int UNROLL, typename Feat, int QMODE, bool FUSED, typename AccT>
+// PARTIAL: a lane may own fewer than VEC valid features (nv of them: the end of a row whose length is
+// not a multiple of VEC); such a lane loads them one by one.
+template <int LPR, int UNROLL, typename Feat, int QMODE, bool FUSED, typename AccT, bool PARTIAL = false>
 __device__ __forceinline__ void accumulate_tiles(const SlotSource &src, const RowInfo &ri, int2 *my_stage, int lane,
                                                  bool lane_on, const typename Feat::elem_t *__restrict__ X,
                                                  int64_t ldx, int32_t f, const QParams &qp, int64_t first_tile,
-                                                 int64_t tile_step, AccT (&acc)[Feat::VEC], AccT &side)
+                                                 int64_t tile_step, AccT (&acc)[Feat::VEC], AccT &side,
+                                                 int nv = Feat::VEC)
 {
+    auto load_feat = [&](const typename Feat::elem_t *p) {
+        if constexpr (PARTIAL) {
+            if (nv != Feat::VEC) return Feat::load_n(p, nv);
+        }
+        return Feat::load(p);
+    };
     // Column indices are non-negative and the host has checked ldx < 2^32: the row offset is one
     // 32 x 32 -> 64-bit multiply-add per gather instead of a sign-extended 64 x 64-bit product.
     const uint32_t ld = static_cast<uint32_t>(ldx);
@@ -214,7 +241,7 @@ __device__ __forceinline__ void accumulate_tiles(const SlotSource &src, const Ro
 #pragma unroll
                 for (int u = 0; u < UNROLL; ++u) cv[u] = my_stage[k + u];
 #pragma unroll
-                for (int u = 0; u < UNROLL; ++u) x[u] = Feat::load(row_of(cv[u].x));
+                for (int u = 0; u < UNROLL; ++u) x[u] = load_feat(row_of(cv[u].x));
 #pragma unroll
                 for (int u = 0; u < UNROLL; ++u) Feat::fma(acc, __int_as_float(cv[u].y), x[u]);
             }
@@ -228,7 +255,7 @@ __device__ __forceinline__ void accumulate_tiles(const SlotSource &src, const Ro
 #pragma unroll
                 for (int u = 0; u < UNROLL; ++u) {
                     x[u] = typename Feat::raw_t{};
-                    if (cv[u].x >= 0) x[u] = Feat::load(row_of(cv[u].x));
+                    if (cv[u].x >= 0) x[u] = load_feat(row_of(cv[u].x));
                 }
 #pragma unroll
                 for (int u = 0; u < UNROLL; ++u) Feat::fma(acc, __int_as_float(cv[u].y), x[u]);
@@ -249,7 +276,7 @@ struct LaneConstants {
 
 template <typename Feat, int QMODE>
 __device__ __forceinline__ void load_lane_constants(const QParams &qp, int32_t f, bool lane_on, int64_t r,
-                                                    LaneConstants<Feat, QMODE> &k)
+                                                    LaneConstants<Feat, QMODE> &k, int nv = Feat::VEC)
 {
     constexpr int VEC = Feat::VEC;
     constexpr bool AFFINE = QTraits<Feat, QMODE>::kAffine;
@@ -270,18 +297,25 @@ __device__ __forceinline__ void load_lane_constants(const QParams &qp, int32_t f
         }
     } else if constexpr (QMODE == kQColumn) {
         if (lane_on) {
+            bool fetched = false;
             if constexpr (VEC == 4) {
-                const Float4U s = *reinterpret_cast<const Float4U *>(qp.scale + f);
-                k.scale[0] = s.x; k.scale[1] = s.y; k.scale[2] = s.z; k.scale[3] = s.w;
-                if constexpr (AFFINE) {
-                    const Float4U z = *reinterpret_cast<const Float4U *>(qp.zero + f);
-                    k.zero[0] = z.x; k.zero[1] = z.y; k.zero[2] = z.z; k.zero[3] = z.w;
+                if (nv == VEC) {
+                    const Float4U s = *reinterpret_cast<const Float4U *>(qp.scale + f);
+                    k.scale[0] = s.x; k.scale[1] = s.y; k.scale[2] = s.z; k.scale[3] = s.w;
+                    if constexpr (AFFINE) {
+                        const Float4U z = *reinterpret_cast<const Float4U *>(qp.zero + f);
+                        k.zero[0] = z.x; k.zero[1] = z.y; k.zero[2] = z.z; k.zero[3] = z.w;
+                    }
+                    fetched = true;
                 }
-            } else {
+            }
+            if (!fetched) {                           // one column per lane, or the ragged end of a row
 #pragma unroll
                 for (int i = 0; i < VEC; ++i) {
-                    k.scale[i] = qp.scale[f + i];
-                    if constexpr (AFFINE) k.zero[i] = qp.zero[f + i];
+                    if (i < nv) {
+                        k.scale[i] = qp.scale[f + i];
+                        if constexpr (AFFINE) k.zero[i] = qp.zero[f + i];
+                    }
                 }
             }
         }

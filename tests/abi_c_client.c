@@ -35,7 +35,9 @@ int main(void)
     CHECK(strstr(aes_last_error(), "workspace") != NULL);
     CHECK(aes_quantize_features(4, 8, fake, 8, 7, AES_Q_PER_ROW, fake, 8, fake, fake, NULL, 0, NULL) ==
           AES_ERR_INVALID_ARG);
-    CHECK(aes_gcn_layer_f32(4, 4, 0, row, fake, fake, fake, 512, 512, fake, 8, 8, fake, 8, NULL) == AES_ERR_UNSUPPORTED);
+    CHECK(aes_gcn_layer_f32(4, 4, 0, row, fake, fake, fake, 8, 8, fake, 4, 8, fake, 8, NULL) == AES_ERR_INVALID_ARG);
+    CHECK(aes_sample_build_noalloc((int64_t)AES_NOALLOC_MAX_ROWS + 1, 4, 8, row, fake, fake, 4, 0, AES_STRATEGY_ADAPTIVE, row,
+                                   fake, fake, NULL, NULL, NULL) == AES_ERR_UNSUPPORTED);
     printf("abi c client ok\n");
     return 0;
 }
