@@ -23,9 +23,9 @@ inside the timed region:
              counter on this chip separates them from HBM reads)
   frac       traffic / time / 8 TB/s: an upper bound on the HBM fraction of the
              timed launch, never above 1
-  hbm_anchor the same kernel on the same plan with every column index replaced
-             by a uniformly random row of an 8 GiB feature table, measured in
-             this run: no reuse is possible, every gather comes from HBM, so
+  hbm_anchor the same kernels on the same plan with every column index replaced
+             by a uniformly random row of a 2 GiB / 8 GiB feature table, measured
+             in this run: no reuse is possible, the gathers come from HBM, so
              algorithmic bytes = HBM bytes and the rate is the kernel's fraction
              of the HBM roof proper
 `cpu_baseline` is the CPU oracle timed on the same workload on this machine's host
@@ -75,7 +75,7 @@ def main() -> int:
     ap.add_argument("--cpu-rows", type=int, default=-1,
                     help="rows in the CPU oracle's sample (-1: all rows, 0: skip the CPU baseline)")
     ap.add_argument("--no-hbm-anchor", action="store_true",
-                    help="skip the cache-defeating run of the fp32 kernel (random columns over an 8 GiB table)")
+                    help="skip the cache-defeating runs of the multiply kernels (random columns over 2 GiB / 8 GiB tables)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="mark the run as a counter-calibration run (kept for the rocprofv3 command lines; the "
                          "plain 1 GiB read + 1 GiB write elementwise kernel they scale against always runs)")
@@ -279,47 +279,52 @@ def main() -> int:
         roofline["traffic_over_stream_copy"] = roofline["traffic_GBps"] / out["stream_copy_GBps"]
 
     # The HBM roof proper: the timed kernels on the same plan (same rows, same slot counts, same launch) with
-    # the column indices replaced by uniformly random rows of an 8 GiB table.  Nothing is reused and neither
-    # L2 (32 MiB) nor the Infinity Cache (256 MiB) can hold a useful part of the table, so every gather
-    # comes from HBM and algorithmic bytes are HBM bytes.  Skipped when the workload's own feature matrix is
-    # already that large (then the timed legs are the anchor) or when memory is short.
-    anchor_bytes = 8 << 30
-    if not args.no_hbm_anchor and S > 0 and X.numel() * 4 < anchor_bytes:
-        try:
-            torch.cuda.empty_cache()
-            free, _ = torch.cuda.mem_get_info()
-            if free < anchor_bytes + 4 * S + (4 << 30):
-                raise RuntimeError(f"only {free >> 30} GiB free")
-            gen = torch.Generator(device=dev)
-            gen.manual_seed(7)
-            rows_f32 = anchor_bytes // (4 * F)
-            Xa = torch.empty((rows_f32, F), dtype=torch.float32, device=dev).normal_(generator=gen)
-            ca = torch.randint(0, rows_f32, (S,), dtype=torch.int32, device=dev, generator=gen)
-            pa = aes.Plan(n, rows_f32, W, plan.s_rowptr, ca, plan.s_val, None, None)
-            t_a = timed(lambda: aes.aes_spmm_f32(pa, Xa, Y))
-            g_a = leg_bytes["spmm_f32"] / (t_a * 1e-3) / 1e9
-            roofline["hbm_anchor"] = {
-                "what": "aes_spmm_f32, same plan rows and launch, columns uniformly random over an 8 GiB table "
-                        "(no reuse: algorithmic bytes = HBM bytes), measured in this run",
-                "ms": t_a, "GBps": g_a, "frac": g_a / HBM_PEAK_GBPS,
-                "over_stream_copy": g_a / out["stream_copy_GBps"], "table_rows": rows_f32}
-            del Xa, ca, pa
-            rows_q8 = anchor_bytes // F
-            Xqa = torch.randint(-127, 128, (rows_q8, F), dtype=torch.int8, device=dev, generator=gen)
-            ca = torch.randint(0, rows_q8, (S,), dtype=torch.int32, device=dev, generator=gen)
-            groups_a = {0: 1, 1: F, 2: rows_q8}[gran]
-            sa = torch.rand(groups_a, device=dev, generator=gen) + 0.5
-            za = torch.zeros(groups_a, device=dev)
-            pa = aes.Plan(n, rows_q8, W, plan.s_rowptr, ca, plan.s_val, None, None)
-            t_q = timed(lambda: aes.aes_spmm_q8(pa, Xqa, scheme, gran, sa, za, Yq))
-            g_q = leg_bytes["spmm_q8"] / (t_q * 1e-3) / 1e9
-            roofline["hbm_anchor_q8"] = {
-                "what": "aes_spmm_q8, same construction (8 GiB of 8-bit rows; per-node scales, where used, over "
-                        "the same random nodes)",
-                "ms": t_q, "GBps": g_q, "frac": g_q / HBM_PEAK_GBPS, "table_rows": rows_q8}
-            del Xqa, ca, sa, za, pa
-        except (RuntimeError, torch.OutOfMemoryError) as exc:   # never let the anchor cost the bench line
-            roofline["hbm_anchor"] = {"skipped": str(exc)[:200]}
+    # the column indices replaced by uniformly random rows of a feature table far larger than the caches
+    # (L2 32 MiB, Infinity Cache 256 MiB), so nothing is reused and algorithmic bytes are HBM bytes.
+    # Two table sizes: 2 GiB (at most 1/8 of the gathers can be served by the Infinity Cache; address
+    # translation is still comfortable) and 8 GiB (no cache can matter, but random 512-byte gathers over so
+    # many pages saturate the address-translation path: rocprofv3 shows the L2 TLB busy 98 % of the time).
+    # Skipped when the workload's own feature matrix is already that large (then the timed legs are the
+    # anchor) or when memory is short.
+    def anchor(table_bytes):
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(7)
+        res = {}
+        rows_f32 = table_bytes // (4 * F)
+        Xa = torch.empty((rows_f32, F), dtype=torch.float32, device=dev).normal_(generator=gen)
+        ca = torch.randint(0, rows_f32, (S,), dtype=torch.int32, device=dev, generator=gen)
+        pa = aes.Plan(n, rows_f32, W, plan.s_rowptr, ca, plan.s_val, None, None)
+        t_a = timed(lambda: aes.aes_spmm_f32(pa, Xa, Y))
+        g_a = leg_bytes["spmm_f32"] / (t_a * 1e-3) / 1e9
+        res["spmm_f32"] = {"ms": t_a, "GBps": g_a, "frac": g_a / HBM_PEAK_GBPS,
+                           "over_stream_copy": g_a / out["stream_copy_GBps"], "table_rows": rows_f32}
+        del Xa, ca, pa
+        rows_q8 = table_bytes // F
+        Xqa = torch.randint(-127, 128, (rows_q8, F), dtype=torch.int8, device=dev, generator=gen)
+        ca = torch.randint(0, rows_q8, (S,), dtype=torch.int32, device=dev, generator=gen)
+        groups_a = {0: 1, 1: F, 2: rows_q8}[gran]
+        sa = torch.rand(groups_a, device=dev, generator=gen) + 0.5
+        za = torch.zeros(groups_a, device=dev)
+        pa = aes.Plan(n, rows_q8, W, plan.s_rowptr, ca, plan.s_val, None, None)
+        t_q = timed(lambda: aes.aes_spmm_q8(pa, Xqa, scheme, gran, sa, za, Yq))
+        g_q = leg_bytes["spmm_q8"] / (t_q * 1e-3) / 1e9
+        res["spmm_q8"] = {"ms": t_q, "GBps": g_q, "frac": g_q / HBM_PEAK_GBPS, "table_rows": rows_q8}
+        return res
+
+    if not args.no_hbm_anchor and S > 0 and X.numel() * 4 < (2 << 30):
+        roofline["hbm_anchor"] = {
+            "what": "the timed kernels (aes_spmm_f32, aes_spmm_q8) on the same plan rows and launch, columns uniformly "
+                    "random over a feature table of the given size (no reuse: algorithmic bytes = HBM bytes), measured "
+                    "in this run; per-node int8 scales, where used, are gathered over the same random nodes"}
+        for label, table_bytes in (("table_2GiB", 2 << 30), ("table_8GiB", 8 << 30)):
+            try:
+                torch.cuda.empty_cache()
+                free, _ = torch.cuda.mem_get_info()
+                if free < table_bytes + 4 * S + (4 << 30):
+                    raise RuntimeError(f"only {free >> 30} GiB free")
+                roofline["hbm_anchor"][label] = anchor(table_bytes)
+            except (RuntimeError, torch.OutOfMemoryError) as exc:   # never let the anchor cost the bench line
+                roofline["hbm_anchor"][label] = {"skipped": str(exc)[:200]}
     print(json.dumps(out))
     return 0
 
