@@ -188,6 +188,35 @@ __device__ inline RowInfo row_info(const SlotSource &src, int64_t r)
     return ri;
 }
 
+// Stages slots t0 .. t0 + m - 1 of the row in the group's LDS tile: a coalesced load of the (col, val)
+// pairs (from the plan, or sampled on the fly from the CSR row), per-node 8-bit constants folded into
+// the value, then the fences that make the tile visible to the whole group.
+template <int LPR, typename Feat, int QMODE, bool FUSED, typename AccT>
+__device__ __forceinline__ void stage_tile(const SlotSource &src, const RowInfo &ri, int2 *my_stage, int lane,
+                                           const QParams &qp, int64_t t0, int m, AccT &side)
+{
+    wave_lds_sync();                                 // previous tile fully consumed
+#pragma unroll
+    for (int s = lane; s < kTile; s += LPR) {
+        if (s < m) {
+            int64_t e = ri.k_begin + t0 + s;
+            if (FUSED && ri.sampled)
+                e = aes::sampled_entry(ri.k_begin, ri.row_nnz, ri.samp_n, ri.samp_cnt, ri.s_r,
+                                       static_cast<int32_t>(t0) + s);
+            const int32_t c = src.col[e];
+            float v = src.val[e];
+            if constexpr (QMODE == kQRowScale) {
+                if constexpr (QTraits<Feat, QMODE>::kAffine) side = fma_acc(v, qp.zero[c], side);
+                v *= qp.scale[c];
+            } else if constexpr (QTraits<Feat, QMODE>::kAffine) {
+                side += v;
+            }
+            my_stage[s] = make_int2(c, __float_as_int(v));
+        }
+    }
+    wave_lds_sync();                                 // tile visible to the whole group
+}
+
 // Adds the row's tiles first_tile, first_tile + tile_step, ... into acc (one chunk of
 // features).  side collects the zero-point sum the affine 8-bit epilogue needs.
 // PARTIAL: a lane may own fewer than VEC valid features (nv of them: the end of a row whose length is
@@ -212,26 +241,7 @@ __device__ __forceinline__ void accumulate_tiles(const SlotSource &src, const Ro
     auto row_of = [&](int32_t c) { return x_lane + static_cast<uint64_t>(static_cast<uint32_t>(c)) * ld; };
     for (int64_t t0 = first_tile * kTile; t0 < ri.n_slots; t0 += tile_step * kTile) {
         const int m = static_cast<int>(ri.n_slots - t0 < kTile ? ri.n_slots - t0 : kTile);
-        wave_lds_sync();                             // previous tile fully consumed
-#pragma unroll
-        for (int s = lane; s < kTile; s += LPR) {
-            if (s < m) {
-                int64_t e = ri.k_begin + t0 + s;
-                if (FUSED && ri.sampled)
-                    e = aes::sampled_entry(ri.k_begin, ri.row_nnz, ri.samp_n, ri.samp_cnt, ri.s_r,
-                                           static_cast<int32_t>(t0) + s);
-                const int32_t c = src.col[e];
-                float v = src.val[e];
-                if constexpr (QMODE == kQRowScale) {
-                    if constexpr (QTraits<Feat, QMODE>::kAffine) side = fma_acc(v, qp.zero[c], side);
-                    v *= qp.scale[c];
-                } else if constexpr (QTraits<Feat, QMODE>::kAffine) {
-                    side += v;
-                }
-                my_stage[s] = make_int2(c, __float_as_int(v));
-            }
-        }
-        wave_lds_sync();                             // tile visible to the whole group
+        stage_tile<LPR, Feat, QMODE, FUSED, AccT>(src, ri, my_stage, lane, qp, t0, m, side);
         if (lane_on) {
             // UNROLL gathers are issued back to back before the first one is consumed.
             int k = 0;
@@ -259,6 +269,45 @@ __device__ __forceinline__ void accumulate_tiles(const SlotSource &src, const Ro
                 }
 #pragma unroll
                 for (int u = 0; u < UNROLL; ++u) Feat::fma(acc, __int_as_float(cv[u].y), x[u]);
+            }
+        }
+    }
+}
+
+// The same for feature rows wider than one pass of the lane group: a lane owns NV vectors, LPR * VEC
+// features apart (f, f + LPR*VEC, ...; on[j] says which of them exist), and gathers all of them for a
+// slot together.  The slots are staged once for the NV * LPR * VEC features, and a gathered row is
+// read as one contiguous piece instead of once per pass.
+template <int LPR, int UNROLL, typename Feat, int QMODE, bool FUSED, typename AccT, int NV>
+__device__ __forceinline__ void accumulate_tiles_wide(const SlotSource &src, const RowInfo &ri, int2 *my_stage, int lane,
+                                                      const bool (&on)[NV], const typename Feat::elem_t *__restrict__ X,
+                                                      int64_t ldx, int32_t f, const QParams &qp, int64_t first_tile,
+                                                      int64_t tile_step, AccT (&acc)[NV][Feat::VEC], AccT &side)
+{
+    constexpr int kApart = LPR * Feat::VEC;
+    const uint32_t ld = static_cast<uint32_t>(ldx);
+    const typename Feat::elem_t *const x_lane = X + f;
+    auto row_of = [&](int32_t c) { return x_lane + static_cast<uint64_t>(static_cast<uint32_t>(c)) * ld; };
+    for (int64_t t0 = first_tile * kTile; t0 < ri.n_slots; t0 += tile_step * kTile) {
+        const int m = static_cast<int>(ri.n_slots - t0 < kTile ? ri.n_slots - t0 : kTile);
+        stage_tile<LPR, Feat, QMODE, FUSED, AccT>(src, ri, my_stage, lane, qp, t0, m, side);
+        if (on[0]) {
+            for (int k = 0; k < m; k += UNROLL) {
+                int2 cv[UNROLL];
+                typename Feat::raw_t x[UNROLL][NV];
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u) cv[u] = (k + u < m) ? my_stage[k + u] : make_int2(-1, 0);
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u)
+#pragma unroll
+                    for (int j = 0; j < NV; ++j) {
+                        x[u][j] = typename Feat::raw_t{};
+                        if (cv[u].x >= 0 && on[j]) x[u][j] = Feat::load(row_of(cv[u].x) + j * kApart);
+                    }
+#pragma unroll
+                for (int u = 0; u < UNROLL; ++u)
+#pragma unroll
+                    for (int j = 0; j < NV; ++j) Feat::fma(acc[j], __int_as_float(cv[u].y), x[u][j]);
             }
         }
     }

@@ -37,12 +37,14 @@ constexpr int kLongRow = 2048;
 //       fast paths, 1 otherwise)
 // QMODE how the constants of the 8-bit path are applied (kQNone: float32 features); FUSED: sample
 //       from the CSR on the fly
+// NV    vectors per lane and pass: 1 for rows of up to LPR * VEC features; 2 or 4 (with LPR = 64) for
+//       wider rows, so that the slots are staged once and a gathered row is read in one piece
 // LONG  rows above kLongRow slots are processed by the whole workgroup: its lane groups
 //       take the row's tiles round-robin and their partial sums (carried in float64,
 //       since such sums run over up to millions of terms) are added in a fixed order
 //       through LDS, so the result stays bit-reproducible.  Without LONG the kernel
 //       has no workgroup barrier at all.
-template <int LPR, int UNROLL, typename Feat, int QMODE, bool FUSED, bool LONG>
+template <int LPR, int UNROLL, typename Feat, int QMODE, bool FUSED, bool LONG, int NV = 1>
 __global__ void __launch_bounds__(kBlock)
 spmm_rows_kernel(int64_t n_rows, SlotSource src, const int32_t *__restrict__ row_perm,
                  const typename Feat::elem_t *__restrict__ X, int64_t ldx, int32_t F, QParams qp,
@@ -75,27 +77,52 @@ spmm_rows_kernel(int64_t n_rows, SlotSource src, const int32_t *__restrict__ row
     const bool is_long = LONG && valid && ri.n_slots > kLongRow;
 
     if (valid && !is_long) {
-        for (int32_t f0 = 0; f0 < F; f0 += LPR * VEC) {
-            const int32_t f = f0 + lane * VEC;
-            const bool lane_on = f < F;
-            float acc[VEC];
+        if constexpr (NV == 1) {
+            for (int32_t f0 = 0; f0 < F; f0 += LPR * VEC) {
+                const int32_t f = f0 + lane * VEC;
+                const bool lane_on = f < F;
+                float acc[VEC];
 #pragma unroll
-            for (int i = 0; i < VEC; ++i) acc[i] = 0.0f;
-            float side = 0.0f;      // this lane's share of sum(val * zero-point weight)
-            LaneConstants<Feat, QMODE> k;
-            if constexpr (kEarlyConstants) load_lane_constants<Feat, QMODE>(qp, f, lane_on, r, k);
-            accumulate_tiles<LPR, UNROLL, Feat, QMODE, FUSED, float>(src, ri, my_stage, lane, lane_on, X, ldx, f, qp, 0, 1,
-                                                                     acc, side);
-            if constexpr (!kEarlyConstants) load_lane_constants<Feat, QMODE>(qp, f, lane_on, r, k);
-            if constexpr (QTraits<Feat, QMODE>::kAffine) side = group_sum<LPR, float>(side);
-            finish_chunk<Feat, QMODE, float>(acc, side, lane_on, k, Y + r * ldy + f);
+                for (int i = 0; i < VEC; ++i) acc[i] = 0.0f;
+                float side = 0.0f;      // this lane's share of sum(val * zero-point weight)
+                LaneConstants<Feat, QMODE> k;
+                if constexpr (kEarlyConstants) load_lane_constants<Feat, QMODE>(qp, f, lane_on, r, k);
+                accumulate_tiles<LPR, UNROLL, Feat, QMODE, FUSED, float>(src, ri, my_stage, lane, lane_on, X, ldx, f, qp, 0,
+                                                                         1, acc, side);
+                if constexpr (!kEarlyConstants) load_lane_constants<Feat, QMODE>(qp, f, lane_on, r, k);
+                if constexpr (QTraits<Feat, QMODE>::kAffine) side = group_sum<LPR, float>(side);
+                finish_chunk<Feat, QMODE, float>(acc, side, lane_on, k, Y + r * ldy + f);
+            }
+        } else {
+            for (int32_t f0 = 0; f0 < F; f0 += NV * LPR * VEC) {
+                const int32_t f = f0 + lane * VEC;
+                bool on[NV];
+                float acc[NV][VEC];
+#pragma unroll
+                for (int j = 0; j < NV; ++j) {
+                    on[j] = f + j * LPR * VEC < F;
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i) acc[j][i] = 0.0f;
+                }
+                float side = 0.0f;
+                accumulate_tiles_wide<LPR, UNROLL, Feat, QMODE, FUSED, float, NV>(src, ri, my_stage, lane, on, X, ldx, f, qp,
+                                                                                  0, 1, acc, side);
+                if constexpr (QTraits<Feat, QMODE>::kAffine) side = group_sum<LPR, float>(side);
+#pragma unroll
+                for (int j = 0; j < NV; ++j) {
+                    const int32_t fj = f + j * LPR * VEC;
+                    LaneConstants<Feat, QMODE> k;
+                    load_lane_constants<Feat, QMODE>(qp, fj, on[j], r, k);
+                    finish_chunk<Feat, QMODE, float>(acc[j], side, on[j], k, Y + r * ldy + fj);
+                }
+            }
         }
     }
 
     if constexpr (LONG) {
         __shared__ int sh_n_long;
         __shared__ int64_t sh_long_row[kRowsPerBlock];
-        __shared__ double sh_part[kRowsPerBlock][LPR][VEC + 1];
+        __shared__ double sh_part[kRowsPerBlock][LPR][NV * VEC + 1];
         if (threadIdx.x == 0) sh_n_long = 0;
         __syncthreads();
         if (is_long && lane == 0) sh_long_row[atomicAdd(&sh_n_long, 1)] = r;   // order affects no sum
@@ -105,29 +132,45 @@ spmm_rows_kernel(int64_t n_rows, SlotSource src, const int32_t *__restrict__ row
         for (int i = 0; i < n_long; ++i) {
             const int64_t lr = sh_long_row[i];
             const RowInfo lri = row_info<FUSED>(src, lr);
-            for (int32_t f0 = 0; f0 < F; f0 += LPR * VEC) {
+            for (int32_t f0 = 0; f0 < F; f0 += NV * LPR * VEC) {
                 const int32_t f = f0 + lane * VEC;
-                const bool lane_on = f < F;
-                double acc[VEC];                         // long sums are carried in float64
+                bool on[NV];
+                double acc[NV][VEC];                     // long sums are carried in float64
 #pragma unroll
-                for (int j = 0; j < VEC; ++j) acc[j] = 0.0;
+                for (int j = 0; j < NV; ++j) {
+                    on[j] = f + j * LPR * VEC < F;
+#pragma unroll
+                    for (int q = 0; q < VEC; ++q) acc[j][q] = 0.0;
+                }
                 double side = 0.0;
-                accumulate_tiles<LPR, UNROLL, Feat, QMODE, FUSED, double>(src, lri, my_stage, lane, lane_on, X, ldx, f, qp,
-                                                                          gib, kRowsPerBlock, acc, side);
+                if constexpr (NV == 1)
+                    accumulate_tiles<LPR, UNROLL, Feat, QMODE, FUSED, double>(src, lri, my_stage, lane, on[0], X, ldx, f, qp,
+                                                                              gib, kRowsPerBlock, acc[0], side);
+                else
+                    accumulate_tiles_wide<LPR, UNROLL, Feat, QMODE, FUSED, double, NV>(src, lri, my_stage, lane, on, X, ldx,
+                                                                                       f, qp, gib, kRowsPerBlock, acc, side);
                 if constexpr (QTraits<Feat, QMODE>::kAffine) side = group_sum<LPR, double>(side);
 #pragma unroll
-                for (int j = 0; j < VEC; ++j) sh_part[gib][lane][j] = acc[j];
-                sh_part[gib][lane][VEC] = side;
+                for (int j = 0; j < NV; ++j)
+#pragma unroll
+                    for (int q = 0; q < VEC; ++q) sh_part[gib][lane][j * VEC + q] = acc[j][q];
+                sh_part[gib][lane][NV * VEC] = side;
                 __syncthreads();
                 if (gib == 0) {
                     for (int g = 1; g < kRowsPerBlock; ++g) {   // fixed order: bit-reproducible
 #pragma unroll
-                        for (int j = 0; j < VEC; ++j) acc[j] += sh_part[g][lane][j];
-                        side += sh_part[g][lane][VEC];
+                        for (int j = 0; j < NV; ++j)
+#pragma unroll
+                            for (int q = 0; q < VEC; ++q) acc[j][q] += sh_part[g][lane][j * VEC + q];
+                        side += sh_part[g][lane][NV * VEC];
                     }
-                    LaneConstants<Feat, QMODE> k;
-                    load_lane_constants<Feat, QMODE>(qp, f, lane_on, lr, k);
-                    finish_chunk<Feat, QMODE, double>(acc, side, lane_on, k, Y + lr * ldy + f);
+#pragma unroll
+                    for (int j = 0; j < NV; ++j) {
+                        const int32_t fj = f + j * LPR * VEC;
+                        LaneConstants<Feat, QMODE> k;
+                        load_lane_constants<Feat, QMODE>(qp, fj, on[j], lr, k);
+                        finish_chunk<Feat, QMODE, double>(acc[j], side, on[j], k, Y + lr * ldy + fj);
+                    }
                 }
                 __syncthreads();
             }
@@ -135,7 +178,7 @@ spmm_rows_kernel(int64_t n_rows, SlotSource src, const int32_t *__restrict__ row
     }
 }
 
-template <int LPR, int UNROLL, typename Feat, int QMODE, bool FUSED>
+template <int LPR, int UNROLL, typename Feat, int QMODE, bool FUSED, int NV = 1>
 inline int launch_rows(bool long_rows, int64_t n_rows, const SlotSource &src,
                 const int32_t *row_perm, const typename Feat::elem_t *X, int64_t ldx, int32_t F, QParams qp,
                 float *Y, int64_t ldy, hipStream_t stream, const char *what)
@@ -145,10 +188,10 @@ inline int launch_rows(bool long_rows, int64_t n_rows, const SlotSource &src,
     if (grid > INT32_MAX) return aes::fail(AES_ERR_UNSUPPORTED, "%s: n_rows=%lld too large", what, (long long)n_rows);
     const dim3 g(static_cast<unsigned>(grid)), b(kBlock);
     if (long_rows)
-        spmm_rows_kernel<LPR, UNROLL, Feat, QMODE, FUSED, true>
+        spmm_rows_kernel<LPR, UNROLL, Feat, QMODE, FUSED, true, NV>
             <<<g, b, 0, stream>>>(n_rows, src, row_perm, X, ldx, F, qp, Y, ldy);
     else
-        spmm_rows_kernel<LPR, UNROLL, Feat, QMODE, FUSED, false>
+        spmm_rows_kernel<LPR, UNROLL, Feat, QMODE, FUSED, false, NV>
             <<<g, b, 0, stream>>>(n_rows, src, row_perm, X, ldx, F, qp, Y, ldy);
     return aes::check_launch(what);
 }
@@ -169,6 +212,24 @@ int dispatch_lanes(bool lr, int64_t n_rows, const SlotSource &src, const int32_t
                    const typename Feat::elem_t *X, int64_t ldx, int32_t F, QParams qp, float *Y, int64_t ldy,
                    hipStream_t stream, const char *what)
 {
+    // Rows wider than one pass of 64 lanes (256 features): several vectors per lane, so that the slots are
+    // staged once and a gathered row is read in one piece.  8-bit codes (one register per gather): two
+    // vectors with sixteen gathers in flight, four vectors beyond 512 features (-22 % at F = 300 and 602).
+    // float32: only where the last of the 256-feature passes would be less than half full (-7 % at
+    // F = 300, -10 % at F = 602) - two vectors, three for 513..768 features, passes of 512 beyond; at
+    // whole multiples of 256 the plain passes are as fast or 3 % faster.
+    constexpr bool kCodes = sizeof(typename Feat::elem_t) == 1;
+    constexpr int kPass = kWave * Feat::VEC;
+    if constexpr (kCodes) {
+        if (F > 2 * kPass)
+            return launch_rows<64, 4, Feat, QMODE, FUSED, 4>(lr, n_rows, src, row_perm, X, ldx, F, qp, Y, ldy, stream, what);
+        if (F > kPass)
+            return launch_rows<64, 8, Feat, QMODE, FUSED, 2>(lr, n_rows, src, row_perm, X, ldx, F, qp, Y, ldy, stream, what);
+    } else if (F > kPass && 2 * (F - kPass * ((F - 1) / kPass)) <= kPass) {
+        if (F > 2 * kPass && F <= 3 * kPass)
+            return launch_rows<64, 3, Feat, QMODE, FUSED, 3>(lr, n_rows, src, row_perm, X, ldx, F, qp, Y, ldy, stream, what);
+        return launch_rows<64, 4, Feat, QMODE, FUSED, 2>(lr, n_rows, src, row_perm, X, ldx, F, qp, Y, ldy, stream, what);
+    }
     switch (lanes_per_row(F, Feat::VEC)) {
         case 8: return launch_rows<8, 8, Feat, QMODE, FUSED>(lr, n_rows, src, row_perm, X, ldx, F, qp, Y, ldy, stream, what);
         case 16: return launch_rows<16, 8, Feat, QMODE, FUSED>(lr, n_rows, src, row_perm, X, ldx, F, qp, Y, ldy, stream, what);

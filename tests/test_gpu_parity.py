@@ -96,7 +96,7 @@ def test_small_workloads(G, name):
             G.check_q8(plan, ref, xq[scheme][0], xq[scheme][1], scheme, w.q_granularity)
 
 
-@pytest.mark.parametrize("F", [1, 3, 4, 8, 20, 32, 50, 64, 100, 128, 192, 256, 260, 320, 512, 777])
+@pytest.mark.parametrize("F", [1, 3, 4, 8, 20, 32, 50, 64, 100, 128, 192, 256, 260, 320, 512, 602, 777, 1024, 1100, 2053])
 def test_feature_widths_and_alignment(G, F):
     rowptr, col, val, _, n_cols = _ragged_case(F, 32, n=300)
     rng = np.random.default_rng(F)
@@ -306,7 +306,7 @@ def test_hip_graph_capture_replays(G):
                 assert torch.equal(a, b), rep
 
 
-@pytest.mark.parametrize("F", [32, 96, 256, 320, 50])
+@pytest.mark.parametrize("F", [32, 96, 256, 320, 50, 602, 1300])
 @pytest.mark.parametrize("W", [0, 4096])
 def test_long_rows_shared_by_the_workgroup(G, F, W):
     """Rows above 2048 slots are split over all lane groups of a workgroup and
