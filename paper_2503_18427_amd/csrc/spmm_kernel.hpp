@@ -37,8 +37,9 @@ constexpr int kLongRow = 2048;
 //       fast paths, 1 otherwise)
 // QMODE how the constants of the 8-bit path are applied (kQNone: float32 features); FUSED: sample
 //       from the CSR on the fly
-// NV    vectors per lane and pass: 1 for rows of up to LPR * VEC features; 2 or 4 (with LPR = 64) for
-//       wider rows, so that the slots are staged once and a gathered row is read in one piece
+// NV    vectors per lane and pass: 1 for rows of up to LPR * VEC features; 2, 3 or 4 (with LPR = 64) for
+//       wider rows, so that the slots are staged once and a gathered row is read in one piece (which
+//       widths take which NV: dispatch_lanes)
 // LONG  rows above kLongRow slots are processed by the whole workgroup: its lane groups
 //       take the row's tiles round-robin and their partial sums (carried in float64,
 //       since such sums run over up to millions of terms) are added in a fixed order
