@@ -92,6 +92,29 @@ def test_row_offset_definition(oracle):
         assert oracle.row_offset(seed, r) == exp
 
 
+def test_row_offset_invariants(oracle):
+    """What the seed extension's offset must satisfy whatever its multiplier is written as (the build's
+    own addition to Eq. 3, so nothing printed pins it): it is a product of the seed, the odd number 2r+1
+    and an odd constant, reduced mod 2^32.  Hence: seed 0 gives 0 for every row (the paper's Eq. 3);
+    an odd seed gives odd offsets that are pairwise distinct over rows (multiplication by an odd number is
+    a bijection mod 2^32 and r -> 2r+1 is injective below 2^31); a seed with k trailing zero bits gives
+    offsets with exactly k trailing zero bits; and the offset is linear in the seed mod 2^32."""
+    rows = list(range(0, 4000)) + [2 ** 20 + 17, 2 ** 30 + 3, 2 ** 31 - 1]
+    assert all(oracle.row_offset(0, r) == 0 for r in rows)
+    for seed in (1, 3, 0x9E3779B97F4A7C15, 2 ** 64 - 1):
+        offs = [oracle.row_offset(seed, r) for r in rows]
+        assert all(o % 2 == 1 for o in offs)
+        assert len(set(offs)) == len(offs)
+    for k in (1, 5, 17, 31):
+        for odd in (1, 12345677):
+            for r in (0, 1, 99, 2 ** 25 + 1):
+                o = oracle.row_offset(odd << k, r)
+                assert o % (1 << k) == 0 and (o >> k) % 2 == 1
+    assert oracle.row_offset(1 << 32, 7) == 0                   # the seed's high half only shifts the product out
+    for a, b, r in ((5, 11, 3), (2 ** 40 + 9, 77, 123456)):
+        assert (oracle.row_offset(a, r) + oracle.row_offset(b, r)) % 2 ** 32 == oracle.row_offset(a + b, r)
+
+
 @pytest.mark.parametrize("W", [1, 4, 16, 32, 48, 64, 256])
 @pytest.mark.parametrize("seed", [0, 1234567])
 def test_plan_invariants(oracle, W, seed):
