@@ -145,7 +145,8 @@ gcn_layer_kernel(int64_t n_rows, SlotSource src, const typename Feat::elem_t *__
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int64_t r_base = row0 + 8 * (v / 4) + (v % 4);     // uniform; this lane's row is r_base + 4h
-                if (r_base + 4 * h < n_rows) (H + r_base * ldh)[out_off] = c[v];
+                // streaming store: H is written once and must not take cache space from the gathered rows
+                if (r_base + 4 * h < n_rows) __builtin_nontemporal_store(c[v], &(H + r_base * ldh)[out_off]);
             }
         }
         const int next = nb + kWavesPerBlock;        // a further column block of this wave: its first chunks
@@ -318,7 +319,7 @@ gcn_layer_wide_kernel(int64_t n_rows, SlotSource src, const typename Feat::elem_
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int64_t r = row0 + 8 * (v / 4) + 4 * h + (v % 4);
-                if (r < n_rows) H[r * ldh + col] = c[j][v];
+                if (r < n_rows) __builtin_nontemporal_store(c[j][v], &H[r * ldh + col]);
             }
         }
     }
