@@ -603,3 +603,86 @@ def test_gcn_layer_on_8bit_features(G, scheme, gran, F, Fo):
         Hf = aes.aes_gcn_layer_q8(fplan, qd[0], scheme, aes.AES_Q_PER_ROW_FOLDED, None, bias, G.to_dev(Theta))
         torch.cuda.synchronize()
         assert float((Hf - H).abs().max()) < 1e-4
+
+
+def test_random_shapes_sweep(G):
+    """Two hundred seeded random combinations of graph shape (degree mixes with empty rows, rows
+    around the tile, unroll and long-row boundaries, hubs), feature width, leading-dimension
+    padding, W, seed, granularity and 8-bit scheme: plan bit-exact, both multiplies against the
+    oracle, the one-kernel forms bit-identical to build + multiply, and every third case through
+    the fused layer.  Sizes keep every output away from total cancellation (>= 17 rows, >= 64
+    columns), so the whole-matrix error figure stays meaningful."""
+    import oracle as orc
+    import paper_2503_18427_amd as aes
+
+    def degrees(rng, n):
+        kind = int(rng.integers(0, 5))
+        if kind == 0:
+            return rng.integers(0, 12, size=n)
+        if kind == 1:
+            return rng.integers(0, 300, size=n)
+        if kind == 2:
+            return np.minimum((rng.pareto(1.2, size=n) * 4).astype(np.int64), 6000)
+        if kind == 3:
+            return rng.choice([0, 1, 2, 63, 64, 65, 127, 128, 129, 255, 256, 257, 511, 512, 513, 1023, 1025, 2047,
+                               2048, 2049], size=n)
+        d = rng.integers(0, 40, size=n)
+        d[rng.integers(0, n, size=max(1, n // 50))] = rng.integers(2000, 9000)
+        return d
+
+    widths = [1, 2, 3, 4, 5, 7, 8, 12, 16, 31, 32, 33, 60, 64, 100, 127, 128, 129, 192, 255, 256, 257, 300, 384, 511,
+              512, 513, 602, 640, 768, 769, 1000, 1024, 1025, 1500]
+    Ws = [0, 1, 2, 3, 4, 5, 8, 15, 16, 17, 31, 32, 33, 48, 64, 65, 100, 128, 200, 256, 512, 1000, 1024, 2048, 2049,
+          3000, 4096]
+    for case in range(200):
+        rng = np.random.default_rng(20250318 + case)
+        n = int(rng.choice([17, 63, 64, 65, 100, 255, 256, 257, 300]))
+        n_cols = int(rng.choice([64, 333, 1000, 4000]))
+        d = degrees(rng, n).astype(np.int64)
+        if d.sum() > 300_000:
+            d //= 4
+        F, W = int(rng.choice(widths)), int(rng.choice(Ws))
+        seed = int(rng.choice([0, 1, 2, 77, 0x9E3779B97F4A7C15, 2 ** 63 + 5]))
+        strategy = int(rng.choice([0, 0, 0, 1, 2]))
+        padl, padr = int(rng.integers(0, 4)), int(rng.integers(0, 6))
+        scheme, gran = int(rng.choice([SYM, AFF])), int(rng.integers(0, 3))
+        what = (case, n, n_cols, int(d.sum()), F, W, seed, strategy, padl, padr, scheme, gran)
+        rowptr, col, val = random_csr(n, n_cols, d, rng, sort_cols=bool(rng.integers(0, 2)))
+        X = (rng.standard_normal((n_cols, F)) * rng.uniform(0.1, 8.0, size=(n_cols, 1))).astype(np.float32)
+        if rng.integers(0, 4) == 0:
+            X[rng.integers(0, n_cols)] = 0.0
+        try:
+            plan, ref = G.check_plan(rowptr, col, val, n_cols, W, seed, strategy)
+            Xb = torch.zeros((n_cols, F + padl + padr), device="cuda")
+            Xb[:, padl:padl + F] = G.to_dev(X)
+            Xv = Xb[:, padl:padl + F]
+            use_perm = bool(rng.integers(0, 2))
+            Y, _, _ = G.check_f32(plan, ref, Xv, use_perm=use_perm)
+            csr = (G.to_dev(rowptr), G.to_dev(col), G.to_dev(val))
+            Yf = aes.aes_spmm_fused_f32(*csr, n_cols, W, Xv, seed, strategy=strategy)
+            assert torch.equal(Y, Yf), "one-kernel float32 form differs from build + multiply"
+            qd, qr = G.check_quantize(X, scheme, gran)
+            Yq, _, _ = G.check_q8(plan, ref, qd, qr, scheme, gran, use_perm=use_perm)
+            Yqf = aes.aes_spmm_fused_q8(*csr, n_cols, W, qd[0], scheme, gran, qd[1], qd[2], seed, strategy=strategy)
+            assert torch.equal(Yq, Yqf), "one-kernel 8-bit form differs from build + multiply"
+            if case % 3 == 0:
+                Fo = int(rng.choice([1, 7, 32, 33, 64, 100, 128, 256, 300, 513, 600]))
+                Theta = (rng.standard_normal((F, Fo)) / np.sqrt(F)).astype(np.float32)
+                H = aes.aes_gcn_layer_f32(plan, Xv, G.to_dev(Theta))
+                torch.cuda.synchronize()
+                Href, Habs = _layer_reference(orc, ref, X, Theta)
+                comp = float(np.max(np.abs(H.cpu().numpy() - Href) / np.where(Habs > 0, Habs, 1.0)))
+                assert comp <= LAYER_TOL, ("layer float32", Fo, comp)
+                Hq = aes.aes_gcn_layer_q8(plan, qd[0], scheme, gran, qd[1], qd[2], G.to_dev(Theta))
+                torch.cuda.synchronize()
+                Yr, Ya = orc.spmm_q8(ref[0], ref[1], ref[2], qr[0], scheme, gran, qr[1], qr[2], want_abs=True)
+                if scheme == AFF:
+                    sc = {0: qr[1][0], 1: qr[1][None, :], 2: qr[1][:, None]}[gran]
+                    zr = {0: qr[2][0], 1: qr[2][None, :], 2: qr[2][:, None]}[gran]
+                    mag = np.zeros(X.shape, np.float32) + (np.abs(qr[0].astype(np.float32) * sc) + np.abs(zr))
+                    Ya = orc.spmm_plan(ref[0], ref[1], np.abs(ref[2]), mag.astype(np.float32))
+                Hqa = orc.combine(Ya, np.abs(Theta))
+                comp = float(np.max(np.abs(Hq.cpu().numpy() - orc.combine(Yr, Theta)) / np.where(Hqa > 0, Hqa, 1.0)))
+                assert comp <= G.Q8_TOL, ("layer 8-bit", Fo, comp)
+        except AssertionError as e:
+            raise AssertionError(f"case (index, n, n_cols, nnz, F, W, seed, strategy, pad, pad, scheme, gran) = {what}: {e}")
