@@ -97,6 +97,30 @@ def test_rmat20(G):
     _run(G, "rmat20", (16, 32, 64, 128, 256), schemes=(SYM,))
 
 
+def test_reddit_like_with_602_features(G):
+    """The reddit-shaped graph at the width of the paper's Reddit features (602, Table 2): neither a
+    multiple of 256 nor of 4, so the multiplies take their several-vectors-per-lane variants and the
+    layer its general kernel, here over 233 000 rows instead of a few hundred.  Every row of Y
+    (float32 and 8-bit), sampled rows of the fused layer."""
+    from workloads import configs, graphs
+    import paper_2503_18427_amd as aes
+    w = configs.WORKLOADS["reddit_like"]
+    rowptr, colidx, val = configs.make_graph(w, "cuda")
+    F, W = 602, 64
+    X = graphs.features(w.n, F, w.x_dist, w.seed + 1000, torch.device("cuda"))
+    d = {"n": w.n, "F": F, "X": X}
+    print(f"[reddit_like F=602] n={w.n} nnz={int(colidx.numel())}", flush=True)
+    plan, ref = G.check_plan(rowptr, colidx, val, w.n, W, 0)
+    Y, c, g = G.check_f32(plan, ref, X, use_perm=False)
+    print(f"[reddit_like F=602] fp32 err on all rows comp={c:.2e} glob={g:.2e}", flush=True)
+    assert torch.equal(aes.aes_spmm_fused_f32(rowptr, colidx, val, w.n, W, X), Y)
+    q = G.check_quantize(X, SYM, w.q_granularity)
+    _, c, g = G.check_q8(plan, ref, q[0], q[1], SYM, w.q_granularity, use_perm=False)
+    print(f"[reddit_like F=602] int8 err on all rows comp={c:.2e} glob={g:.2e}", flush=True)
+    rows = np.sort(np.random.default_rng(2).choice(w.n, size=N_ROWS_CHECKED, replace=False)).astype(np.int64)
+    _check_layer(G, "reddit_like F=602", d, plan, ref, X.cpu().numpy(), q, w.q_granularity, rows, Fo=128)
+
+
 def test_entry_indices_beyond_2_31(G):
     """A matrix with 2.6 billion stored entries (48 rows of 54 M): every sampled
     entry index needs 64 bits.  Plan (with source indices) bit-exact against the
