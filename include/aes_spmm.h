@@ -11,7 +11,9 @@
  *   - Pointers marked [dev] are DEVICE pointers on the current HIP device;
  *     [host] pointers are ordinary host memory.  The library never allocates,
  *     frees or keeps device memory: all buffers, workspaces included, are owned
- *     by the caller and may be released once the stream has passed the call.
+ *     by the caller and may be released once the stream has passed the call
+ *     (the one exception, a fixed array inside the code object, is described
+ *     with aes_sample_build_noalloc).
  *   - Every call is asynchronous: it enqueues kernels on `stream` (a
  *     hipStream_t passed as void*, NULL = the default stream) and returns.  It
  *     never synchronises.  Calls on different streams may run concurrently as
