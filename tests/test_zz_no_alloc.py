@@ -62,3 +62,26 @@ def test_noalloc_matches_workspace_entry_point_twice():
     rc = aes.library().aes_sample_build_noalloc(aes.AES_NOALLOC_MAX_ROWS + 1, 4, 0, rp.data_ptr(), None, None, 4, 0, 0,
                                                 rp.data_ptr(), None, None, None, None, None)
     assert rc == -2 and "built-in scratch" in aes.aes_last_error()
+
+
+def test_noalloc_at_its_row_limit():
+    """AES_NOALLOC_MAX_ROWS rows (the whole built-in array is in use), short rows with a few long ones."""
+    import paper_2503_18427_amd as aes
+
+    n_rows, n_cols, W = aes.AES_NOALLOC_MAX_ROWS, 1_000_000, 4
+    g = torch.Generator(device="cuda")
+    g.manual_seed(11)
+    deg = torch.randint(0, 7, (n_rows,), dtype=torch.int64, device="cuda", generator=g)
+    deg[torch.randint(0, n_rows, (64,), device="cuda", generator=g)] = 5000
+    rowptr = torch.zeros(n_rows + 1, dtype=torch.int64, device="cuda")
+    torch.cumsum(deg, 0, out=rowptr[1:])
+    nnz = int(rowptr[-1].item())
+    colidx = torch.randint(0, n_cols, (nnz,), dtype=torch.int32, device="cuda", generator=g)
+    val = torch.rand(nnz, device="cuda", generator=g)
+    print(f"noalloc limit case n_rows={n_rows} nnz={nnz}", flush=True)
+    ref = aes.aes_sample_build(rowptr, colidx, val, n_cols, W, 5, want_eid=True, want_perm=True)
+    buf = aes.Plan(n_rows, n_cols, W, torch.empty_like(ref.s_rowptr), torch.empty_like(ref.s_col),
+                   torch.empty_like(ref.s_val), torch.empty_like(ref.s_eid), torch.empty_like(ref.row_perm))
+    got = aes.aes_sample_build_noalloc(rowptr, colidx, val, n_cols, W, 5, out=buf)
+    torch.cuda.synchronize()
+    _same(got, ref, int(ref.s_rowptr[-1].item()))
