@@ -8,6 +8,7 @@ loaded the import of a function's first call raises.
 """
 from .binding import (  # noqa: F401
     AES_NOALLOC_MAX_ROWS,
+    AES_MAX_W,
     AES_Q_AFFINE_FLOOR_U8,
     AES_Q_PER_COLUMN,
     AES_Q_PER_ROW,

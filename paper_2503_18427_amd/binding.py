@@ -15,6 +15,7 @@ AES_Q_PER_TENSOR, AES_Q_PER_COLUMN, AES_Q_PER_ROW, AES_Q_PER_ROW_FOLDED = 0, 1, 
 AES_Q_AFFINE_FLOOR_U8, AES_Q_SYMMETRIC_RNE_I8 = 0, 1
 AES_STRATEGY_ADAPTIVE, AES_STRATEGY_AFS, AES_STRATEGY_SFS = 0, 1, 2
 AES_NOALLOC_MAX_ROWS = 1 << 24
+AES_MAX_W = 1 << 20
 
 _i64, _i32, _u64, _vp, _sz = ctypes.c_int64, ctypes.c_int32, ctypes.c_uint64, ctypes.c_void_p, ctypes.c_size_t
 

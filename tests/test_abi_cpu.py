@@ -28,6 +28,17 @@ def test_header_symbols_exported(lib):
         assert hasattr(lib, n), n
 
 
+def test_binding_constants_equal_the_headers():
+    """Every enumerator of include/aes_spmm.h has the same value under the same name in the binding."""
+    import paper_2503_18427_amd as aes
+    text = open(os.path.join(ROOT, "include", "aes_spmm.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    found = dict(re.findall(r"\b(AES_[A-Z0-9_]+)\s*=\s*([-0-9 <]+?)\s*[,}\n]", text))
+    assert len(found) == 16, found
+    for name, expr in found.items():
+        assert getattr(aes.binding, name) == eval(expr, {"__builtins__": {}}), name
+
+
 def test_no_oracle_in_product():
     """The product package must not reach the oracle (or any CPU fallback)."""
     pkg = os.path.join(ROOT, "paper_2503_18427_amd")

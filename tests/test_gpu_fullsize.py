@@ -209,3 +209,36 @@ def test_papers_like_scale(G):
     comp, glob = rel_err(Yq[rt].cpu().numpy(), Yqref, Yqabs)
     print(f"[papers_like] int8 err comp={comp:.2e} glob={glob:.2e}", flush=True)
     assert comp <= G.Q8_TOL and glob <= G.Q8_TOL
+
+
+def test_stated_maxima_of_F_and_W(G):
+    """The largest feature width the entry points accept (2^24 - 1: odd, so the element-wise tail
+    launch runs too) on a four-row matrix, and the largest sampling width (AES_MAX_W = 2^20) on a
+    row of three million entries, which Table 1 samples down to 2^20 slots shared by the workgroup."""
+    import paper_2503_18427_amd as aes
+    rng = np.random.default_rng(9)
+    F = 2 ** 24 - 1
+    rowptr = np.array([0, 3, 3, 4, 9], dtype=np.int64)
+    col = np.array([2, 0, 1, 1, 0, 2, 2, 1, 0], dtype=np.int32)
+    val = rng.standard_normal(9).astype(np.float32)
+    X = rng.standard_normal((3, F)).astype(np.float32)
+    print("[maxima] F = 2^24 - 1", flush=True)
+    plan, ref = G.check_plan(rowptr, col, val, 3, 4, 0)
+    G.check_f32(plan, ref, X)
+    qd, qr = G.check_quantize(X, SYM, 2)
+    G.check_q8(plan, ref, qd, qr, SYM, 2)
+    del X, qd, qr, plan, ref
+    W = aes.AES_MAX_W
+    deg = np.array([3_000_000, 5, 0, W, W + 1], dtype=np.int64)
+    n_cols, F = 50_000, 96
+    rowptr = np.concatenate([[0], np.cumsum(deg)]).astype(np.int64)
+    col = rng.integers(0, n_cols, size=int(rowptr[-1])).astype(np.int32)
+    val = rng.standard_normal(int(rowptr[-1])).astype(np.float32)
+    X = rng.standard_normal((n_cols, F)).astype(np.float32)
+    print("[maxima] W = 2^20", flush=True)
+    plan, ref = G.check_plan(rowptr, col, val, n_cols, W, 0)
+    assert int(ref[0][1]) == W and int(ref[0][-1] - ref[0][-2]) == W       # both long rows sampled to W slots
+    Y, _, _ = G.check_f32(plan, ref, X)
+    Yf = aes.aes_spmm_fused_f32(G.to_dev(rowptr), G.to_dev(col), G.to_dev(val), n_cols, W, G.to_dev(X))
+    torch.cuda.synchronize()
+    assert torch.equal(Y, Yf)
