@@ -242,3 +242,50 @@ def test_stated_maxima_of_F_and_W(G):
     Yf = aes.aes_spmm_fused_f32(G.to_dev(rowptr), G.to_dev(col), G.to_dev(val), n_cols, W, G.to_dev(X))
     torch.cuda.synchronize()
     assert torch.equal(Y, Yf)
+
+
+def test_column_indices_up_to_2_31(G):
+    """n_cols = 2^31 - 1, the largest the entry points accept: gathers from feature rows whose index
+    has bit 30 set, up to the last one, float32 (17 GB table, only the referenced rows are
+    initialised and read) and 8-bit with per-column constants.  The oracle sees the referenced rows
+    as a compact table."""
+    import oracle as orc
+    import paper_2503_18427_amd as aes
+    from helpers import rel_err
+    n_cols, F = 2 ** 31 - 1, 2
+    free, _ = torch.cuda.mem_get_info()
+    if free < 30 * 2 ** 30:
+        pytest.skip("needs about 22 GiB of free GPU memory")
+    rng = np.random.default_rng(12)
+    cols = np.array([0, 12345, 2 ** 30 - 1, 2 ** 30, 2 ** 30 + 77, 3 * 2 ** 29, 2 ** 31 - 3, 2 ** 31 - 2], dtype=np.int64)
+    deg = np.array([5, 0, 8, 3, 70], dtype=np.int64)
+    rowptr = np.concatenate([[0], np.cumsum(deg)]).astype(np.int64)
+    pick = rng.integers(0, cols.size, size=int(rowptr[-1]))
+    pick[:cols.size] = np.arange(cols.size)                  # every special column occurs
+    col = cols[pick].astype(np.int32)
+    val = rng.standard_normal(col.size).astype(np.float32)
+    Xc = rng.standard_normal((cols.size, F)).astype(np.float32)
+    print("[2^31 columns] allocating", flush=True)
+    X = torch.empty((n_cols, F), dtype=torch.float32, device="cuda")
+    X[torch.from_numpy(cols).cuda()] = torch.from_numpy(Xc).cuda()
+    W = 16
+    plan = aes.aes_sample_build(G.to_dev(rowptr), G.to_dev(col), G.to_dev(val), n_cols, W, 0)
+    ref = orc.sample_build(rowptr, pick.astype(np.int32), val, W, seed=0)      # same plan over the compact table
+    S = int(ref[0][-1])
+    assert np.array_equal(plan.s_rowptr.cpu().numpy(), ref[0])
+    assert np.array_equal(plan.s_col[:S].cpu().numpy(), cols[ref[1]].astype(np.int32))
+    Y = aes.aes_spmm_f32(plan, X)
+    Yf = aes.aes_spmm_fused_f32(G.to_dev(rowptr), G.to_dev(col), G.to_dev(val), n_cols, W, X)
+    torch.cuda.synchronize()
+    Yref, Yabs = orc.spmm_plan(ref[0], ref[1], ref[2], Xc, want_abs=True)
+    comp, glob = rel_err(Y.cpu().numpy(), Yref, Yabs)
+    assert comp <= G.F32_TOL and glob <= G.F32_TOL and torch.equal(Y, Yf), (comp, glob)
+    del X
+    q, s, z = orc.quantize(Xc, SYM, 1)
+    Xq = torch.empty((n_cols, F), dtype=torch.int8, device="cuda")
+    Xq[torch.from_numpy(cols).cuda()] = torch.from_numpy(q).cuda()
+    Yq = aes.aes_spmm_q8(plan, Xq, SYM, 1, G.to_dev(s), G.to_dev(z))
+    torch.cuda.synchronize()
+    Yqref, Yqabs = orc.spmm_q8(ref[0], ref[1], ref[2], q, SYM, 1, s, z, want_abs=True)
+    comp, glob = rel_err(Yq.cpu().numpy(), Yqref, Yqabs)
+    assert comp <= G.Q8_TOL and glob <= G.Q8_TOL, (comp, glob)
