@@ -289,3 +289,46 @@ def test_column_indices_up_to_2_31(G):
     Yqref, Yqabs = orc.spmm_q8(ref[0], ref[1], ref[2], q, SYM, 1, s, z, want_abs=True)
     comp, glob = rel_err(Yq.cpu().numpy(), Yqref, Yqabs)
     assert comp <= G.Q8_TOL and glob <= G.Q8_TOL, (comp, glob)
+
+
+def test_largest_leading_dimensions(G):
+    """Feature matrices whose rows are 2^32 - 1 elements apart (the largest leading dimension the
+    gathers accept) and an output whose rows are more than 2^32 elements apart: only the F
+    columns in use are ever touched, so the buffers are allocated and never filled."""
+    import oracle as orc
+    import paper_2503_18427_amd as aes
+    from helpers import rel_err
+    free, _ = torch.cuda.mem_get_info()
+    if free < 130 * 2 ** 30:
+        pytest.skip("needs about 100 GiB of free GPU memory")
+    rng = np.random.default_rng(13)
+    n_cols, F, ld = 3, 8, 2 ** 32 - 1
+    rowptr = np.array([0, 4, 4, 9], dtype=np.int64)
+    col = rng.integers(0, n_cols, size=9).astype(np.int32)
+    val = rng.standard_normal(9).astype(np.float32)
+    Xh = rng.standard_normal((n_cols, F)).astype(np.float32)
+    print("[largest ld] allocating", flush=True)
+    buf = torch.empty(((n_cols - 1) * ld + F,), dtype=torch.float32, device="cuda")
+    X = torch.as_strided(buf, (n_cols, F), (ld, 1))
+    X.copy_(torch.from_numpy(Xh).cuda())
+    ldy = 2 ** 32 + 5
+    ybuf = torch.empty((2 * ldy + F,), dtype=torch.float32, device="cuda")
+    Y = torch.as_strided(ybuf, (3, F), (ldy, 1))
+    plan, ref = G.check_plan(rowptr, col, val, n_cols, 4, 0)
+    aes.aes_spmm_f32(plan, X, Y)
+    torch.cuda.synchronize()
+    Yref, Yabs = orc.spmm_plan(ref[0], ref[1], ref[2], Xh, want_abs=True)
+    comp, glob = rel_err(Y.cpu().numpy(), Yref, Yabs)
+    assert comp <= G.F32_TOL and glob <= G.F32_TOL, (comp, glob)
+    # quantise from, and multiply with, the strided operands
+    qbuf = torch.empty(((n_cols - 1) * ld + F,), dtype=torch.int8, device="cuda")
+    Xq = torch.as_strided(qbuf, (n_cols, F), (ld, 1))
+    rq, rs, rz = orc.quantize(Xh, SYM, 2)
+    got = aes.aes_quantize_features(X, SYM, 2, out=(Xq, torch.empty(n_cols, device="cuda"), torch.empty(n_cols, device="cuda")))
+    torch.cuda.synchronize()
+    assert np.array_equal(got[0].cpu().numpy(), rq) and np.array_equal(got[1].cpu().numpy().view(np.uint32), rs.view(np.uint32))
+    aes.aes_spmm_q8(plan, Xq, SYM, 2, got[1], got[2], Y)
+    torch.cuda.synchronize()
+    Yqref, Yqabs = orc.spmm_q8(ref[0], ref[1], ref[2], rq, SYM, 2, rs, rz, want_abs=True)
+    comp, glob = rel_err(Y.cpu().numpy(), Yqref, Yqabs)
+    assert comp <= G.Q8_TOL and glob <= G.Q8_TOL, (comp, glob)
