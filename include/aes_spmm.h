@@ -55,10 +55,30 @@ typedef enum aes_q_granularity {
     AES_Q_PER_TENSOR = 0,      /* 1 group                                        */
     AES_Q_PER_COLUMN = 1,      /* F groups, one per feature column               */
     AES_Q_PER_ROW = 2,         /* n groups, one per node                         */
-    AES_Q_PER_ROW_FOLDED = 3   /* aes_spmm_q8 only: per-node constants already    */
+    AES_Q_PER_ROW_FOLDED = 3,  /* aes_spmm_q8 only: per-node constants already    */
                                /* folded into the plan's values, see              */
                                /* aes_plan_fold_row_constants                     */
+    AES_Q_PER_ROW_INLINE = 4   /* n groups, one per node, the constants stored in  */
+                               /* the node's own row of codes: see below           */
 } aes_q_granularity;
+
+/*
+ * AES_Q_PER_ROW_INLINE: per-node constants that travel with the node's codes.
+ * Row i of Xq holds its F codes, padding up to byte 4*ceil(F/4), there the
+ * float32 scale of node i and, for AES_Q_AFFINE_FLOOR_U8, its float32 zero
+ * point in the next four bytes.  It needs ldq >= 4*ceil(F/4) + 4 (+ 8 for the
+ * affine scheme), ldq a multiple of 4 and Xq 4-byte aligned (else
+ * AES_ERR_INVALID_ARG); the scale / zero arguments are ignored and may be NULL.
+ * Why: with AES_Q_PER_ROW the multiply gathers scale[col] for every slot from
+ * an array of its own, a second memory line per slot.  Inside the row the
+ * constants come with a line the gather fetches anyway WHEN THE ROW HAS ROOM
+ * for them in its last 128-byte line (F = 100, 500, 602 ... with ldq rounded up
+ * to a multiple of 128); a row of exactly 128 or 256 codes has none, its
+ * constants would start a line of their own, and AES_Q_PER_ROW (or the folded
+ * plan) is the better choice there.  aes_quantize_inline_ld gives the smallest
+ * such leading dimension that is a multiple of 128.
+ */
+int64_t aes_quantize_inline_ld(int32_t F, int32_t scheme);
 
 typedef enum aes_q_scheme {
     /* Sec. 2.3 Eq. 1-2 with b = 8: q = floor((x-x_min)/(x_max-x_min)*255) in
@@ -223,7 +243,8 @@ size_t aes_quantize_workspace_bytes(int64_t n, int32_t F, int32_t granularity);
  *                for AFFINE_FLOOR_U8, int8 for SYMMETRIC_RNE_I8)
  *   scale [dev]  out, 1 | F | n float32 according to granularity
  *   zero  [dev]  out, same count; may be NULL for SYMMETRIC_RNE_I8 (written
- *                as 0 otherwise)
+ *                as 0 otherwise).  AES_Q_PER_ROW_INLINE: both ignored, the
+ *                constants are written into the rows of Xq
  *   workspace [dev] aes_quantize_workspace_bytes() bytes, 4-byte aligned; may
  *                be NULL when that is 0
  */
@@ -240,8 +261,8 @@ int aes_quantize_features(int64_t n, int32_t F, const float *X, int64_t ldx,
  * unnecessary; it exists to measure what the fusion saves.
  *
  *   Xq [dev] n x F bytes (ldq); scale, zero [dev] as written by
- *   aes_quantize_features (zero may be NULL for SYMMETRIC_RNE_I8);
- *   X [dev] out, n x F float32 (ldx)
+ *   aes_quantize_features (zero may be NULL for SYMMETRIC_RNE_I8; both
+ *   ignored for AES_Q_PER_ROW_INLINE); X [dev] out, n x F float32 (ldx)
  */
 int aes_dequantize_features(int64_t n, int32_t F, const int8_t *Xq, int64_t ldq,
                             int32_t scheme, int32_t granularity,
@@ -262,7 +283,8 @@ int aes_dequantize_features(int64_t n, int32_t F, const int8_t *Xq, int64_t ldq,
  *   Xq    [dev]  n_cols x F bytes, leading dimension ldq
  *   scale, zero [dev]  as written by aes_quantize_features; zero may be NULL
  *                for SYMMETRIC_RNE_I8 (for AES_Q_PER_ROW_FOLDED see
- *                aes_plan_fold_row_constants)
+ *                aes_plan_fold_row_constants; ignored for
+ *                AES_Q_PER_ROW_INLINE, which reads them from the rows of Xq)
  * Other arguments as aes_spmm_f32, including the treatment of F % 4 columns;
  * Xq and ldq need no particular alignment.
  */
@@ -358,7 +380,7 @@ int aes_gcn_layer_f32(int64_t n_rows, int64_t n_cols, int32_t W,
 /*
  * The same layer on 8-bit features: H = (A_s x_hat) Theta with the dequantisation of Sec. 2.3
  * Eq. 2 fused into the gather exactly as in aes_spmm_q8 (same scheme / granularity / scale /
- * zero arguments, AES_Q_PER_ROW_FOLDED included), the aggregated tile multiplied by Theta on
+ * zero arguments, AES_Q_PER_ROW_FOLDED and AES_Q_PER_ROW_INLINE included), the aggregated tile multiplied by Theta on
  * the matrix cores.  Any F, as for aes_gcn_layer_f32; Xq and ldq need no particular alignment.
  */
 int aes_gcn_layer_q8(int64_t n_rows, int64_t n_cols, int32_t W,

@@ -13,6 +13,7 @@ from .binding import (  # noqa: F401
     AES_Q_PER_COLUMN,
     AES_Q_PER_ROW,
     AES_Q_PER_ROW_FOLDED,
+    AES_Q_PER_ROW_INLINE,
     AES_Q_PER_TENSOR,
     AES_Q_SYMMETRIC_RNE_I8,
     AES_STRATEGY_ADAPTIVE,
@@ -26,6 +27,7 @@ from .binding import (  # noqa: F401
     aes_last_error,
     aes_plan_fold_row_constants,
     aes_quantize_features,
+    aes_quantize_inline_ld,
     aes_quantize_workspace_bytes,
     aes_sample_build,
     aes_sample_build_noalloc,

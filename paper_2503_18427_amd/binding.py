@@ -11,7 +11,7 @@ import torch
 from . import build as _build
 
 AES_OK, AES_ERR_INVALID_ARG, AES_ERR_UNSUPPORTED, AES_ERR_WORKSPACE, AES_ERR_HIP = 0, -1, -2, -3, -4
-AES_Q_PER_TENSOR, AES_Q_PER_COLUMN, AES_Q_PER_ROW, AES_Q_PER_ROW_FOLDED = 0, 1, 2, 3
+AES_Q_PER_TENSOR, AES_Q_PER_COLUMN, AES_Q_PER_ROW, AES_Q_PER_ROW_FOLDED, AES_Q_PER_ROW_INLINE = 0, 1, 2, 3, 4
 AES_Q_AFFINE_FLOOR_U8, AES_Q_SYMMETRIC_RNE_I8 = 0, 1
 AES_STRATEGY_ADAPTIVE, AES_STRATEGY_AFS, AES_STRATEGY_SFS = 0, 1, 2
 AES_NOALLOC_MAX_ROWS = 1 << 24
@@ -34,6 +34,7 @@ SIGNATURES = {
                                          _vp, _vp, _vp, _i64, _vp]),
     "aes_spmm_f32": (ctypes.c_int, [_i64, _i64, _i32, _vp, _vp, _vp, _vp, _vp, _i64, _i32, _vp, _i64, _vp]),
     "aes_quantize_workspace_bytes": (_sz, [_i64, _i32, _i32]),
+    "aes_quantize_inline_ld": (_i64, [_i32, _i32]),
     "aes_quantize_features": (ctypes.c_int, [_i64, _i32, _vp, _i64, _i32, _i32, _vp, _i64, _vp, _vp, _vp, _sz, _vp]),
     "aes_plan_fold_row_constants": (ctypes.c_int, [_i64, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp]),
     "aes_gcn_layer_f32": (ctypes.c_int, [_i64, _i64, _i32, _vp, _vp, _vp, _vp, _i64, _i32, _vp, _i64, _i32, _vp, _i64,
@@ -152,6 +153,21 @@ def aes_quantize_workspace_bytes(n: int, F: int, granularity: int) -> int:
     return int(library().aes_quantize_workspace_bytes(n, F, granularity))
 
 
+def aes_quantize_inline_ld(F: int, scheme: int) -> int:
+    """Smallest multiple of 128 bytes that holds a row of F codes and its constants (AES_Q_PER_ROW_INLINE)."""
+    ld = int(library().aes_quantize_inline_ld(int(F), int(scheme)))
+    if ld < 0:
+        raise AesError(ld, aes_last_error())
+    return ld
+
+
+def _inline_views(buf: torch.Tensor, F: int, scheme: int):
+    """(Xq, scale, zero) as views of an n x ld byte buffer laid out for AES_Q_PER_ROW_INLINE."""
+    off = (F + 3) // 4
+    words = buf.view(torch.float32)
+    return buf[:, :F], words[:, off], (words[:, off + 1] if scheme == AES_Q_AFFINE_FLOOR_U8 else None)
+
+
 @_on_stream
 def aes_sample_build(rowptr, colidx, val, n_cols: int, W: int, seed: int = 0, *,
                      strategy: int = AES_STRATEGY_ADAPTIVE, want_eid: bool = False,
@@ -234,6 +250,15 @@ def aes_quantize_features(X, scheme: int, granularity: int, *, out=None, workspa
     dev = X.device
     groups = {AES_Q_PER_TENSOR: 1, AES_Q_PER_COLUMN: F, AES_Q_PER_ROW: n}.get(granularity, 1)
     qdtype = torch.uint8 if scheme == AES_Q_AFFINE_FLOOR_U8 else torch.int8
+    if granularity == AES_Q_PER_ROW_INLINE:
+        # out: an n x ld byte buffer (ld from aes_quantize_inline_ld or larger); the results are views of it
+        buf = out if out is not None else torch.empty((n, aes_quantize_inline_ld(F, scheme)), dtype=qdtype, device=dev)
+        buf = _dev(buf, qdtype, "out", 2)
+        if buf.shape[0] != n or not buf.is_contiguous() or buf.shape[1] % 4:
+            raise ValueError("out: a contiguous n x ld buffer (ld a multiple of 4) is required for constants inside the rows")
+        _check(library().aes_quantize_features(n, F, _ptr(X), _ld(X), int(scheme), int(granularity), _ptr(buf),
+                                               buf.shape[1], None, None, None, 0, _stream(stream)))
+        return _inline_views(buf, F, scheme)
     if out is None:
         out = (torch.empty((n, F), dtype=qdtype, device=dev),
                torch.empty(groups, dtype=torch.float32, device=dev),
@@ -255,6 +280,8 @@ def aes_spmm_q8(plan: Plan, Xq, scheme: int, granularity: int, scale, zero=None,
     if not isinstance(Xq, torch.Tensor) or Xq.dtype not in (torch.int8, torch.uint8):
         raise TypeError("Xq: int8 / uint8 tensor required")
     Xq = _dev(Xq, Xq.dtype, "Xq", 2)
+    if granularity == AES_Q_PER_ROW_INLINE:
+        scale = zero = None                      # read from the rows of Xq
     if scale is not None:
         scale = _dev(scale, torch.float32, "scale")
     if zero is not None:
@@ -318,7 +345,10 @@ def aes_spmm_fused_q8(rowptr, colidx, val, n_cols: int, W: int, Xq, scheme: int,
     if not isinstance(Xq, torch.Tensor) or Xq.dtype not in (torch.int8, torch.uint8):
         raise TypeError("Xq: int8 / uint8 tensor required")
     Xq = _dev(Xq, Xq.dtype, "Xq", 2)
-    scale = _dev(scale, torch.float32, "scale")
+    if granularity == AES_Q_PER_ROW_INLINE:
+        scale = zero = None
+    if scale is not None or granularity != AES_Q_PER_ROW_INLINE:
+        scale = _dev(scale, torch.float32, "scale")
     if zero is not None:
         zero = _dev(zero, torch.float32, "zero")
     n_rows, F = rowptr.numel() - 1, Xq.shape[1]
@@ -345,7 +375,10 @@ def aes_dequantize_features(Xq, scheme: int, granularity: int, scale, zero=None,
     if not isinstance(Xq, torch.Tensor) or Xq.dtype not in (torch.int8, torch.uint8):
         raise TypeError("Xq: int8 / uint8 tensor required")
     Xq = _dev(Xq, Xq.dtype, "Xq", 2)
-    scale = _dev(scale, torch.float32, "scale")
+    if granularity == AES_Q_PER_ROW_INLINE:
+        scale = zero = None
+    if scale is not None or granularity != AES_Q_PER_ROW_INLINE:
+        scale = _dev(scale, torch.float32, "scale")
     if zero is not None:
         zero = _dev(zero, torch.float32, "zero")
     n, F = Xq.shape
@@ -409,6 +442,8 @@ def aes_gcn_layer_q8(plan: Plan, Xq, scheme: int, granularity: int, scale, zero,
         raise TypeError("Xq: int8 / uint8 tensor required")
     Xq = _dev(Xq, Xq.dtype, "Xq", 2)
     Theta = _dev(Theta, torch.float32, "Theta", 2)
+    if granularity == AES_Q_PER_ROW_INLINE:
+        scale = zero = None
     if scale is not None:
         scale = _dev(scale, torch.float32, "scale")
     if zero is not None:

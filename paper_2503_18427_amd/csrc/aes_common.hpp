@@ -38,6 +38,26 @@ inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
+// AES_Q_PER_ROW_INLINE: a node's constants live in its own row of codes, the float32 scale at byte
+// q_inline_offset(F) (the codes rounded up to a multiple of four), the affine scheme's zero point in
+// the four bytes after it.  Checks the layout and returns where node 0's constants are and how many
+// floats lie between two nodes' constants.
+inline int64_t q_inline_offset(int32_t F) { return (static_cast<int64_t>(F) + 3) & ~static_cast<int64_t>(3); }
+
+inline int q_inline_constants(const char *what, const int8_t *Xq, int64_t ldq, int32_t F, bool affine,
+                              const float *&scale, const float *&zero, int64_t &stride)
+{
+    const int64_t off = q_inline_offset(F), need = off + (affine ? 8 : 4);
+    if (ldq < need || ldq % 4 != 0)
+        return fail(AES_ERR_INVALID_ARG, "%s: constants inside the rows need ldq >= %lld and a multiple of 4 (ldq=%lld, F=%d)",
+                    what, (long long)need, (long long)ldq, (int)F);
+    if (!aligned(Xq, 4)) return fail(AES_ERR_INVALID_ARG, "%s: constants inside the rows need Xq 4-byte aligned", what);
+    scale = reinterpret_cast<const float *>(Xq + off);
+    zero = affine ? scale + 1 : nullptr;
+    stride = ldq / 4;
+    return AES_OK;
+}
+
 // Smallest power of two >= v (v >= 1).
 inline int pow2_ceil(int64_t v)
 {

@@ -409,7 +409,7 @@ extern "C" int aes_gcn_layer_f32(int64_t n_rows, int64_t n_cols, int32_t W,
     if (int rc = check_layer(what, n_rows, n_cols, W, s_rowptr, X, ldx, F, Theta, ldt, Fo, H, ldh)) return rc;
     if (n_rows == 0) return AES_OK;
     const SlotSource src = {s_rowptr, s_col, s_val, W, 0, 0};
-    const QParams qp = {nullptr, nullptr};
+    const QParams qp = {nullptr, nullptr, 1, -1};
     return run_gcn<FeatF32<4>, kQNone>(what, W, n_rows, src, X, ldx, F, qp, Theta, ldt, Fo, H, ldh,
                                        static_cast<hipStream_t>(stream));
 }
@@ -423,18 +423,12 @@ extern "C" int aes_gcn_layer_q8(int64_t n_rows, int64_t n_cols, int32_t W,
 {
     const char *what = "aes_gcn_layer_q8";
     if (int rc = check_layer(what, n_rows, n_cols, W, s_rowptr, Xq, ldq, F, Theta, ldt, Fo, H, ldh)) return rc;
-    if (scheme != AES_Q_AFFINE_FLOOR_U8 && scheme != AES_Q_SYMMETRIC_RNE_I8)
-        return fail(AES_ERR_INVALID_ARG, "%s: unknown scheme %d", what, (int)scheme);
-    if (granularity < AES_Q_PER_TENSOR || granularity > AES_Q_PER_ROW_FOLDED)
-        return fail(AES_ERR_INVALID_ARG, "%s: unknown granularity %d", what, (int)granularity);
-    const bool folded = granularity == AES_Q_PER_ROW_FOLDED;
-    const bool affine = scheme == AES_Q_AFFINE_FLOOR_U8;
-    if (!folded && scale == nullptr) return fail(AES_ERR_INVALID_ARG, "%s: scale is NULL", what);
-    if (affine && zero == nullptr) return fail(AES_ERR_INVALID_ARG, "%s: zero is NULL for the affine scheme", what);
+    QParams qp;
+    if (int rc = resolve_q8(what, false, Xq, ldq, F, scheme, granularity, scale, zero, qp)) return rc;
     if (n_rows == 0) return AES_OK;
+    const bool affine = scheme == AES_Q_AFFINE_FLOOR_U8;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     const SlotSource src = {s_rowptr, s_col, s_val, W, 0, 0};
-    const QParams qp = {scale, affine ? zero : nullptr};
 #define AES_GCN_Q8(SIGNED, MODE) \
     run_gcn<FeatQ8<4, SIGNED>, MODE>(what, W, n_rows, src, Xq, ldq, F, qp, Theta, ldt, Fo, H, ldh, stream)
     switch (granularity) {

@@ -62,8 +62,7 @@ __device__ inline void group_constants(float lo, float hi, bool affine, float &d
 template <int LPR, int VEC, bool SINGLE>
 __global__ void __launch_bounds__(kBlock)
 quantize_rows_kernel(int64_t n, int32_t F, const float *__restrict__ X, int64_t ldx, int affine_,
-                     int8_t *__restrict__ Xq, int64_t ldq, float *__restrict__ scale_out,
-                     float *__restrict__ zero_out)
+                     int8_t *__restrict__ Xq, int64_t ldq, float *scale_out, float *zero_out, int64_t cstride)
 {
     constexpr int kGroups = kBlock / LPR;
     const bool affine = affine_ != 0;
@@ -100,8 +99,8 @@ quantize_rows_kernel(int64_t n, int32_t F, const float *__restrict__ X, int64_t 
     float d, scale, zero;
     group_constants(lo, hi, affine, d, scale, zero);
     if (lane == 0) {
-        scale_out[r] = scale;
-        if (zero_out) zero_out[r] = zero;
+        scale_out[r * cstride] = scale;
+        if (zero_out) zero_out[r * cstride] = zero;
     }
     int8_t *q_row = Xq + r * ldq;
     for (int32_t f0 = 0; f0 < F; f0 += LPR * VEC) {
@@ -134,8 +133,8 @@ quantize_rows_kernel(int64_t n, int32_t F, const float *__restrict__ X, int64_t 
 template <int LPR, int RPG>
 __global__ void __launch_bounds__(kBlock)
 quantize_rows_batched_kernel(int64_t n, int32_t F, const float *__restrict__ X, int64_t ldx, int affine_,
-                             int8_t *__restrict__ Xq, int64_t ldq, float *__restrict__ scale_out,
-                             float *__restrict__ zero_out)
+                             int8_t *__restrict__ Xq, int64_t ldq, float *scale_out, float *zero_out,
+                             int64_t cstride)
 {
     constexpr int kGroups = kBlock / LPR;
     const bool affine = affine_ != 0;
@@ -171,8 +170,8 @@ quantize_rows_batched_kernel(int64_t n, int32_t F, const float *__restrict__ X, 
         float d, scale, zero;
         group_constants(lo, hi, affine, d, scale, zero);
         if (lane == 0) {
-            scale_out[r] = scale;
-            if (zero_out) zero_out[r] = zero;
+            scale_out[r * cstride] = scale;
+            if (zero_out) zero_out[r * cstride] = zero;
         }
         if (lane_on) {
             const uint32_t w = encode(x[0], lo, d, scale, affine) | (encode(x[1], lo, d, scale, affine) << 8) |
@@ -406,8 +405,8 @@ __device__ inline float dequantize_one(uint32_t byte, bool affine, float scale, 
 // Vector form: groups of kEncodeRows consecutive rows per thread, as in encode_vec_kernel.
 __global__ void __launch_bounds__(kBlock)
 dequantize_vec_kernel(int64_t n, int32_t F, const int8_t *__restrict__ Xq, int64_t ldq, int affine_, int granularity,
-                      const float *__restrict__ scale, const float *__restrict__ zero, float *__restrict__ X,
-                      int64_t ldx)
+                      const float *__restrict__ scale, const float *__restrict__ zero, int64_t cstride,
+                      float *__restrict__ X, int64_t ldx)
 {
     const bool affine = affine_ != 0;
     const int64_t n_groups = (n + kEncodeRows - 1) / kEncodeRows;
@@ -425,7 +424,7 @@ dequantize_vec_kernel(int64_t n, int32_t F, const int8_t *__restrict__ Xq, int64
             float out[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const int64_t g = granularity == AES_Q_PER_TENSOR ? 0 : granularity == AES_Q_PER_COLUMN ? f + i : r;
+                const int64_t g = granularity == AES_Q_PER_TENSOR ? 0 : granularity == AES_Q_PER_COLUMN ? f + i : r * cstride;
                 out[i] = dequantize_one((word[b] >> (8 * i)) & 0xffu, affine, scale[g], affine ? zero[g] : 0.0f);
             }
             *reinterpret_cast<aes::Float4U *>(X + r * ldx + f) = aes::Float4U{out[0], out[1], out[2], out[3]};
@@ -436,11 +435,11 @@ dequantize_vec_kernel(int64_t n, int32_t F, const int8_t *__restrict__ Xq, int64
 __global__ void __launch_bounds__(kBlock)
 dequantize_scalar_kernel(int64_t n, int32_t F, const int8_t *__restrict__ Xq, int64_t ldq, int affine_,
                          int granularity, const float *__restrict__ scale, const float *__restrict__ zero,
-                         float *__restrict__ X, int64_t ldx)
+                         int64_t cstride, float *__restrict__ X, int64_t ldx)
 {
     const bool affine = affine_ != 0;
     for (ItemWalk w(F); w.r < n; w.next()) {
-        const int64_t g = granularity == AES_Q_PER_TENSOR ? 0 : granularity == AES_Q_PER_COLUMN ? w.i : w.r;
+        const int64_t g = granularity == AES_Q_PER_TENSOR ? 0 : granularity == AES_Q_PER_COLUMN ? w.i : w.r * cstride;
         X[w.r * ldx + w.i] = dequantize_one(static_cast<uint8_t>(Xq[w.r * ldq + w.i]), affine, scale[g],
                                             affine ? zero[g] : 0.0f);
     }
@@ -457,26 +456,34 @@ constexpr int64_t kMaxElementwiseBlocks = 256 * 64;   // grid-stride beyond: mea
 
 template <int LPR, int VEC>
 void launch_rows(int64_t n, int32_t F, const float *X, int64_t ldx, int affine, int8_t *Xq, int64_t ldq,
-                 float *scale, float *zero, hipStream_t stream)
+                 float *scale, float *zero, int64_t cstride, hipStream_t stream)
 {
     const unsigned grid = static_cast<unsigned>(aes::ceil_div(n, kBlock / LPR));
     if (VEC == 4 && F <= LPR * VEC) {
         const unsigned bgrid = static_cast<unsigned>(aes::ceil_div(n, static_cast<int64_t>(kBlock / LPR) * kRowsPerGroup));
         quantize_rows_batched_kernel<LPR, kRowsPerGroup><<<dim3(bgrid), dim3(kBlock), 0, stream>>>(n, F, X, ldx, affine, Xq,
-                                                                                                   ldq, scale, zero);
+                                                                                                   ldq, scale, zero, cstride);
     } else if (F <= LPR * VEC)
-        quantize_rows_kernel<LPR, VEC, true><<<dim3(grid), dim3(kBlock), 0, stream>>>(n, F, X, ldx, affine, Xq, ldq, scale, zero);
+        quantize_rows_kernel<LPR, VEC, true><<<dim3(grid), dim3(kBlock), 0, stream>>>(n, F, X, ldx, affine, Xq, ldq, scale, zero, cstride);
     else
-        quantize_rows_kernel<LPR, VEC, false><<<dim3(grid), dim3(kBlock), 0, stream>>>(n, F, X, ldx, affine, Xq, ldq, scale, zero);
+        quantize_rows_kernel<LPR, VEC, false><<<dim3(grid), dim3(kBlock), 0, stream>>>(n, F, X, ldx, affine, Xq, ldq, scale, zero, cstride);
 }
 
 }  // namespace
 
 extern "C" size_t aes_quantize_workspace_bytes(int64_t n, int32_t F, int32_t granularity)
 {
-    if (n < 0 || F < 1 || granularity == AES_Q_PER_ROW) return 0;
+    if (n < 0 || F < 1 || granularity == AES_Q_PER_ROW || granularity == AES_Q_PER_ROW_INLINE) return 0;
     // slab partials (min and max per column) + per-group x_min and range
     return (static_cast<size_t>(slabs_for(n)) * 2 + 2) * static_cast<size_t>(F) * sizeof(float);
+}
+
+extern "C" int64_t aes_quantize_inline_ld(int32_t F, int32_t scheme)
+{
+    if (F < 1 || F >= (1 << 24) || (scheme != AES_Q_AFFINE_FLOOR_U8 && scheme != AES_Q_SYMMETRIC_RNE_I8))
+        return aes::fail(AES_ERR_INVALID_ARG, "aes_quantize_inline_ld: F=%d / scheme=%d out of range", (int)F, (int)scheme);
+    const int64_t need = aes::q_inline_offset(F) + (scheme == AES_Q_AFFINE_FLOOR_U8 ? 8 : 4);
+    return (need + 127) / 128 * 128;
 }
 
 extern "C" int aes_quantize_features(int64_t n, int32_t F, const float *X, int64_t ldx,
@@ -492,10 +499,18 @@ extern "C" int aes_quantize_features(int64_t n, int32_t F, const float *X, int64
                          (long long)ldx, (long long)ldq, (int)F);
     if (scheme != AES_Q_AFFINE_FLOOR_U8 && scheme != AES_Q_SYMMETRIC_RNE_I8)
         return aes::fail(AES_ERR_INVALID_ARG, "%s: unknown scheme %d", what, (int)scheme);
-    if (granularity < AES_Q_PER_TENSOR || granularity > AES_Q_PER_ROW)
+    if (granularity == AES_Q_PER_ROW_FOLDED || granularity < AES_Q_PER_TENSOR || granularity > AES_Q_PER_ROW_INLINE)
         return aes::fail(AES_ERR_INVALID_ARG, "%s: unknown granularity %d", what, (int)granularity);
     const int affine = scheme == AES_Q_AFFINE_FLOOR_U8 ? 1 : 0;
     if (n > 0 && (X == nullptr || Xq == nullptr)) return aes::fail(AES_ERR_INVALID_ARG, "%s: X / Xq is NULL", what);
+    int64_t cstride = 1;
+    if (granularity == AES_Q_PER_ROW_INLINE) {       // the constants go into the rows of codes
+        const float *s = nullptr, *z = nullptr;
+        if (int rc = aes::q_inline_constants(what, Xq, ldq, F, affine != 0, s, z, cstride)) return rc;
+        scale = const_cast<float *>(s);
+        zero = const_cast<float *>(z);
+        granularity = AES_Q_PER_ROW;
+    }
     if (scale == nullptr && (n > 0 || granularity != AES_Q_PER_ROW))
         return aes::fail(AES_ERR_INVALID_ARG, "%s: scale is NULL", what);
     if (affine && zero == nullptr && (n > 0 || granularity != AES_Q_PER_ROW))
@@ -513,15 +528,15 @@ extern "C" int aes_quantize_features(int64_t n, int32_t F, const float *X, int64
         if (n == 0) return AES_OK;
         if (aes::ceil_div(n, kBlock / 64) > INT32_MAX) return aes::fail(AES_ERR_UNSUPPORTED, "%s: n=%lld too large", what, (long long)n);
         if (!vec) {
-            launch_rows<64, 1>(n, F, X, ldx, affine, Xq, ldq, scale, zero, stream);
+            launch_rows<64, 1>(n, F, X, ldx, affine, Xq, ldq, scale, zero, cstride, stream);
         } else {
             int l = aes::pow2_ceil(aes::ceil_div(F, 4));
             l = l < 8 ? 8 : l > 64 ? 64 : l;
             switch (l) {
-                case 8: launch_rows<8, 4>(n, F, X, ldx, affine, Xq, ldq, scale, zero, stream); break;
-                case 16: launch_rows<16, 4>(n, F, X, ldx, affine, Xq, ldq, scale, zero, stream); break;
-                case 32: launch_rows<32, 4>(n, F, X, ldx, affine, Xq, ldq, scale, zero, stream); break;
-                default: launch_rows<64, 4>(n, F, X, ldx, affine, Xq, ldq, scale, zero, stream); break;
+                case 8: launch_rows<8, 4>(n, F, X, ldx, affine, Xq, ldq, scale, zero, cstride, stream); break;
+                case 16: launch_rows<16, 4>(n, F, X, ldx, affine, Xq, ldq, scale, zero, cstride, stream); break;
+                case 32: launch_rows<32, 4>(n, F, X, ldx, affine, Xq, ldq, scale, zero, cstride, stream); break;
+                default: launch_rows<64, 4>(n, F, X, ldx, affine, Xq, ldq, scale, zero, cstride, stream); break;
             }
         }
         return aes::check_launch("aes_quantize_features/rows");
@@ -573,9 +588,14 @@ extern "C" int aes_dequantize_features(int64_t n, int32_t F, const int8_t *Xq, i
                          (long long)ldx, (long long)ldq, (int)F);
     if (scheme != AES_Q_AFFINE_FLOOR_U8 && scheme != AES_Q_SYMMETRIC_RNE_I8)
         return aes::fail(AES_ERR_INVALID_ARG, "%s: unknown scheme %d", what, (int)scheme);
-    if (granularity < AES_Q_PER_TENSOR || granularity > AES_Q_PER_ROW)
+    if (granularity == AES_Q_PER_ROW_FOLDED || granularity < AES_Q_PER_TENSOR || granularity > AES_Q_PER_ROW_INLINE)
         return aes::fail(AES_ERR_INVALID_ARG, "%s: unknown granularity %d", what, (int)granularity);
     const int affine = scheme == AES_Q_AFFINE_FLOOR_U8 ? 1 : 0;
+    int64_t cstride = 1;
+    if (granularity == AES_Q_PER_ROW_INLINE) {
+        if (int rc = aes::q_inline_constants(what, Xq, ldq, F, affine != 0, scale, zero, cstride)) return rc;
+        granularity = AES_Q_PER_ROW;
+    }
     if (scale == nullptr || (affine && zero == nullptr))
         return aes::fail(AES_ERR_INVALID_ARG, "%s: scale (or zero, affine scheme) is NULL", what);
     if (n == 0) return AES_OK;
@@ -587,9 +607,9 @@ extern "C" int aes_dequantize_features(int64_t n, int32_t F, const int8_t *Xq, i
     if (blocks > kMaxElementwiseBlocks) blocks = kMaxElementwiseBlocks;
     if (vec)
         dequantize_vec_kernel<<<dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, stream>>>(
-            n, F, Xq, ldq, affine, granularity, scale, zero, X, ldx);
+            n, F, Xq, ldq, affine, granularity, scale, zero, cstride, X, ldx);
     else
         dequantize_scalar_kernel<<<dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, stream>>>(
-            n, F, Xq, ldq, affine, granularity, scale, zero, X, ldx);
+            n, F, Xq, ldq, affine, granularity, scale, zero, cstride, X, ldx);
     return aes::check_launch(what);
 }

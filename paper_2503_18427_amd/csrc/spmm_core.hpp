@@ -19,7 +19,10 @@ enum QMode {
     kQRowScale = 1,  // one pair per node (= per gathered row): folded into the staged edge value
     kQTensor = 2,    // one pair for the whole matrix: applied once per output
     kQColumn = 3,    // one pair per feature column: applied once per output
-    kQFolded = 4     // per-node pairs already multiplied into the plan's values; zero = row bias or NULL
+    kQFolded = 4,    // per-node pairs already multiplied into the plan's values; zero = row bias or NULL
+    kQRowInGather = 5  // one pair per node, stored behind the node's codes inside the row the lane group gathers
+                       // anyway: the lane that holds those words hands them to the group by a cross-lane read,
+                       // so the constants cost neither a memory request nor a step in the chain of dependent loads
 };
 
 // Where a row's (col, val) slots come from: a materialised plan (FUSED = false: the
@@ -37,6 +40,9 @@ struct SlotSource {
 struct QParams {
     const float *scale;   // kQRowScale: indexed by column of A (= row of X); kQFolded: unused
     const float *zero;    // NULL for signed codes; kQFolded: the row bias, or NULL
+    int64_t node_stride;  // kQRowScale: floats between two nodes' constants (1: plain arrays; ldq / 4: constants
+                          // kept inside the rows of codes)
+    int32_t inline_off;   // constants inside the rows: byte offset of the scale in a row (the zero point follows); else -1
 };
 
 // Unsigned codes carry a zero point (x_hat = q*scale + zero), signed codes do not (x_hat = q*scale).
@@ -45,7 +51,38 @@ template <typename Feat, int QMODE>
 struct QTraits {
     static constexpr bool kQuant = QMODE != kQNone;
     static constexpr bool kAffine = kQuant && QMODE != kQFolded && !Feat::kSigned;
+    // The zero-point sum is collected by the lanes that stage the slots (one share each, added over the group
+    // before the epilogue), except where every lane sees every slot's constants itself.
+    static constexpr bool kSideOverLanes = kAffine && QMODE != kQRowInGather;
 };
+
+// The scheme / granularity / scale / zero arguments of an 8-bit entry point, checked and turned into
+// the kernels' QParams; `granularity` comes back as the one that selects the kernel (constants inside
+// the rows are per-node constants read with a stride).
+inline int resolve_q8(const char *what, bool fused, const int8_t *Xq, int64_t ldq, int32_t F, int32_t scheme,
+                      int32_t &granularity, const float *scale, const float *zero, QParams &qp)
+{
+    if (scheme != AES_Q_AFFINE_FLOOR_U8 && scheme != AES_Q_SYMMETRIC_RNE_I8)
+        return fail(AES_ERR_INVALID_ARG, "%s: unknown scheme %d", what, (int)scheme);
+    if (granularity < AES_Q_PER_TENSOR || granularity > AES_Q_PER_ROW_INLINE)
+        return fail(AES_ERR_INVALID_ARG, "%s: unknown granularity %d", what, (int)granularity);
+    const bool affine = scheme == AES_Q_AFFINE_FLOOR_U8;
+    const bool folded = granularity == AES_Q_PER_ROW_FOLDED;
+    if (fused && folded) return fail(AES_ERR_INVALID_ARG, "%s: folded constants need a materialised plan", what);
+    int64_t stride = 1;
+    if (granularity == AES_Q_PER_ROW_INLINE) {
+        if (int rc = q_inline_constants(what, Xq, ldq, F, affine, scale, zero, stride)) return rc;
+        granularity = AES_Q_PER_ROW;
+    }
+    if (!folded && scale == nullptr) return fail(AES_ERR_INVALID_ARG, "%s: scale is NULL", what);
+    if (affine && zero == nullptr)
+        return fail(AES_ERR_INVALID_ARG, "%s: zero (the row bias, for folded constants) is NULL for the affine scheme", what);
+    // Unsigned codes (the affine scheme) use zero; signed codes ignore it.  Folded: zero is the row
+    // bias the fold pass wrote for the affine scheme, and nothing otherwise.
+    qp = QParams{scale, affine ? zero : nullptr, stride,
+                 stride == 1 ? -1 : static_cast<int32_t>(q_inline_offset(F))};
+    return AES_OK;
+}
 
 // acc + a * b in the accumulator's precision: one fused multiply-add in float32 for
 // ordinary rows, in float64 for the long-row variant (whose sums run over up to
@@ -206,9 +243,10 @@ __device__ __forceinline__ void stage_tile(const SlotSource &src, const RowInfo 
             const int32_t c = src.col[e];
             float v = src.val[e];
             if constexpr (QMODE == kQRowScale) {
-                if constexpr (QTraits<Feat, QMODE>::kAffine) side = fma_acc(v, qp.zero[c], side);
-                v *= qp.scale[c];
-            } else if constexpr (QTraits<Feat, QMODE>::kAffine) {
+                const uint64_t g = static_cast<uint64_t>(static_cast<uint32_t>(c)) * static_cast<uint64_t>(qp.node_stride);
+                if constexpr (QTraits<Feat, QMODE>::kAffine) side = fma_acc(v, qp.zero[g], side);
+                v *= qp.scale[g];
+            } else if constexpr (QTraits<Feat, QMODE>::kSideOverLanes) {
                 side += v;
             }
             my_stage[s] = make_int2(c, __float_as_int(v));
@@ -239,6 +277,19 @@ __device__ __forceinline__ void accumulate_tiles(const SlotSource &src, const Ro
     const uint32_t ld = static_cast<uint32_t>(ldx);
     const typename Feat::elem_t *const x_lane = X + f;
     auto row_of = [&](int32_t c) { return x_lane + static_cast<uint64_t>(static_cast<uint32_t>(c)) * ld; };
+    // kQRowInGather: lane_on covers the lanes up to the constants, which the lanes k_lane (scale) and
+    // k_lane + 1 (zero point) of the group hold as their gathered word.
+    const int k_lane = QMODE == kQRowInGather ? qp.inline_off / Feat::VEC : 0;
+    auto consume = [&](const int2 &slot, const typename Feat::raw_t &x) {
+        float v = __int_as_float(slot.y);
+        if constexpr (QMODE == kQRowInGather) {
+            static_assert(QMODE != kQRowInGather || (sizeof(typename Feat::raw_t) == 4 && !PARTIAL), "four codes per lane");
+            const float word = __uint_as_float(static_cast<uint32_t>(x));
+            if constexpr (QTraits<Feat, QMODE>::kAffine) side = fma_acc(v, __shfl(word, k_lane + 1, LPR), side);
+            v *= __shfl(word, k_lane, LPR);
+        }
+        Feat::fma(acc, v, x);
+    };
     for (int64_t t0 = first_tile * kTile; t0 < ri.n_slots; t0 += tile_step * kTile) {
         const int m = static_cast<int>(ri.n_slots - t0 < kTile ? ri.n_slots - t0 : kTile);
         stage_tile<LPR, Feat, QMODE, FUSED, AccT>(src, ri, my_stage, lane, qp, t0, m, side);
@@ -253,7 +304,7 @@ __device__ __forceinline__ void accumulate_tiles(const SlotSource &src, const Ro
 #pragma unroll
                 for (int u = 0; u < UNROLL; ++u) x[u] = load_feat(row_of(cv[u].x));
 #pragma unroll
-                for (int u = 0; u < UNROLL; ++u) Feat::fma(acc, __int_as_float(cv[u].y), x[u]);
+                for (int u = 0; u < UNROLL; ++u) consume(cv[u], x[u]);
             }
             // Ragged last round: the missing slots are predicated off (value 0, no load), so
             // short rows and row tails keep their gathers in flight together as well.
@@ -268,7 +319,7 @@ __device__ __forceinline__ void accumulate_tiles(const SlotSource &src, const Ro
                     if (cv[u].x >= 0) x[u] = load_feat(row_of(cv[u].x));
                 }
 #pragma unroll
-                for (int u = 0; u < UNROLL; ++u) Feat::fma(acc, __int_as_float(cv[u].y), x[u]);
+                for (int u = 0; u < UNROLL; ++u) consume(cv[u], x[u]);
             }
         }
     }
@@ -288,6 +339,10 @@ __device__ __forceinline__ void accumulate_tiles_wide(const SlotSource &src, con
     const uint32_t ld = static_cast<uint32_t>(ldx);
     const typename Feat::elem_t *const x_lane = X + f;
     auto row_of = [&](int32_t c) { return x_lane + static_cast<uint64_t>(static_cast<uint32_t>(c)) * ld; };
+    // kQRowInGather: which of a lane's NV words, in which lane, is the node's scale / zero point
+    const int k_off = QMODE == kQRowInGather ? qp.inline_off : 0;
+    const int ks_vec = k_off / kApart, ks_lane = (k_off % kApart) / Feat::VEC;
+    const int kz_vec = (k_off + 4) / kApart, kz_lane = ((k_off + 4) % kApart) / Feat::VEC;
     for (int64_t t0 = first_tile * kTile; t0 < ri.n_slots; t0 += tile_step * kTile) {
         const int m = static_cast<int>(ri.n_slots - t0 < kTile ? ri.n_slots - t0 : kTile);
         stage_tile<LPR, Feat, QMODE, FUSED, AccT>(src, ri, my_stage, lane, qp, t0, m, side);
@@ -305,9 +360,23 @@ __device__ __forceinline__ void accumulate_tiles_wide(const SlotSource &src, con
                         if (cv[u].x >= 0 && on[j]) x[u][j] = Feat::load(row_of(cv[u].x) + j * kApart);
                     }
 #pragma unroll
-                for (int u = 0; u < UNROLL; ++u)
+                for (int u = 0; u < UNROLL; ++u) {
+                    float v = __int_as_float(cv[u].y);
+                    if constexpr (QMODE == kQRowInGather) {
+                        static_assert(QMODE != kQRowInGather || sizeof(typename Feat::raw_t) == 4, "four codes per lane");
+                        uint32_t ws = static_cast<uint32_t>(x[u][0]), wz = ws;
 #pragma unroll
-                    for (int j = 0; j < NV; ++j) Feat::fma(acc[j], __int_as_float(cv[u].y), x[u][j]);
+                        for (int j = 1; j < NV; ++j) {
+                            ws = j == ks_vec ? static_cast<uint32_t>(x[u][j]) : ws;
+                            wz = j == kz_vec ? static_cast<uint32_t>(x[u][j]) : wz;
+                        }
+                        if constexpr (QTraits<Feat, QMODE>::kAffine)
+                            side = fma_acc(v, __shfl(__uint_as_float(wz), kz_lane, LPR), side);
+                        v *= __shfl(__uint_as_float(ws), ks_lane, LPR);
+                    }
+#pragma unroll
+                    for (int j = 0; j < NV; ++j) Feat::fma(acc[j], v, x[u][j]);
+                }
             }
         }
     }
@@ -394,7 +463,7 @@ __device__ __forceinline__ void finish_values(const AccT (&acc_in)[Feat::VEC], A
 #pragma unroll
     for (int i = 0; i < VEC; ++i) {
         out[i] = static_cast<float>(acc_in[i]);
-        if constexpr (QMODE == kQRowScale) {
+        if constexpr (QMODE == kQRowScale || QMODE == kQRowInGather) {
             if constexpr (AFFINE) out[i] += side;
         } else if constexpr (QMODE == kQFolded) {
             if (k.bias) out[i] += k.zero[i];

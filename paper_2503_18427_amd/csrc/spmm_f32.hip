@@ -14,7 +14,7 @@ int run_f32(const char *what, int64_t n_rows, const SlotSource &src, const int32
             int64_t ldx, int32_t F, float *Y, int64_t ldy, hipStream_t stream)
 {
     const bool lr = long_rows_possible(src.W);
-    const QParams qp = {nullptr, nullptr};
+    const QParams qp = {nullptr, nullptr, 1, -1};
     const int32_t F4 = F & ~3;
     if (F4 > 0)
         if (int rc = dispatch_lanes<FeatF32<4>, kQNone, FUSED>(lr, n_rows, src, row_perm, X, ldx, F4, qp, Y, ldy, stream, what))

@@ -46,7 +46,11 @@ constexpr int kLongRow = 2048;
 //       through LDS, so the result stays bit-reproducible.  Without LONG the kernel
 //       has no workgroup barrier at all.
 template <int LPR, int UNROLL, typename Feat, int QMODE, bool FUSED, bool LONG, int NV = 1>
-__global__ void __launch_bounds__(kBlock)
+// (Second launch bound: the narrow-group variants that take a node's constants from the gather would otherwise
+// be compiled to 73-88 vector registers, 6 wavefronts per SIMD; held to 8 wavefronts they need 50-62 and spill
+// nothing, which is worth 13 % on the short rows of the products-shaped graph; the sample-on-the-fly variants
+// with 8 or 16 lanes per row would spill and are left alone.)
+__global__ void __launch_bounds__(kBlock, (QMODE == kQRowInGather && LPR < kWave && !LONG && (!FUSED || LPR == 32)) ? 8 : 1)
 spmm_rows_kernel(int64_t n_rows, SlotSource src, const int32_t *__restrict__ row_perm,
                  const typename Feat::elem_t *__restrict__ X, int64_t ldx, int32_t F, QParams qp,
                  float *__restrict__ Y, int64_t ldy)
@@ -65,6 +69,9 @@ spmm_rows_kernel(int64_t n_rows, SlotSource src, const int32_t *__restrict__ row
     const int wave = threadIdx.x / kWave;
     const int group = (threadIdx.x % kWave) / LPR;
     const int lane = threadIdx.x % LPR;
+    // Lanes whose features lie below this gather: the F features, and with kQRowInGather also the words
+    // behind them that hold the node's constants (the host has checked that one pass of the group reaches them).
+    const int32_t f_gather = QMODE == kQRowInGather ? qp.inline_off + (QTraits<Feat, QMODE>::kAffine ? 8 : 4) : F;
     const int64_t slot_in_order = static_cast<int64_t>(blockIdx.x) * kRowsPerBlock + wave * kGroups + group;
     const bool valid = slot_in_order < n_rows;
     if (!LONG && !valid) return;                         // whole group leaves together
@@ -88,27 +95,28 @@ spmm_rows_kernel(int64_t n_rows, SlotSource src, const int32_t *__restrict__ row
                 float side = 0.0f;      // this lane's share of sum(val * zero-point weight)
                 LaneConstants<Feat, QMODE> k;
                 if constexpr (kEarlyConstants) load_lane_constants<Feat, QMODE>(qp, f, lane_on, r, k);
-                accumulate_tiles<LPR, UNROLL, Feat, QMODE, FUSED, float>(src, ri, my_stage, lane, lane_on, X, ldx, f, qp, 0,
-                                                                         1, acc, side);
+                accumulate_tiles<LPR, UNROLL, Feat, QMODE, FUSED, float>(src, ri, my_stage, lane, f < f_gather, X, ldx, f, qp,
+                                                                         0, 1, acc, side);
                 if constexpr (!kEarlyConstants) load_lane_constants<Feat, QMODE>(qp, f, lane_on, r, k);
-                if constexpr (QTraits<Feat, QMODE>::kAffine) side = group_sum<LPR, float>(side);
+                if constexpr (QTraits<Feat, QMODE>::kSideOverLanes) side = group_sum<LPR, float>(side);
                 finish_chunk<Feat, QMODE, float>(acc, side, lane_on, k, Y + r * ldy + f);
             }
         } else {
             for (int32_t f0 = 0; f0 < F; f0 += NV * LPR * VEC) {
                 const int32_t f = f0 + lane * VEC;
-                bool on[NV];
+                bool on[NV], gather[NV];
                 float acc[NV][VEC];
 #pragma unroll
                 for (int j = 0; j < NV; ++j) {
                     on[j] = f + j * LPR * VEC < F;
+                    gather[j] = f + j * LPR * VEC < f_gather;
 #pragma unroll
                     for (int i = 0; i < VEC; ++i) acc[j][i] = 0.0f;
                 }
                 float side = 0.0f;
-                accumulate_tiles_wide<LPR, UNROLL, Feat, QMODE, FUSED, float, NV>(src, ri, my_stage, lane, on, X, ldx, f, qp,
-                                                                                  0, 1, acc, side);
-                if constexpr (QTraits<Feat, QMODE>::kAffine) side = group_sum<LPR, float>(side);
+                accumulate_tiles_wide<LPR, UNROLL, Feat, QMODE, FUSED, float, NV>(src, ri, my_stage, lane, gather, X, ldx, f,
+                                                                                  qp, 0, 1, acc, side);
+                if constexpr (QTraits<Feat, QMODE>::kSideOverLanes) side = group_sum<LPR, float>(side);
 #pragma unroll
                 for (int j = 0; j < NV; ++j) {
                     const int32_t fj = f + j * LPR * VEC;
@@ -135,22 +143,24 @@ spmm_rows_kernel(int64_t n_rows, SlotSource src, const int32_t *__restrict__ row
             const RowInfo lri = row_info<FUSED>(src, lr);
             for (int32_t f0 = 0; f0 < F; f0 += NV * LPR * VEC) {
                 const int32_t f = f0 + lane * VEC;
-                bool on[NV];
+                bool on[NV], gather[NV];
                 double acc[NV][VEC];                     // long sums are carried in float64
 #pragma unroll
                 for (int j = 0; j < NV; ++j) {
                     on[j] = f + j * LPR * VEC < F;
+                    gather[j] = f + j * LPR * VEC < f_gather;
 #pragma unroll
                     for (int q = 0; q < VEC; ++q) acc[j][q] = 0.0;
                 }
                 double side = 0.0;
                 if constexpr (NV == 1)
-                    accumulate_tiles<LPR, UNROLL, Feat, QMODE, FUSED, double>(src, lri, my_stage, lane, on[0], X, ldx, f, qp,
-                                                                              gib, kRowsPerBlock, acc[0], side);
+                    accumulate_tiles<LPR, UNROLL, Feat, QMODE, FUSED, double>(src, lri, my_stage, lane, gather[0], X, ldx, f,
+                                                                              qp, gib, kRowsPerBlock, acc[0], side);
                 else
-                    accumulate_tiles_wide<LPR, UNROLL, Feat, QMODE, FUSED, double, NV>(src, lri, my_stage, lane, on, X, ldx,
-                                                                                       f, qp, gib, kRowsPerBlock, acc, side);
-                if constexpr (QTraits<Feat, QMODE>::kAffine) side = group_sum<LPR, double>(side);
+                    accumulate_tiles_wide<LPR, UNROLL, Feat, QMODE, FUSED, double, NV>(src, lri, my_stage, lane, gather, X,
+                                                                                       ldx, f, qp, gib, kRowsPerBlock, acc,
+                                                                                       side);
+                if constexpr (QTraits<Feat, QMODE>::kSideOverLanes) side = group_sum<LPR, double>(side);
 #pragma unroll
                 for (int j = 0; j < NV; ++j)
 #pragma unroll
@@ -202,6 +212,15 @@ inline int lanes_per_row(int32_t F, int vec)
 {
     int l = aes::pow2_ceil(aes::ceil_div(F, vec));
     return l < 8 ? 8 : l > 64 ? 64 : l;
+}
+
+// Codes one pass of a lane group reaches on the 8-bit vector path (the shape dispatch_lanes picks for F).
+inline int32_t codes_per_pass(int32_t F)
+{
+    constexpr int kPass = kWave * 4;
+    if (F > 2 * kPass) return 4 * kPass;
+    if (F > kPass) return 2 * kPass;
+    return lanes_per_row(F, 4) * 4;
 }
 
 // Rows can exceed kLongRow slots only without sampling (W == 0) or with a very wide W.

@@ -22,8 +22,10 @@ int dispatch_q8(int64_t n_rows, const SlotSource &src, const int32_t *row_perm, 
             qp.scale += F4;
             if (qp.zero) qp.zero += F4;
         }
-        return launch_rows<8, 8, FeatQ8<1, SIGNED>, QMODE, FUSED>(lr, n_rows, src, row_perm, Xq + F4, ldq, F - F4, qp,
-                                                                 Y + F4, ldy, stream, what);
+        // (constants that the vector launch takes from its own gather are read with a load of their own here)
+        constexpr int kTailMode = QMODE == kQRowInGather ? kQRowScale : QMODE;
+        return launch_rows<8, 8, FeatQ8<1, SIGNED>, kTailMode, FUSED>(lr, n_rows, src, row_perm, Xq + F4, ldq, F - F4, qp,
+                                                                     Y + F4, ldy, stream, what);
     }
     return AES_OK;
 }
@@ -36,7 +38,16 @@ int dispatch_granularity(int32_t granularity, int64_t n_rows, const SlotSource &
     switch (granularity) {
         case AES_Q_PER_TENSOR: return dispatch_q8<SIGNED, kQTensor, FUSED>(n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
         case AES_Q_PER_COLUMN: return dispatch_q8<SIGNED, kQColumn, FUSED>(n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
-        case AES_Q_PER_ROW: return dispatch_q8<SIGNED, kQRowScale, FUSED>(n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
+        case AES_Q_PER_ROW: {
+            // Constants inside the rows: where one pass of the lane group that gathers a row's codes also reaches
+            // the words behind them, the group takes them from that gather; otherwise (and for constants in arrays
+            // of their own) each slot's constants are loaded when the slot is staged.
+            const int32_t F4 = F & ~3;
+            const int32_t end = qp.inline_off + (SIGNED ? 4 : 8);
+            if (qp.inline_off >= 0 && F4 > 0 && F4 <= codes_per_pass(F4) && end <= codes_per_pass(F4))
+                return dispatch_q8<SIGNED, kQRowInGather, FUSED>(n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
+            return dispatch_q8<SIGNED, kQRowScale, FUSED>(n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
+        }
         default:
             if constexpr (FUSED) return aes::fail(AES_ERR_INVALID_ARG, "%s: folded constants need a materialised plan", what);
             else return dispatch_q8<SIGNED, kQFolded, false>(n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
@@ -48,21 +59,10 @@ int run_q8(const char *what, int64_t n_rows, const SlotSource &src, const int32_
            int64_t ldq, int32_t F, int32_t scheme, int32_t granularity, const float *scale, const float *zero,
            float *Y, int64_t ldy, hipStream_t stream)
 {
-    if (scheme != AES_Q_AFFINE_FLOOR_U8 && scheme != AES_Q_SYMMETRIC_RNE_I8)
-        return aes::fail(AES_ERR_INVALID_ARG, "%s: unknown scheme %d", what, (int)scheme);
-    if (granularity < AES_Q_PER_TENSOR || granularity > AES_Q_PER_ROW_FOLDED)
-        return aes::fail(AES_ERR_INVALID_ARG, "%s: unknown granularity %d", what, (int)granularity);
-    const bool folded = granularity == AES_Q_PER_ROW_FOLDED;
-    if (FUSED && folded)
-        return aes::fail(AES_ERR_INVALID_ARG, "%s: folded constants need a materialised plan", what);
-    if (!folded && scale == nullptr) return aes::fail(AES_ERR_INVALID_ARG, "%s: scale is NULL", what);
-    const bool affine = scheme == AES_Q_AFFINE_FLOOR_U8;
-    if (affine && zero == nullptr)
-        return aes::fail(AES_ERR_INVALID_ARG, "%s: zero (the row bias, for folded constants) is NULL for the affine scheme", what);
+    QParams qp;
+    if (int rc = resolve_q8(what, FUSED, Xq, ldq, F, scheme, granularity, scale, zero, qp)) return rc;
     if (n_rows == 0) return AES_OK;
-    // Unsigned codes (the affine scheme) use zero; signed codes ignore it.  Folded: zero is the row
-    // bias the fold pass wrote for the affine scheme, and nothing otherwise.
-    const QParams qp = {scale, affine ? zero : nullptr};
+    const bool affine = scheme == AES_Q_AFFINE_FLOOR_U8;
     if (affine) return dispatch_granularity<false, FUSED>(granularity, n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
     return dispatch_granularity<true, FUSED>(granularity, n_rows, src, row_perm, Xq, ldq, F, qp, Y, ldy, stream, what);
 }

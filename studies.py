@@ -7,6 +7,7 @@
     python studies.py graph       [workload]
     python studies.py sampling-rate [workload]
     python studies.py folded      [workload]
+    python studies.py inline      [workload]
     python studies.py table-size
 
 They reproduce the *shape* of the paper's evaluation on the synthetic workloads
@@ -262,6 +263,49 @@ def folded(name: str) -> None:
     print()
 
 
+def inline(name: str) -> None:
+    """8-bit SpMM with per-node constants: gathered from arrays of their own, read from the node's own
+    row of codes (AES_Q_PER_ROW_INLINE), or folded into the plan, on the workload's graph at several
+    feature widths (the paper's own widths, 100 / 500 / 602, leave room in a row's last 128-byte line;
+    128 and 256 do not)."""
+    from workloads import graphs
+    w = configs.WORKLOADS[name]
+    rowptr, colidx, val = configs.make_graph(w, "cuda")
+    n, W = w.n, w.widths[0]
+    plan = aes.aes_sample_build(rowptr, colidx, val, n, W)
+    S = int(plan.s_rowptr[-1])
+    print(f"### per-node constants: own arrays vs inside the rows vs folded, `{name}` graph (n = {n}, S = {S}, W = {W}; ms)\n")
+    print("| F | scheme | bytes per row of codes (own arrays / inside) | aes_quantize_features (own / inside) | "
+          "aes_spmm_q8 own arrays | inside the rows | folded plan | inside vs own | bit-identical |")
+    print("|---|---|---|---|---|---|---|---|---|")
+    for F in (100, 128, 500, 602):
+        if n * F * 4 > 8 * 2 ** 30:
+            continue
+        X = graphs.features(n, F, w.x_dist, w.seed + 1000, torch.device("cuda"))
+        Y = torch.empty((n, F), device="cuda")
+        for scheme, label in ((aes.AES_Q_SYMMETRIC_RNE_I8, "symmetric int8"), (aes.AES_Q_AFFINE_FLOOR_U8, "affine uint8")):
+            ld_own = (F + 127) // 128 * 128                  # rows on whole 128-byte lines in both layouts
+            qdtype = torch.uint8 if scheme == aes.AES_Q_AFFINE_FLOOR_U8 else torch.int8
+            own_buf = torch.empty((n, ld_own), dtype=qdtype, device="cuda")
+            own = (own_buf[:, :F], torch.empty(n, device="cuda"), torch.empty(n, device="cuda"))
+            t_qo = _time_ms(lambda: aes.aes_quantize_features(X, scheme, aes.AES_Q_PER_ROW, out=own), iters=5)
+            ld_in = aes.aes_quantize_inline_ld(F, scheme)
+            in_buf = torch.empty((n, ld_in), dtype=qdtype, device="cuda")
+            t_qi = _time_ms(lambda: aes.aes_quantize_features(X, scheme, aes.AES_Q_PER_ROW_INLINE, out=in_buf), iters=5)
+            q_in = aes.aes_quantize_features(X, scheme, aes.AES_Q_PER_ROW_INLINE, out=in_buf)
+            t_own = _time_ms(lambda: aes.aes_spmm_q8(plan, own[0], scheme, aes.AES_Q_PER_ROW, own[1], own[2], Y), iters=5)
+            Y0 = Y.clone()
+            t_in = _time_ms(lambda: aes.aes_spmm_q8(plan, q_in[0], scheme, aes.AES_Q_PER_ROW_INLINE, None, None, Y), iters=5)
+            same = bool(torch.equal(Y, Y0))
+            fplan, bias = aes.aes_plan_fold_row_constants(plan, scheme, own[1], own[2])
+            t_f = _time_ms(lambda: aes.aes_spmm_q8(fplan, own[0], scheme, aes.AES_Q_PER_ROW_FOLDED, None, bias, Y), iters=5)
+            print(f"| {F} | {label} | {ld_own} / {ld_in} | {t_qo:.3f} / {t_qi:.3f} | {t_own:.3f} | {t_in:.3f} | {t_f:.3f} | "
+                  f"{t_own / t_in:.2f}x | {same} |")
+            del own_buf, own, in_buf, q_in, fplan, Y0
+        del X, Y
+    print()
+
+
 def sampling_rate(name: str) -> None:
     """Distribution of the per-row sampling rate slots / row_nnz (the quantity of the paper's Fig. 5)."""
     d = configs.make(name, "cuda")
@@ -348,14 +392,14 @@ def table_size(_name=None):
 
 
 def main(argv) -> int:
-    if len(argv) < 2 or argv[1] not in ("width-sweep", "strategies", "loading", "layer", "graph", "sampling-rate", "folded", "table-size"):
+    if len(argv) < 2 or argv[1] not in ("width-sweep", "strategies", "loading", "layer", "graph", "sampling-rate", "folded", "inline", "table-size"):
         print(__doc__)
         return 2
     assert torch.cuda.is_available(), "the studies need a GPU"
     name = argv[2] if len(argv) > 2 else {"width-sweep": "rmat20", "strategies": "reddit_like",
-                                          "loading": "products_like", "layer": "products_like", "graph": "arxiv_like", "sampling-rate": "reddit_like", "folded": "products_like", "table-size": None}[argv[1]]
+                                          "loading": "products_like", "layer": "products_like", "graph": "arxiv_like", "sampling-rate": "reddit_like", "folded": "products_like", "inline": "products_like", "table-size": None}[argv[1]]
     {"width-sweep": width_sweep, "strategies": strategies, "loading": loading, "layer": layer,
-     "graph": graph, "sampling-rate": sampling_rate, "folded": folded, "table-size": table_size}[argv[1]](name)
+     "graph": graph, "sampling-rate": sampling_rate, "folded": folded, "inline": inline, "table-size": table_size}[argv[1]](name)
     return 0
 
 

@@ -34,7 +34,7 @@ def test_binding_constants_equal_the_headers():
     text = open(os.path.join(ROOT, "include", "aes_spmm.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     found = dict(re.findall(r"\b(AES_[A-Z0-9_]+)\s*=\s*([-0-9 <]+?)\s*[,}\n]", text))
-    assert len(found) == 16, found
+    assert len(found) == 17, found
     for name, expr in found.items():
         assert getattr(aes.binding, name) == eval(expr, {"__builtins__": {}}), name
 
@@ -164,6 +164,21 @@ def test_argument_errors_are_host_side(lib):
     assert q8(4, 4, 0, fake, fake, fake, None, fake, 8, 8, 1, 1, None, fake, fake, 8, None) == -1
     assert q8(4, 4, 0, fake, fake, fake, None, fake, 8, 8, 0, 1, fake, None, fake, 8, None) == -1
     assert q8(0, 4, 0, fake, fake, fake, None, fake, 8, 8, 1, 1, fake, None, None, 8, None) == 0
+
+    # per-node constants inside the rows of codes (granularity 4): the layout is checked on the host
+    ild = lib.aes_quantize_inline_ld
+    assert ild(100, 1) == 128 and ild(124, 1) == 128 and ild(128, 1) == 256 and ild(602, 1) == 640
+    assert ild(121, 1) == 128 and ild(121, 0) == 256 and ild(120, 0) == 128
+    assert ild(0, 1) == -1 and ild(8, 5) == -1
+    assert q8(4, 4, 0, fake, fake, fake, None, fake, 8, 8, 1, 4, None, None, fake, 8, None) == -1       # ldq = 8 < 8 + 4
+    assert "inside the rows" in aes.aes_last_error()
+    assert q8(4, 4, 0, fake, fake, fake, None, fake, 14, 8, 1, 4, None, None, fake, 8, None) == -1      # ldq % 4
+    assert q8(4, 4, 0, fake, fake, fake, None, fake + 2, 16, 8, 1, 4, None, None, fake, 8, None) == -1  # Xq misaligned
+    assert q8(4, 4, 0, fake, fake, fake, None, fake, 12, 8, 0, 4, None, None, fake, 8, None) == -1      # affine: 8 more bytes
+    assert q(4, 8, fake, 8, 1, 4, fake, 8, None, None, None, 0, None) == -1
+    assert dq(4, 8, fake, 8, 1, 4, None, None, fake, 8, None) == -1
+    assert glq(4, 4, 0, fake, fake, fake, fake, 8, 8, 1, 4, None, None, fake, 8, 8, fake, 8, None) == -1
+    assert lib.aes_spmm_fused_q8(4, 4, fake, fake, fake, 16, 0, 0, fake, 8, 8, 1, 4, None, None, fake, 8, None) == -1
 
 
 def test_header_and_library_from_plain_c(lib, tmp_path):

@@ -253,6 +253,7 @@ def test_column_indices_up_to_2_31(G):
     import paper_2503_18427_amd as aes
     from helpers import rel_err
     n_cols, F = 2 ** 31 - 1, 2
+    torch.cuda.empty_cache()
     free, _ = torch.cuda.mem_get_info()
     if free < 30 * 2 ** 30:
         pytest.skip("needs about 22 GiB of free GPU memory")
@@ -298,6 +299,7 @@ def test_largest_leading_dimensions(G):
     import oracle as orc
     import paper_2503_18427_amd as aes
     from helpers import rel_err
+    torch.cuda.empty_cache()
     free, _ = torch.cuda.mem_get_info()
     if free < 130 * 2 ** 30:
         pytest.skip("needs about 100 GiB of free GPU memory")

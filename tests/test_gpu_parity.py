@@ -686,3 +686,70 @@ def test_random_shapes_sweep(G):
                 assert comp <= G.Q8_TOL, ("layer 8-bit", Fo, comp)
         except AssertionError as e:
             raise AssertionError(f"case (index, n, n_cols, nnz, F, W, seed, strategy, pad, pad, scheme, gran) = {what}: {e}")
+
+
+@pytest.mark.parametrize("scheme", [SYM, AFF])
+@pytest.mark.parametrize("F", [100, 128, 30, 3, 602, 121, 500, 124, 1000, 1024, 1500, 8])
+def test_constants_inside_the_rows(G, scheme, F):
+    """AES_Q_PER_ROW_INLINE: a node's scale (and zero point) stored behind its codes in its own row.
+    Codes and constants bit-exact against the oracle's per-node quantisation, the bytes of the row
+    beyond them untouched; every consumer (both multiplies, the one-kernel form, the fused layer,
+    the stand-alone Eq. 2 pass) gives bit for bit what it gives with the constants in arrays of
+    their own, and so the oracle's result."""
+    import oracle as orc
+    import paper_2503_18427_amd as aes
+    INLINE = aes.AES_Q_PER_ROW_INLINE
+    rowptr, col, val, _, n_cols = _ragged_case(F + 31 * scheme, 16, n=300)
+    rng = np.random.default_rng(F)
+    X = (rng.standard_normal((n_cols, F)) * rng.uniform(0.2, 5.0, size=(n_cols, 1))).astype(np.float32)
+    Xd = G.to_dev(X)
+    ld = aes.aes_quantize_inline_ld(F, scheme)
+    off = (F + 3) // 4 * 4
+    assert ld % 128 == 0 and ld >= off + (8 if scheme == AFF else 4) and ld - 128 < off + (8 if scheme == AFF else 4)
+    qdtype = torch.uint8 if scheme == AFF else torch.int8
+    buf = torch.full((n_cols, ld), 0x5A, dtype=qdtype, device="cuda")
+    Xq, scale, zero = aes.aes_quantize_features(Xd, scheme, INLINE, out=buf)
+    torch.cuda.synchronize()
+    rq, rs, rz = orc.quantize(X, scheme, ROW)
+    assert np.array_equal(Xq.cpu().numpy(), rq), "codes"
+    assert np.array_equal(scale.cpu().numpy().view(np.uint32), rs.view(np.uint32)), "scale inside the rows"
+    used = off + 4
+    if scheme == AFF:
+        assert np.array_equal(zero.cpu().numpy().view(np.uint32), rz.view(np.uint32)), "zero inside the rows"
+        used += 4
+    raw = buf.cpu().numpy().view(np.uint8)
+    assert np.all(raw[:, F:off] == 0x5A) and np.all(raw[:, used:] == 0x5A), "bytes outside codes and constants were written"
+    # the same constants in arrays of their own
+    sep = aes.aes_quantize_features(Xd, scheme, ROW)
+    assert torch.equal(sep[1], scale) and (scheme == SYM or torch.equal(sep[2], zero))
+    plan, ref = G.check_plan(rowptr, col, val, n_cols, 16, 0)
+    Y_in = aes.aes_spmm_q8(plan, Xq, scheme, INLINE, None)
+    Y_sep, _, _ = G.check_q8(plan, ref, sep, (rq, rs, rz), scheme, ROW)
+    # symmetric codes: the same operations in the same order wherever the scale comes from.  Affine: where the
+    # lane group takes the constants from its own gather it adds the zero-point terms slot by slot instead of
+    # lane by lane, so the two agree to rounding only; both are held to the oracle.
+    if scheme == SYM:
+        assert torch.equal(Y_in, Y_sep)
+    else:
+        Yref, _ = orc.spmm_q8(ref[0], ref[1], ref[2], rq, scheme, ROW, rs, rz, want_abs=True)
+        mag = (np.abs(rq.astype(np.float32) * rs[:, None]) + np.abs(rz[:, None])).astype(np.float32)
+        Yabs = orc.spmm_plan(ref[0], ref[1], np.abs(ref[2]), np.ascontiguousarray(mag))
+        from helpers import rel_err
+        comp, glob = rel_err(Y_in.cpu().numpy(), Yref, Yabs)
+        assert comp <= G.Q8_TOL and glob <= G.Q8_TOL, (comp, glob)
+        assert float((Y_in - Y_sep).abs().max()) <= 1e-5 * float(Y_sep.abs().max())
+    csr = (G.to_dev(rowptr), G.to_dev(col), G.to_dev(val))
+    assert torch.equal(aes.aes_spmm_fused_q8(*csr, n_cols, 16, Xq, scheme, INLINE, None), Y_in)
+    Theta = G.to_dev((rng.standard_normal((F, 40)) / np.sqrt(F)).astype(np.float32))
+    assert torch.equal(aes.aes_gcn_layer_q8(plan, Xq, scheme, INLINE, None, None, Theta),
+                       aes.aes_gcn_layer_q8(plan, sep[0], scheme, ROW, sep[1], sep[2], Theta))
+    Xhat = aes.aes_dequantize_features(Xq, scheme, INLINE, None)
+    torch.cuda.synchronize()
+    assert np.array_equal(Xhat.cpu().numpy().view(np.uint32), orc.dequantize(rq, scheme, ROW, rs, rz).view(np.uint32))
+    # the unsampled plan: rows of 1436 and 5000 slots, the longer one shared by the workgroup (float64 partial sums)
+    plan0, ref0 = G.check_plan(rowptr, col, val, n_cols, 0, 0)
+    Y0_in = aes.aes_spmm_q8(plan0, Xq, scheme, INLINE, None)
+    Y0_sep, _, _ = G.check_q8(plan0, ref0, sep, (rq, rs, rz), scheme, ROW)
+    assert float((Y0_in - Y0_sep).abs().max()) <= 1e-5 * float(Y0_sep.abs().max())
+    if scheme == SYM:
+        assert torch.equal(Y0_in, Y0_sep)
