@@ -45,12 +45,24 @@ constexpr int kLongRow = 2048;
 //       since such sums run over up to millions of terms) are added in a fixed order
 //       through LDS, so the result stays bit-reproducible.  Without LONG the kernel
 //       has no workgroup barrier at all.
+// Second launch bound: the 8-bit kernels that read a materialised plan are held to 8 wavefronts per SIMD.  Left
+// alone, the unsigned-code variants come out at 66-71 vector registers (7 wavefronts) and the narrow-group
+// variants that take a node's constants from the gather at 73-88 (6); held to 64 they spill nothing, and the
+// latency-bound ragged rows gain from the extra wavefronts: -9 % on the products- and arxiv-shaped graphs with the
+// affine scheme, -13 % with constants from the gather, nothing slower.  The sample-on-the-fly variants (77-110
+// registers, some would spill) and the long-row variants are left to the compiler, except the 32-lane form that
+// takes constants from the gather.
+template <typename Feat, int QMODE, int LPR, bool FUSED, bool LONG>
+constexpr int min_waves_per_simd()
+{
+    constexpr bool kCodes = sizeof(typename Feat::elem_t) == 1;
+    if (kCodes && !FUSED && !LONG) return 8;
+    if (QMODE == kQRowInGather && LPR == 32 && FUSED && !LONG) return 8;
+    return 1;
+}
+
 template <int LPR, int UNROLL, typename Feat, int QMODE, bool FUSED, bool LONG, int NV = 1>
-// (Second launch bound: the narrow-group variants that take a node's constants from the gather would otherwise
-// be compiled to 73-88 vector registers, 6 wavefronts per SIMD; held to 8 wavefronts they need 50-62 and spill
-// nothing, which is worth 13 % on the short rows of the products-shaped graph; the sample-on-the-fly variants
-// with 8 or 16 lanes per row would spill and are left alone.)
-__global__ void __launch_bounds__(kBlock, (QMODE == kQRowInGather && LPR < kWave && !LONG && (!FUSED || LPR == 32)) ? 8 : 1)
+__global__ void __launch_bounds__(kBlock, (min_waves_per_simd<Feat, QMODE, LPR, FUSED, LONG>()))
 spmm_rows_kernel(int64_t n_rows, SlotSource src, const int32_t *__restrict__ row_perm,
                  const typename Feat::elem_t *__restrict__ X, int64_t ldx, int32_t F, QParams qp,
                  float *__restrict__ Y, int64_t ldy)
