@@ -48,6 +48,8 @@ gcn_layer_kernel(int64_t n_rows, SlotSource src, const typename Feat::elem_t *__
     // ---- aggregation: Algorithm 1's accumulation loop, one lane group per row ----
     const int32_t f = lane * 4;
     const bool lane_on = f < F;
+    // With a node's constants taken from the gather itself, the lanes up to those words gather too.
+    const bool gather_on = QMODE == kQRowInGather ? f < qp.inline_off + (QTraits<Feat, QMODE>::kAffine ? 8 : 4) : lane_on;
     for (int rr = wave * kGroups + group; rr < kTileRows; rr += kGroupsPerBlock) {
         const int64_t r = row0 + rr;
         float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
@@ -55,11 +57,11 @@ gcn_layer_kernel(int64_t n_rows, SlotSource src, const typename Feat::elem_t *__
         LaneConstants<Feat, QMODE> k;
         if (r < n_rows) {
             const RowInfo ri = row_info<false>(src, r);
-            accumulate_tiles<LPR, 8, Feat, QMODE, false, float>(src, ri, stage[wave][group], lane, lane_on, X, ldx, f, qp, 0,
-                                                                1, acc, side);
+            accumulate_tiles<LPR, 8, Feat, QMODE, false, float>(src, ri, stage[wave][group], lane, gather_on, X, ldx, f, qp,
+                                                                0, 1, acc, side);
             load_lane_constants<Feat, QMODE>(qp, f, lane_on, r, k);
         }
-        if constexpr (QTraits<Feat, QMODE>::kAffine) side = group_sum<LPR, float>(side);
+        if constexpr (QTraits<Feat, QMODE>::kSideOverLanes) side = group_sum<LPR, float>(side);
         if (lane_on) {
             float y[4] = {0.0f, 0.0f, 0.0f, 0.0f};
             if (r < n_rows) finish_values<Feat, QMODE, float>(acc, side, k, y);
@@ -183,6 +185,16 @@ int dispatch_gcn(const char *what, int64_t n_rows, const SlotSource &src, const 
         case 32: return launch_gcn<32, Feat, QMODE>(what, n_rows, src, X, ldx, F, qp, Theta, ldt, Fo, H, ldh, stream);
         default: return launch_gcn<64, Feat, QMODE>(what, n_rows, src, X, ldx, F, qp, Theta, ldt, Fo, H, ldh, stream);
     }
+}
+
+// Lane groups of 32 or 64 only (F > 64).
+template <typename Feat, int QMODE>
+int dispatch_gcn_lanes(const char *what, int64_t n_rows, const SlotSource &src, const typename Feat::elem_t *X, int64_t ldx,
+                       int32_t F, QParams qp, const float *Theta, int64_t ldt, int32_t Fo, float *H, int64_t ldh,
+                       hipStream_t stream)
+{
+    if (F <= 128) return launch_gcn<32, Feat, QMODE>(what, n_rows, src, X, ldx, F, qp, Theta, ldt, Fo, H, ldh, stream);
+    return launch_gcn<64, Feat, QMODE>(what, n_rows, src, X, ldx, F, qp, Theta, ldt, Fo, H, ldh, stream);
 }
 
 // ---- the general form: any F, any row length --------------------------------------------------
@@ -367,8 +379,18 @@ int run_gcn(const char *what, int32_t W, int64_t n_rows, const SlotSource &src, 
             hipStream_t stream)
 {
     const bool long_rows = W == 0 || W > kLongRowLayer;
-    if (F <= kMaxFeatures && F % 4 == 0 && !long_rows)
+    if (F <= kMaxFeatures && F % 4 == 0 && !long_rows) {
+        if constexpr (QMODE == kQRowScale && sizeof(typename Feat::elem_t) == 1) {
+            // Constants inside the rows of codes, within reach of the lane group that gathers the row: taken
+            // from that gather (as in the SpMM; lane groups of 32 and 64, the narrower ones would spill a register);
+            // otherwise loaded when a slot is staged.
+            int lanes = pow2_ceil(ceil_div(F, 4));
+            lanes = lanes < 8 ? 8 : lanes;
+            if (qp.inline_off >= 0 && lanes >= 32 && qp.inline_off + (Feat::kSigned ? 4 : 8) <= lanes * 4)
+                return dispatch_gcn_lanes<Feat, kQRowInGather>(what, n_rows, src, X, ldx, F, qp, Theta, ldt, Fo, H, ldh, stream);
+        }
         return dispatch_gcn<Feat, QMODE>(what, n_rows, src, X, ldx, F, qp, Theta, ldt, Fo, H, ldh, stream);
+    }
     return dispatch_gcn_wide<Feat, QMODE>(what, long_rows, n_rows, src, X, ldx, F, qp, Theta, ldt, Fo, H, ldh, stream);
 }
 
