@@ -126,6 +126,14 @@ def _ld(t: torch.Tensor) -> int:
     return int(t.stride(0)) if t.shape[0] > 1 else max(int(t.shape[1]), 1)
 
 
+def _ldq(Xq: torch.Tensor, granularity: int) -> int:
+    """Leading dimension of a matrix of codes; with the constants inside the rows the view's own row stride
+    counts even for a single row (the constants lie beyond the F columns of the view)."""
+    if granularity == AES_Q_PER_ROW_INLINE:
+        return max(int(Xq.stride(0)), int(Xq.shape[1]), 1)
+    return _ld(Xq)
+
+
 class Plan(NamedTuple):
     """The sampled matrix A_s as written by aes_sample_build (device tensors)."""
     n_rows: int
@@ -303,7 +311,7 @@ def aes_spmm_q8(plan: Plan, Xq, scheme: int, granularity: int, scale, zero=None,
         raise ValueError("Y has the wrong shape")
     perm = plan.row_perm if use_perm else None
     _check(library().aes_spmm_q8(plan.n_rows, plan.n_cols, plan.W, _ptr(plan.s_rowptr), _ptr(plan.s_col), _ptr(plan.s_val),
-                                 _ptr(perm), _ptr(Xq), _ld(Xq), F, int(scheme), int(granularity), _ptr(scale),
+                                 _ptr(perm), _ptr(Xq), _ldq(Xq, granularity), F, int(scheme), int(granularity), _ptr(scale),
                                  _ptr(zero), _ptr(Y), _ld(Y), _stream(stream)))
     return Y
 
@@ -363,7 +371,7 @@ def aes_spmm_fused_q8(rowptr, colidx, val, n_cols: int, W: int, Xq, scheme: int,
     if Y.shape[0] != n_rows or Y.shape[1] != F:
         raise ValueError("Y has the wrong shape")
     _check(library().aes_spmm_fused_q8(n_rows, int(n_cols), _ptr(rowptr), _ptr(colidx), _ptr(val), int(W),
-                                       int(seed) & (2 ** 64 - 1), int(strategy), _ptr(Xq), _ld(Xq), F, int(scheme),
+                                       int(seed) & (2 ** 64 - 1), int(strategy), _ptr(Xq), _ldq(Xq, granularity), F, int(scheme),
                                        int(granularity), _ptr(scale), _ptr(zero), _ptr(Y), _ld(Y),
                                        _stream(stream)))
     return Y
@@ -390,7 +398,7 @@ def aes_dequantize_features(Xq, scheme: int, granularity: int, scale, zero=None,
     X = _dev(X, torch.float32, "X", 2)
     if X.shape != Xq.shape:
         raise ValueError("X has the wrong shape")
-    _check(library().aes_dequantize_features(n, F, _ptr(Xq), _ld(Xq), int(scheme), int(granularity), _ptr(scale),
+    _check(library().aes_dequantize_features(n, F, _ptr(Xq), _ldq(Xq, granularity), int(scheme), int(granularity), _ptr(scale),
                                              _ptr(zero), _ptr(X), _ld(X), _stream(stream)))
     return X
 
@@ -460,7 +468,7 @@ def aes_gcn_layer_q8(plan: Plan, Xq, scheme: int, granularity: int, scale, zero,
     if H.shape[0] != plan.n_rows or H.shape[1] != Fo:
         raise ValueError("H has the wrong shape")
     _check(library().aes_gcn_layer_q8(plan.n_rows, plan.n_cols, plan.W, _ptr(plan.s_rowptr), _ptr(plan.s_col),
-                                      _ptr(plan.s_val), _ptr(Xq), _ld(Xq), F, int(scheme), int(granularity),
+                                      _ptr(plan.s_val), _ptr(Xq), _ldq(Xq, granularity), F, int(scheme), int(granularity),
                                       _ptr(scale), _ptr(zero), _ptr(Theta), _ld(Theta), Fo, _ptr(H), _ld(H),
                                       _stream(stream)))
     return H

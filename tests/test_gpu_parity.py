@@ -757,3 +757,26 @@ def test_constants_inside_the_rows(G, scheme, F):
     assert float((Y0_in - Y0_sep).abs().max()) <= 1e-5 * float(Y0_sep.abs().max())
     if scheme == SYM:
         assert torch.equal(Y0_in, Y0_sep)
+
+
+def test_constants_inside_the_rows_single_node(G):
+    """One feature row only (the row stride of a one-row matrix is not visible in its shape), and an empty matrix."""
+    import paper_2503_18427_amd as aes
+    INLINE = aes.AES_Q_PER_ROW_INLINE
+    rng = np.random.default_rng(5)
+    X = G.to_dev(rng.standard_normal((1, 100)).astype(np.float32))
+    rowptr = np.array([0, 3, 3, 4], dtype=np.int64)
+    col = np.zeros(4, dtype=np.int32)
+    val = rng.standard_normal(4).astype(np.float32)
+    plan = aes.aes_sample_build(G.to_dev(rowptr), G.to_dev(col), G.to_dev(val), 1, 8, 0)
+    for scheme in (SYM, AFF):
+        sep = aes.aes_quantize_features(X, scheme, ROW)
+        inl = aes.aes_quantize_features(X, scheme, INLINE)
+        assert torch.equal(inl[0], sep[0]) and torch.equal(inl[1], sep[1])
+        Y_sep = aes.aes_spmm_q8(plan, sep[0], scheme, ROW, sep[1], sep[2])
+        Y_in = aes.aes_spmm_q8(plan, inl[0], scheme, INLINE, None)
+        assert float((Y_in - Y_sep).abs().max()) <= 1e-6 * float(Y_sep.abs().max())
+        assert torch.equal(aes.aes_dequantize_features(inl[0], scheme, INLINE, None),
+                           aes.aes_dequantize_features(sep[0], scheme, ROW, sep[1], sep[2]))
+    empty = aes.aes_quantize_features(torch.empty((0, 100), device="cuda"), SYM, INLINE)
+    assert empty[0].shape == (0, 100)
